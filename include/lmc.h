@@ -1,0 +1,261 @@
+/*
+ * lmc.h -- C ABI of liblmc: batched movement of KV cache between an inference
+ * engine's paged GPU memory and contiguous fixed-size token chunks in pinned host
+ * memory, for AMD MI355X (gfx950).
+ *
+ * The operations are the ones the paper describes for its KV caching layer:
+ *   - section 5.1 "Configurable Chunk Size": pages of many layers are grouped into
+ *     chunks (default 256 tokens); on store a kernel copies the scattered pages into
+ *     a contiguous streaming GPU buffer that is then moved to CPU memory as one
+ *     transfer per chunk; on load the chunk is moved back into the buffer and a
+ *     kernel splits it into pages;
+ *   - section 4 "Store" / "Retrieve": a token processor decides which tokens are new
+ *     (only those are stored) and how many leading tokens of a prompt are already
+ *     present (only those are loaded); a storage manager keeps the CPU addresses;
+ *   - section 1 (#1) and 5.2: store and load are batched and pipelined so that the
+ *     copy kernels overlap the transfers;
+ *   - section 7, Table 3: lookup / pin / unpin / clear, here in their local,
+ *     single-instance form.
+ *
+ * Conventions
+ *   - Every function returns an lmc_status_t; nothing throws or aborts.  A NULL
+ *     pointer where one is required gives LMC_ERR_INVAL.
+ *   - "DEVICE" pointers are HIP device addresses on the context's GPU; "HOST" pointers
+ *     are ordinary process memory.  The library never takes ownership of a caller's
+ *     buffer.  No torch or C++ type crosses this boundary.
+ *   - Paged KV memory is described by lmc_kv_geom_t: one allocation per layer, and in
+ *     it the run of head_dim*elem_bytes bytes of (plane p, block b, in-block token o,
+ *     head h) starts at
+ *         kv_layers[l] + p*plane_stride + b*block_stride + o*token_stride + h*head_stride.
+ *     kv_layers is a HOST array of num_layers DEVICE pointers; it is read during the
+ *     call only.  The pages themselves and the slot mapping must stay alive and
+ *     unmodified (store) / unread (retrieve) until lmc_wait returns for the ticket.
+ *   - A chunk is chunk_tokens tokens over all layers and planes, laid out
+ *     [layer][plane][token][head][dim], dense; lmc_chunk_bytes() bytes.
+ *   - A slot mapping is a DEVICE array of int64, one entry per token:
+ *     slot = block*block_size + in-block offset.  A negative slot means the token has
+ *     no page: store writes zeros for it into the chunk, retrieve writes nothing for
+ *     it.  A slot >= num_blocks*block_size is never dereferenced; it is reported as
+ *     LMC_ERR_BADSLOT (see lmc_wait and LMC_FLAG_VALIDATE_SLOTS).  Two tokens of one
+ *     retrieve call that name the same slot leave that slot's content unspecified.
+ *   - A chunk id is a 64-bit value, normally from lmc_hash_chunks.  Equal ids mean
+ *     the same chunk.
+ *   - One context may be used from several threads; calls are serialised inside.
+ */
+#ifndef LMC_H
+#define LMC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lmc_ctx lmc_ctx_t; /* opaque, owned by the library */
+typedef int32_t lmc_status_t;
+
+enum {
+    LMC_OK = 0,
+    LMC_ERR_INVAL = -1,    /* bad argument or geometry */
+    LMC_ERR_NOMEM = -2,    /* host pool full, or an allocation failed */
+    LMC_ERR_MISS = -3,     /* a chunk id is not in the pool */
+    LMC_ERR_BADSLOT = -4,  /* a slot >= num_blocks*block_size */
+    LMC_ERR_HIP = -5,      /* a HIP call failed; lmc_last_hip_error() has its code */
+    LMC_ERR_BUSY = -6,     /* chunk pinned or in flight */
+    LMC_ERR_NODEVICE = -7  /* data-movement call on an index-only context */
+};
+
+#define LMC_MAX_LAYERS 160        /* kv_layers travels as a kernel argument */
+#define LMC_DEVICE_NONE (-1)      /* index-only context: see lmc_create */
+
+/* lmc_config_t.flags */
+#define LMC_FLAG_VALIDATE_SLOTS 1u /* check every slot mapping on the device before any
+                                      byte moves; a bad slot then fails the call itself
+                                      with LMC_ERR_BADSLOT and nothing is written.  Costs
+                                      one small kernel and a host wait per call. */
+#define LMC_FLAG_FORCE_SYNC 2u     /* wait for the device after every enqueue step: the
+                                      pipeline runs serially.  Same results, for debugging. */
+#define LMC_FLAG_POISON_STAGING 4u /* overwrite a staging buffer with 0xA5 as soon as the
+                                      pipeline releases it: a reuse that came too early
+                                      then shows as corrupt data.  For tests. */
+#define LMC_FLAG_TIMING 8u         /* bracket every gather / scatter launch with HIP events
+                                      on its own stream; durations appear in lmc_stats_t. */
+
+/* Geometry of the engine's paged KV memory (section 5: a page is block_size tokens of
+ * one layer) and the chunk length (section 5.1).  All strides are in bytes. */
+typedef struct {
+    int32_t num_layers;   /* 1 .. LMC_MAX_LAYERS */
+    int32_t num_planes;   /* 2 = K and V, 1 = a single latent (MLA) */
+    int32_t num_heads;
+    int32_t head_dim;     /* elements */
+    int32_t elem_bytes;   /* 2 = bf16 / fp16, 1 = fp8; payload is opaque bytes */
+    int32_t block_size;   /* tokens per page */
+    int32_t num_blocks;   /* pages per layer and plane; num_blocks*block_size < 2^31 */
+    int32_t chunk_tokens; /* 256 by default in the paper */
+    int64_t plane_stride, block_stride, token_stride, head_stride; /* >= 0 */
+} lmc_kv_geom_t;
+/* Each layer's allocation must cover every run the strides can reach:
+ *   (P-1)*plane_stride + (NB-1)*block_stride + (BS-1)*token_stride + (H-1)*head_stride
+ *   + head_dim*elem_bytes bytes.
+ * The kernels move min(16, largest power of two dividing head_dim*elem_bytes and every
+ * stride) bytes per lane; the layer base pointers and staging_dev must be aligned to
+ * that, else LMC_ERR_INVAL.  16-byte multiples everywhere give the fast path. */
+
+typedef struct {
+    lmc_kv_geom_t geom;
+    uint64_t host_pool_bytes; /* pinned pool; holds host_pool_bytes / chunk_bytes chunks */
+    int32_t num_staging;      /* staging buffers per direction, >= 2 (double buffering) */
+    int32_t staging_chunks;   /* chunks per staging buffer, >= 1: one kernel launch covers
+                                 up to this many chunks */
+    int32_t device;           /* HIP device ordinal, or LMC_DEVICE_NONE */
+    uint32_t flags;           /* LMC_FLAG_* */
+    uint64_t hash_seed;       /* "hash before the first chunk" of lmc_hash_chunks */
+} lmc_config_t;
+
+typedef struct {
+    uint64_t pool_slots_total, pool_slots_used;
+    uint64_t chunks_stored;       /* written by lmc_store / lmc_put_host */
+    uint64_t chunks_skipped_dup;  /* offered to lmc_store but already present */
+    uint64_t chunks_retrieved;
+    uint64_t retrieve_misses;     /* calls refused with LMC_ERR_MISS */
+    uint64_t alloc_failures;      /* calls that hit LMC_ERR_NOMEM */
+    uint64_t bytes_gathered, bytes_scattered; /* chunk payload through the kernels */
+    uint64_t bytes_d2h, bytes_h2d;            /* chunk payload over the host link */
+    uint64_t gather_launches, scatter_launches;
+    uint64_t timed_gather_launches, timed_scatter_launches; /* LMC_FLAG_TIMING, completed */
+    double gather_ms, scatter_ms;             /* sum of their HIP-event durations */
+} lmc_stats_t;
+
+/* Create a context: allocates the pinned host pool, 2*num_staging device staging
+ * buffers of staging_chunks chunks each (one ring per direction), four HIP streams
+ * and the index.  With device == LMC_DEVICE_NONE nothing touches HIP: the pool is
+ * ordinary host memory and only the host-side calls work (hashing, lookup, put/get,
+ * pin/unpin/clear, stats); every call that would move data to or from a GPU returns
+ * LMC_ERR_NODEVICE.  There is no CPU implementation of the data path.
+ * Errors: LMC_ERR_INVAL (a geometry field out of the ranges given at lmc_kv_geom_t,
+ * num_staging < 2, staging_chunks < 1, pool smaller than one chunk), LMC_ERR_NOMEM,
+ * LMC_ERR_HIP. */
+lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out);
+/* Waits for outstanding work, then frees everything the context owns. */
+lmc_status_t lmc_destroy(lmc_ctx_t *ctx);
+
+int64_t lmc_chunk_bytes(const lmc_ctx_t *ctx); /* chunk_tokens*layers*planes*heads*dim*elem */
+int64_t lmc_pool_slots(const lmc_ctx_t *ctx);
+
+/* Token processor (section 4): chained 64-bit ids of the full chunks of a token
+ * sequence.  id_i = FNV-1a-64( LE64(id_{i-1}) || LE32(tok[i*CT]) .. LE32(tok[i*CT+CT-1]) ),
+ * id_{-1} = hash_seed; a tail shorter than chunk_tokens is ignored.  tokens: HOST
+ * int32[n_tokens]; ids_out: HOST, room for n_tokens / chunk_tokens values;
+ * n_chunks_out: HOST, receives that count. */
+lmc_status_t lmc_hash_chunks(const lmc_ctx_t *ctx, const int32_t *tokens, int64_t n_tokens,
+                             uint64_t *ids_out, int64_t *n_chunks_out);
+
+/* Prefix match (section 4 "Retrieve"): n_hit_out receives the number of leading ids
+ * that are all present.  A later isolated hit does not count.  HOST pointers. */
+lmc_status_t lmc_lookup(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n,
+                        int64_t *n_hit_out);
+
+/* Store (sections 4 and 5.1).  For each of the n_chunks chunks in order: if its id is
+ * present it is skipped (first writer wins); otherwise it takes the lowest free pool
+ * slot, is gathered from the pages into a staging buffer and copied to that slot.
+ * slot_mapping: DEVICE int64[n_chunks*chunk_tokens].  chunk_ids: HOST.
+ * stream_to_wait_on: a hipStream_t (NULL names the null stream): the library's work is
+ * ordered after everything enqueued on it so far (the kernels that produced the KV and
+ * the slot mapping).
+ * The call only enqueues; *ticket_out (HOST, may be NULL) names the work for lmc_wait.
+ * A stored chunk is visible to lmc_lookup at once; a retrieve of it is ordered after
+ * the store on the device.
+ * Errors: LMC_ERR_NOMEM when the pool fills: chunks before the failing one are stored
+ * and their work is still covered by the ticket.  LMC_ERR_BADSLOT under
+ * LMC_FLAG_VALIDATE_SLOTS (nothing stored).  LMC_ERR_NODEVICE, LMC_ERR_HIP. */
+lmc_status_t lmc_store(lmc_ctx_t *ctx, void *const *kv_layers, const int64_t *slot_mapping,
+                       const uint64_t *chunk_ids, int64_t n_chunks, void *stream_to_wait_on,
+                       uint64_t *ticket_out);
+
+/* Retrieve (sections 4 and 5.1).  All n_chunks ids must be present, else LMC_ERR_MISS
+ * and no page byte is written.  Each chunk is copied from its pool slot into a staging
+ * buffer and scattered into the pages named by slot_mapping (DEVICE
+ * int64[n_chunks*chunk_tokens]); bytes of the pages that no slot names are not
+ * touched.  stream_to_signal: a hipStream_t (NULL names the null stream).  The scatter
+ * is ordered after everything enqueued on it so far (earlier users of the pages, the
+ * producer of the slot mapping), and the stream is made to wait for the last scatter,
+ * so work enqueued on it afterwards sees the pages.  Enqueue only. */
+lmc_status_t lmc_retrieve(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n_chunks,
+                          const int64_t *slot_mapping, void *const *kv_layers,
+                          void *stream_to_signal, uint64_t *ticket_out);
+
+/* Retrieve for many requests in one call.  Request r owns chunks
+ * [req_chunk_offsets[r], req_chunk_offsets[r+1]) of chunk_ids and of slot_mapping
+ * (HOST int64[n_req+1], starting at 0, non-decreasing).  One missing chunk anywhere
+ * gives LMC_ERR_MISS and nothing is written.  Kernel launches span request borders. */
+lmc_status_t lmc_retrieve_batch(lmc_ctx_t *ctx, int64_t n_req, const int64_t *req_chunk_offsets,
+                                const uint64_t *chunk_ids, const int64_t *slot_mapping,
+                                void *const *kv_layers, void *stream_to_signal,
+                                uint64_t *ticket_out);
+
+/* Block until the work of `ticket` (and of every earlier ticket) has finished on the
+ * device; ticket 0 means everything enqueued so far.  Returns LMC_ERR_BADSLOT if a
+ * kernel since the last lmc_wait met a slot >= num_blocks*block_size (that token was
+ * skipped, the rest of the call was carried out), LMC_ERR_HIP on a device error. */
+lmc_status_t lmc_wait(lmc_ctx_t *ctx, uint64_t ticket);
+
+/* The two kernels alone, for unit parity and for measuring them against HBM
+ * bandwidth: pages -> n_chunks contiguous chunks at staging_dev (DEVICE,
+ * n_chunks*chunk_bytes, 16-byte aligned) and back.  Enqueued on `stream`
+ * (hipStream_t, NULL = the null stream); no host wait except under
+ * LMC_FLAG_VALIDATE_SLOTS.  A bad slot is reported by the next lmc_wait. */
+lmc_status_t lmc_gather(lmc_ctx_t *ctx, void *const *kv_layers, const int64_t *slot_mapping,
+                        int64_t n_chunks, void *staging_dev, void *stream);
+lmc_status_t lmc_scatter(lmc_ctx_t *ctx, const void *staging_dev, const int64_t *slot_mapping,
+                         int64_t n_chunks, void *const *kv_layers, void *stream);
+
+/* Chunks that arrive from, or leave to, host memory without touching the GPU (a lower
+ * storage tier, section 5.1 "Parallel Store/load Operations").  lmc_put_host stores n
+ * chunks of lmc_chunk_bytes() each, read back to back from host_src, under the same
+ * rules as lmc_store (present ids skipped, lowest free slot, LMC_ERR_NOMEM keeps what
+ * was stored).  lmc_get_host copies one chunk to host_dst after waiting for a store of
+ * it that is still in flight.  lmc_find_slot reports the pool slot of an id. */
+lmc_status_t lmc_put_host(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n,
+                          const void *host_src);
+lmc_status_t lmc_get_host(lmc_ctx_t *ctx, uint64_t chunk_id, void *host_dst);
+lmc_status_t lmc_find_slot(lmc_ctx_t *ctx, uint64_t chunk_id, int64_t *slot_out);
+
+/* Local forms of the controller verbs of section 7, Table 3.  HOST pointers.
+ * pin: every id must be present (else LMC_ERR_MISS, nothing pinned); adds one pin each.
+ * unpin: every id present (else LMC_ERR_MISS) and pinned often enough (else
+ *        LMC_ERR_INVAL); on error nothing changes.
+ * clear: removes the ids that are present and frees their slots; absent ids are
+ *        ignored; if one is pinned or still in flight the call fails with LMC_ERR_BUSY
+ *        and removes nothing. */
+lmc_status_t lmc_pin(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n);
+lmc_status_t lmc_unpin(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n);
+lmc_status_t lmc_clear(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n);
+
+lmc_status_t lmc_get_stats(lmc_ctx_t *ctx, lmc_stats_t *out);
+lmc_status_t lmc_reset_stats(lmc_ctx_t *ctx);
+
+/* Measurement aids (section 8.6 compares achieved loading bandwidth).
+ * lmc_measure_link: best-of-reps hipMemcpyAsync rate between the context's pinned pool
+ * and a device buffer, per direction, in GB/s (1e9 bytes/s), for transfers of nbytes
+ * (<= pool size).  Blocks.  Pool content is preserved.
+ * lmc_copy: a plain device-to-device copy kernel (DEVICE pointers, 16-byte aligned,
+ * nbytes a multiple of 16) enqueued on `stream`: the streaming-copy ceiling the
+ * gather / scatter kernels are compared with, and the known-size kernel that hardware
+ * counters are calibrated on. */
+lmc_status_t lmc_measure_link(lmc_ctx_t *ctx, uint64_t nbytes, int32_t reps,
+                              double *h2d_gbps_out, double *d2h_gbps_out);
+lmc_status_t lmc_copy(lmc_ctx_t *ctx, void *dst_dev, const void *src_dev, uint64_t nbytes,
+                      void *stream);
+
+/* Launch-shape knobs for experiments; defaults are chosen per geometry at lmc_create.
+ * Keys: "lp_per_block" (layer-planes walked by one workgroup), "nt_load", "nt_store"
+ * (0/1: non-temporal hints).  Unknown key or out-of-range value: LMC_ERR_INVAL. */
+lmc_status_t lmc_tune(lmc_ctx_t *ctx, const char *key, int64_t value);
+
+const char *lmc_strerror(lmc_status_t status);
+int32_t lmc_last_hip_error(const lmc_ctx_t *ctx); /* hipError_t of the last LMC_ERR_HIP */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LMC_H */

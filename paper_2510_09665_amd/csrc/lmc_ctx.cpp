@@ -1,0 +1,900 @@
+// liblmc context, pipelines and C ABI (see include/lmc.h for the contract).
+//
+// Store  (paper sections 4 and 5.1): index probe -> per group of new chunks
+//        gather kernel (stream G) -> event -> hipMemcpyAsync D2H into pool slots
+//        (stream D) -> event that releases the staging buffer.
+// Retrieve: hipMemcpyAsync H2D of the hit chunks (stream H) -> event -> scatter kernel
+//        (stream S) -> event that releases the staging buffer.
+// Each direction owns a ring of num_staging buffers, so the kernel of group k+1 runs
+// while the copy of group k is on the link (section 1 (#1): storing and loading are
+// batched and pipelined).  The host never waits inside store / retrieve; control
+// crosses to the device once per group and direction, not once per page, which is
+// the paper's argument for chunk-granular transfers (section 8.6, Table 5).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <deque>
+#include <mutex>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/lmc.h"
+#include "lmc_index.hpp"
+#include "lmc_kernels.hpp"
+
+namespace {
+
+struct Ring {
+    std::vector<uint8_t *> buf;
+    std::vector<hipEvent_t> filled, drained;
+    std::vector<char> used;
+    uint64_t pos = 0;
+};
+
+struct Op {
+    uint64_t ticket = 0;
+    hipEvent_t done = nullptr;       // null: nothing was enqueued for this ticket
+    std::vector<int64_t> slots;      // pool slots whose in-flight count this op holds
+    bool is_store = false;
+};
+
+struct Timing {
+    hipEvent_t start, stop;
+    bool is_gather;
+};
+
+}  // namespace
+
+struct lmc_ctx {
+    lmc_config_t cfg{};
+    lmc::KernelGeom kg{};
+    lmc::LaunchShape shape{};
+    uint32_t tune_lp_per_block = 0;  // 0 = choose per launch
+    uint32_t target_blocks = 4096;
+    int64_t chunk_bytes = 0;
+    int64_t n_pool_slots = 0;
+    uint8_t *pool = nullptr;
+    bool has_device = false;
+    lmc::ChunkIndex index;
+    std::mutex mu;
+    hipStream_t s_gather = nullptr, s_d2h = nullptr, s_h2d = nullptr, s_scatter = nullptr;
+    Ring store_ring, load_ring;
+    int32_t *bad_flag_host = nullptr, *bad_flag_dev = nullptr;
+    std::deque<Op> ops;
+    std::deque<Timing> timings;
+    uint64_t next_ticket = 1, completed_ticket = 0;
+    std::vector<hipEvent_t> free_sync_events, free_time_events, all_events;
+    lmc_stats_t stats{};
+    int32_t last_hip_error = 0;
+};
+
+namespace {
+
+#define HIPCHK(ctx, expr)                                  \
+    do {                                                   \
+        hipError_t e_ = (expr);                            \
+        if (e_ != hipSuccess) {                            \
+            (ctx)->last_hip_error = int32_t(e_);           \
+            return LMC_ERR_HIP;                            \
+        }                                                  \
+    } while (0)
+
+// Makes the context's device current for the scope of one API call.
+class DeviceScope {
+public:
+    explicit DeviceScope(const lmc_ctx *c) {
+        if (c->has_device && hipGetDevice(&prev_) == hipSuccess && prev_ != c->cfg.device) {
+            if (hipSetDevice(c->cfg.device) == hipSuccess) restore_ = true;
+        }
+    }
+    ~DeviceScope() {
+        if (restore_) (void)hipSetDevice(prev_);
+    }
+
+private:
+    int prev_ = 0;
+    bool restore_ = false;
+};
+
+lmc_status_t get_event(lmc_ctx *c, bool timing, hipEvent_t *out) {
+    std::vector<hipEvent_t> &pool = timing ? c->free_time_events : c->free_sync_events;
+    if (!pool.empty()) {
+        *out = pool.back();
+        pool.pop_back();
+        return LMC_OK;
+    }
+    hipEvent_t e;
+    HIPCHK(c, hipEventCreateWithFlags(&e, timing ? hipEventDefault : hipEventDisableTiming));
+    c->all_events.push_back(e);
+    *out = e;
+    return LMC_OK;
+}
+
+int64_t gcd_pow2(int64_t a, int64_t cap) {
+    int64_t v = cap;
+    while (v > 1 && (a % v) != 0) v >>= 1;
+    return v;
+}
+
+// Fill KernelGeom from the public geometry; LMC_ERR_INVAL if it cannot be expressed.
+lmc_status_t derive_geometry(const lmc_kv_geom_t &g, lmc::KernelGeom *k, int64_t *chunk_bytes) {
+    if (g.num_layers < 1 || g.num_layers > LMC_MAX_LAYERS || g.num_planes < 1 ||
+        g.num_layers * int64_t(g.num_planes) > lmc::kMaxLayerPlanes || g.num_heads < 1 ||
+        g.head_dim < 1 || g.elem_bytes < 1 || g.block_size < 1 || g.num_blocks < 1 ||
+        g.chunk_tokens < 1)
+        return LMC_ERR_INVAL;
+    if (g.plane_stride < 0 || g.block_stride < 0 || g.token_stride < 0 || g.head_stride < 0)
+        return LMC_ERR_INVAL;
+    const int64_t n_slots = int64_t(g.num_blocks) * g.block_size;
+    if (n_slots >= (int64_t(1) << 31)) return LMC_ERR_INVAL;
+    const int64_t run = int64_t(g.head_dim) * g.elem_bytes;
+    const int64_t row = run * g.num_heads;
+    if (run >= (int64_t(1) << 31) || row >= (int64_t(1) << 31)) return LMC_ERR_INVAL;
+    const bool row_contiguous = (g.num_heads == 1) || (g.head_stride == run);
+    int64_t vec = gcd_pow2(run, 16);
+    vec = gcd_pow2(g.plane_stride, vec);
+    vec = gcd_pow2(g.block_stride, vec);
+    vec = gcd_pow2(g.token_stride, vec);
+    if (!row_contiguous) vec = gcd_pow2(g.head_stride, vec);
+    const int64_t pairs = int64_t(g.chunk_tokens) * (row / vec);
+    if (pairs >= (int64_t(1) << 31)) return LMC_ERR_INVAL;
+
+    k->block_stride = g.block_stride;
+    k->token_stride = g.token_stride;
+    k->run_stride = row_contiguous ? 0 : g.head_stride;
+    k->row_stride_lp = uint64_t(g.chunk_tokens) * uint64_t(row);
+    k->chunk_bytes = k->row_stride_lp * uint64_t(g.num_layers) * uint64_t(g.num_planes);
+    k->n_slots = uint32_t(n_slots);
+    k->block_size = uint32_t(g.block_size);
+    k->block_shift = -1;
+    for (int sh = 0; sh < 31; sh++)
+        if ((int64_t(1) << sh) == g.block_size) k->block_shift = sh;
+    k->chunk_tokens = uint32_t(g.chunk_tokens);
+    k->runs_per_row = row_contiguous ? 1u : uint32_t(g.num_heads);
+    k->vec_per_run = uint32_t((row_contiguous ? row : run) / vec);
+    k->vec_per_row = uint32_t(row / vec);
+    k->pairs_per_chunk = uint32_t(pairs);
+    k->n_layer_planes = uint32_t(g.num_layers * g.num_planes);
+    k->vec = uint32_t(vec);
+    *chunk_bytes = int64_t(k->chunk_bytes);
+    return LMC_OK;
+}
+
+lmc_status_t build_layer_ptrs(const lmc_ctx *c, void *const *kv_layers, lmc::LayerPtrs *out) {
+    const lmc_kv_geom_t &g = c->cfg.geom;
+    for (int l = 0; l < g.num_layers; l++) {
+        uint8_t *base = static_cast<uint8_t *>(kv_layers[l]);
+        if (base == nullptr || (reinterpret_cast<uintptr_t>(base) % c->kg.vec) != 0)
+            return LMC_ERR_INVAL;
+        for (int p = 0; p < g.num_planes; p++)
+            out->p[l * g.num_planes + p] = base + int64_t(p) * g.plane_stride;
+    }
+    return LMC_OK;
+}
+
+lmc::LaunchShape shape_for(const lmc_ctx *c, uint32_t n_chunks) {
+    lmc::LaunchShape s = c->shape;
+    const uint32_t lp = c->kg.n_layer_planes;
+    if (c->tune_lp_per_block > 0) {
+        s.lp_per_block = std::min(c->tune_lp_per_block, lp);
+        return s;
+    }
+    // enough workgroups to fill 256 CUs several times over, but never fewer than one
+    // unrolled step (8 layer-planes) per workgroup
+    const uint64_t xb = (uint64_t(n_chunks) * c->kg.pairs_per_chunk + 255) / 256;
+    uint64_t groups = (c->target_blocks + xb - 1) / std::max<uint64_t>(xb, 1);
+    groups = std::max<uint64_t>(1, std::min<uint64_t>(groups, (lp + 7) / 8));
+    uint32_t per = uint32_t((lp + groups - 1) / groups);
+    per = (per + 7) / 8 * 8;
+    s.lp_per_block = std::min(per, lp);
+    return s;
+}
+
+// Finish every operation whose last device step has completed: drop its in-flight
+// counts, collect kernel timings, recycle events.
+void reap(lmc_ctx *c) {
+    while (!c->ops.empty()) {
+        Op &op = c->ops.front();
+        if (op.done != nullptr) {
+            if (hipEventQuery(op.done) != hipSuccess) break;
+            c->free_sync_events.push_back(op.done);
+        }
+        for (int64_t s : op.slots) {
+            lmc::SlotMeta &m = c->index.meta(s);
+            m.inflight--;
+            if (m.ready_ticket == op.ticket) m.ready_ticket = 0;
+        }
+        c->completed_ticket = op.ticket;
+        c->ops.pop_front();
+    }
+    for (size_t i = 0; i < c->timings.size();) {
+        Timing &t = c->timings[i];
+        if (hipEventQuery(t.stop) == hipSuccess) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) {
+                if (t.is_gather) {
+                    c->stats.gather_ms += ms;
+                    c->stats.timed_gather_launches++;
+                } else {
+                    c->stats.scatter_ms += ms;
+                    c->stats.timed_scatter_launches++;
+                }
+            }
+            c->free_time_events.push_back(t.start);
+            c->free_time_events.push_back(t.stop);
+            c->timings.erase(c->timings.begin() + long(i));
+        } else {
+            i++;
+        }
+    }
+}
+
+// Orders `waiter` after everything enqueued so far on `stream`.
+lmc_status_t order_after(lmc_ctx *c, hipStream_t waiter, hipStream_t stream) {
+    hipEvent_t e;
+    lmc_status_t rc = get_event(c, false, &e);
+    if (rc != LMC_OK) return rc;
+    HIPCHK(c, hipEventRecord(e, stream));
+    HIPCHK(c, hipStreamWaitEvent(waiter, e, 0));
+    // the event can be reused once recorded again: waits already enqueued keep the
+    // record they saw
+    c->free_sync_events.push_back(e);
+    return LMC_OK;
+}
+
+// LMC_FLAG_VALIDATE_SLOTS: device-side range check with a host wait.
+lmc_status_t validate_slots(lmc_ctx *c, const int64_t *slot_mapping, int64_t n_tokens,
+                            hipStream_t stream) {
+    if (!(c->cfg.flags & LMC_FLAG_VALIDATE_SLOTS) || n_tokens == 0) return LMC_OK;
+    HIPCHK(c, hipStreamSynchronize(stream));
+    const int32_t before = *c->bad_flag_host;
+    *c->bad_flag_host = 0;
+    HIPCHK(c, lmc::launch_check_slots(slot_mapping, uint64_t(n_tokens), c->kg.n_slots,
+                                      c->bad_flag_dev, stream));
+    HIPCHK(c, hipStreamSynchronize(stream));
+    const bool bad = *c->bad_flag_host != 0;
+    *c->bad_flag_host = before;
+    return bad ? LMC_ERR_BADSLOT : LMC_OK;
+}
+
+lmc_status_t timed_launch(lmc_ctx *c, bool gather, const lmc::LayerPtrs &ptrs,
+                          const int64_t *slots, uint32_t n_chunks, uint8_t *staging,
+                          hipStream_t stream) {
+    const bool timing = (c->cfg.flags & LMC_FLAG_TIMING) != 0;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (timing) {
+        lmc_status_t rc = get_event(c, true, &e0);
+        if (rc == LMC_OK) rc = get_event(c, true, &e1);
+        if (rc != LMC_OK) return rc;
+        HIPCHK(c, hipEventRecord(e0, stream));
+    }
+    const lmc::LaunchShape s = shape_for(c, n_chunks);
+    if (gather) {
+        HIPCHK(c, lmc::launch_gather(c->kg, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream));
+        c->stats.gather_launches++;
+        c->stats.bytes_gathered += uint64_t(n_chunks) * uint64_t(c->chunk_bytes);
+    } else {
+        HIPCHK(c, lmc::launch_scatter(c->kg, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream));
+        c->stats.scatter_launches++;
+        c->stats.bytes_scattered += uint64_t(n_chunks) * uint64_t(c->chunk_bytes);
+    }
+    if (timing) {
+        HIPCHK(c, hipEventRecord(e1, stream));
+        c->timings.push_back(Timing{e0, e1, gather});
+    }
+    return LMC_OK;
+}
+
+lmc_status_t force_sync(lmc_ctx *c, hipStream_t s) {
+    if (c->cfg.flags & LMC_FLAG_FORCE_SYNC) HIPCHK(c, hipStreamSynchronize(s));
+    return LMC_OK;
+}
+
+// Copies between staging and pool, one hipMemcpyAsync per run of consecutive pool slots.
+lmc_status_t copy_group(lmc_ctx *c, bool to_host, uint8_t *staging, const int64_t *pool_slots,
+                        int64_t k, hipStream_t stream) {
+    const int64_t cb = c->chunk_bytes;
+    for (int64_t j = 0; j < k;) {
+        int64_t m = 1;
+        while (j + m < k && pool_slots[j + m] == pool_slots[j] + m) m++;
+        uint8_t *host = c->pool + pool_slots[j] * cb;
+        uint8_t *dev = staging + j * cb;
+        if (to_host) {
+            HIPCHK(c, hipMemcpyAsync(host, dev, size_t(m * cb), hipMemcpyDeviceToHost, stream));
+            c->stats.bytes_d2h += uint64_t(m * cb);
+        } else {
+            HIPCHK(c, hipMemcpyAsync(dev, host, size_t(m * cb), hipMemcpyHostToDevice, stream));
+            c->stats.bytes_h2d += uint64_t(m * cb);
+        }
+        j += m;
+    }
+    return LMC_OK;
+}
+
+lmc_status_t finish_op(lmc_ctx *c, Op &&op, hipStream_t last_stream, bool enqueued,
+                       uint64_t *ticket_out) {
+    if (enqueued) {
+        lmc_status_t rc = get_event(c, false, &op.done);
+        if (rc != LMC_OK) return rc;
+        HIPCHK(c, hipEventRecord(op.done, last_stream));
+    }
+    if (ticket_out) *ticket_out = op.ticket;
+    c->ops.push_back(std::move(op));
+    return LMC_OK;
+}
+
+lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
+                         const int64_t *slot_mapping, void *const *kv_layers, void *user_stream,
+                         uint64_t *ticket_out) {
+    if (!c->has_device) return LMC_ERR_NODEVICE;
+    DeviceScope dev(c);
+    reap(c);
+    std::vector<int64_t> pool_slots(size_t(n_chunks), 0);
+    for (int64_t i = 0; i < n_chunks; i++) {
+        pool_slots[size_t(i)] = c->index.find(ids[i]);
+        if (pool_slots[size_t(i)] < 0) {
+            c->stats.retrieve_misses++;
+            return LMC_ERR_MISS;
+        }
+    }
+    lmc::LayerPtrs ptrs;
+    lmc_status_t rc = build_layer_ptrs(c, kv_layers, &ptrs);
+    if (rc != LMC_OK) return rc;
+    hipStream_t user = static_cast<hipStream_t>(user_stream);
+    const int64_t CT = c->cfg.geom.chunk_tokens;
+    // the pages may still be in use, and the slot mapping still be on its way, by work
+    // already on the caller's stream
+    if (n_chunks > 0 && (rc = order_after(c, c->s_scatter, user)) != LMC_OK) return rc;
+    rc = validate_slots(c, slot_mapping, n_chunks * CT, c->s_scatter);
+    if (rc != LMC_OK) return rc;
+
+    Op op;
+    op.ticket = c->next_ticket++;
+    if (n_chunks == 0) return finish_op(c, std::move(op), nullptr, false, ticket_out);
+
+    // a chunk whose store is still on its way to the pool: load after that store
+    uint64_t newest_store = 0;
+    for (int64_t s : pool_slots) newest_store = std::max(newest_store, c->index.meta(s).ready_ticket);
+    if (newest_store > c->completed_ticket)
+        for (const Op &o : c->ops)
+            if (o.ticket == newest_store && o.done != nullptr)
+                HIPCHK(c, hipStreamWaitEvent(c->s_h2d, o.done, 0));
+
+    Ring &ring = c->load_ring;
+    const int64_t per = c->cfg.staging_chunks;
+    for (int64_t i0 = 0; i0 < n_chunks; i0 += per) {
+        const int64_t k = std::min(per, n_chunks - i0);
+        const size_t b = size_t(ring.pos++ % ring.buf.size());
+        if (ring.used[b]) HIPCHK(c, hipStreamWaitEvent(c->s_h2d, ring.drained[b], 0));
+        rc = copy_group(c, false, ring.buf[b], &pool_slots[size_t(i0)], k, c->s_h2d);
+        if (rc != LMC_OK) return rc;
+        HIPCHK(c, hipEventRecord(ring.filled[b], c->s_h2d));
+        if ((rc = force_sync(c, c->s_h2d)) != LMC_OK) return rc;
+        HIPCHK(c, hipStreamWaitEvent(c->s_scatter, ring.filled[b], 0));
+        rc = timed_launch(c, false, ptrs, slot_mapping + i0 * CT, uint32_t(k), ring.buf[b], c->s_scatter);
+        if (rc != LMC_OK) return rc;
+        if (c->cfg.flags & LMC_FLAG_POISON_STAGING)
+            HIPCHK(c, lmc::launch_fill(ring.buf[b], 0xA5, uint64_t(k * c->chunk_bytes), c->s_scatter));
+        HIPCHK(c, hipEventRecord(ring.drained[b], c->s_scatter));
+        ring.used[b] = 1;
+        if ((rc = force_sync(c, c->s_scatter)) != LMC_OK) return rc;
+    }
+    for (int64_t s : pool_slots) c->index.meta(s).inflight++;
+    op.slots = pool_slots;
+    c->stats.chunks_retrieved += uint64_t(n_chunks);
+    rc = finish_op(c, std::move(op), c->s_scatter, true, ticket_out);
+    if (rc != LMC_OK) return rc;
+    HIPCHK(c, hipStreamWaitEvent(user, c->ops.back().done, 0));
+    return LMC_OK;
+}
+
+lmc_status_t free_ring(Ring &r) {
+    for (uint8_t *p : r.buf)
+        if (p) (void)hipFree(p);
+    r.buf.clear();
+    return LMC_OK;
+}
+
+lmc_status_t make_ring(lmc_ctx *c, Ring &r) {
+    const size_t n = size_t(c->cfg.num_staging);
+    const size_t bytes = size_t(c->cfg.staging_chunks) * size_t(c->chunk_bytes);
+    r.buf.assign(n, nullptr);
+    r.filled.assign(n, nullptr);
+    r.drained.assign(n, nullptr);
+    r.used.assign(n, 0);
+    for (size_t i = 0; i < n; i++) {
+        hipError_t e = hipMalloc(reinterpret_cast<void **>(&r.buf[i]), bytes);
+        if (e != hipSuccess) {
+            c->last_hip_error = int32_t(e);
+            return e == hipErrorOutOfMemory ? LMC_ERR_NOMEM : LMC_ERR_HIP;
+        }
+        lmc_status_t rc = get_event(c, false, &r.filled[i]);
+        if (rc == LMC_OK) rc = get_event(c, false, &r.drained[i]);
+        if (rc != LMC_OK) return rc;
+    }
+    return LMC_OK;
+}
+
+void destroy_ctx(lmc_ctx *c) {
+    if (c->has_device) {
+        DeviceScope dev(c);
+        (void)hipDeviceSynchronize();
+        free_ring(c->store_ring);
+        free_ring(c->load_ring);
+        for (hipEvent_t e : c->all_events) (void)hipEventDestroy(e);
+        for (hipStream_t s : {c->s_gather, c->s_d2h, c->s_h2d, c->s_scatter})
+            if (s) (void)hipStreamDestroy(s);
+        if (c->bad_flag_host) (void)hipHostFree(c->bad_flag_host);
+        if (c->pool) (void)hipHostFree(c->pool);
+    } else {
+        std::free(c->pool);
+    }
+    delete c;
+}
+
+}  // namespace
+
+extern "C" {
+
+lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out) {
+    if (!cfg || !ctx_out) return LMC_ERR_INVAL;
+    *ctx_out = nullptr;
+    lmc_ctx *c = new (std::nothrow) lmc_ctx();
+    if (!c) return LMC_ERR_NOMEM;
+    c->cfg = *cfg;
+    lmc_status_t rc = derive_geometry(cfg->geom, &c->kg, &c->chunk_bytes);
+    if (rc == LMC_OK && (cfg->num_staging < 2 || cfg->staging_chunks < 1 ||
+                         (cfg->device < 0 && cfg->device != LMC_DEVICE_NONE)))
+        rc = LMC_ERR_INVAL;
+    if (rc == LMC_OK) {
+        c->n_pool_slots = int64_t(cfg->host_pool_bytes / uint64_t(c->chunk_bytes));
+        if (c->n_pool_slots < 1) rc = LMC_ERR_INVAL;
+    }
+    if (rc != LMC_OK) {
+        delete c;
+        return rc;
+    }
+    c->shape.lp_per_block = 8;
+    c->shape.nt_load = true;
+    c->shape.nt_store = false;
+    c->has_device = cfg->device != LMC_DEVICE_NONE;
+    const size_t pool_bytes = size_t(c->n_pool_slots) * size_t(c->chunk_bytes);
+    if (!c->has_device) {
+        c->pool = static_cast<uint8_t *>(std::aligned_alloc(4096, (pool_bytes + 4095) / 4096 * 4096));
+        if (!c->pool) {
+            delete c;
+            return LMC_ERR_NOMEM;
+        }
+    } else {
+        int n_dev = 0;
+        hipError_t e = hipGetDeviceCount(&n_dev);
+        if (e != hipSuccess || cfg->device >= n_dev) {
+            c->last_hip_error = int32_t(e);
+            delete c;
+            return e != hipSuccess ? LMC_ERR_HIP : LMC_ERR_INVAL;
+        }
+        DeviceScope dev(c);
+        auto fail = [&](lmc_status_t st) {
+            destroy_ctx(c);
+            return st;
+        };
+        e = hipHostMalloc(reinterpret_cast<void **>(&c->pool), pool_bytes, hipHostMallocDefault);
+        if (e != hipSuccess) {
+            c->pool = nullptr;
+            c->last_hip_error = int32_t(e);
+            return fail(LMC_ERR_NOMEM);
+        }
+        e = hipHostMalloc(reinterpret_cast<void **>(&c->bad_flag_host), 64, hipHostMallocMapped);
+        if (e != hipSuccess) {
+            c->bad_flag_host = nullptr;
+            return fail(LMC_ERR_HIP);
+        }
+        *c->bad_flag_host = 0;
+        if (hipHostGetDevicePointer(reinterpret_cast<void **>(&c->bad_flag_dev), c->bad_flag_host, 0) != hipSuccess)
+            return fail(LMC_ERR_HIP);
+        for (hipStream_t *s : {&c->s_gather, &c->s_d2h, &c->s_h2d, &c->s_scatter})
+            if (hipStreamCreateWithFlags(s, hipStreamNonBlocking) != hipSuccess) return fail(LMC_ERR_HIP);
+        if ((rc = make_ring(c, c->store_ring)) != LMC_OK) return fail(rc);
+        if ((rc = make_ring(c, c->load_ring)) != LMC_OK) return fail(rc);
+    }
+    c->index.reset(c->n_pool_slots);
+    c->stats.pool_slots_total = uint64_t(c->n_pool_slots);
+    *ctx_out = c;
+    return LMC_OK;
+}
+
+lmc_status_t lmc_destroy(lmc_ctx_t *c) {
+    if (!c) return LMC_ERR_INVAL;
+    destroy_ctx(c);
+    return LMC_OK;
+}
+
+int64_t lmc_chunk_bytes(const lmc_ctx_t *c) { return c ? c->chunk_bytes : 0; }
+int64_t lmc_pool_slots(const lmc_ctx_t *c) { return c ? c->n_pool_slots : 0; }
+
+lmc_status_t lmc_hash_chunks(const lmc_ctx_t *c, const int32_t *tokens, int64_t n_tokens,
+                             uint64_t *ids_out, int64_t *n_chunks_out) {
+    if (!c || n_tokens < 0 || (n_tokens > 0 && !tokens) || !n_chunks_out) return LMC_ERR_INVAL;
+    const int32_t CT = c->cfg.geom.chunk_tokens;
+    const int64_t n = n_tokens / CT;
+    if (n > 0 && !ids_out) return LMC_ERR_INVAL;
+    uint64_t prev = c->cfg.hash_seed;
+    for (int64_t i = 0; i < n; i++) {
+        prev = lmc::chunk_id(prev, tokens + i * CT, CT);
+        ids_out[i] = prev;
+    }
+    *n_chunks_out = n;
+    return LMC_OK;
+}
+
+lmc_status_t lmc_lookup(lmc_ctx_t *c, const uint64_t *ids, int64_t n, int64_t *n_hit_out) {
+    if (!c || n < 0 || (n > 0 && !ids) || !n_hit_out) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    int64_t k = 0;
+    while (k < n && c->index.find(ids[k]) >= 0) k++;
+    *n_hit_out = k;
+    return LMC_OK;
+}
+
+lmc_status_t lmc_store(lmc_ctx_t *c, void *const *kv_layers, const int64_t *slot_mapping,
+                       const uint64_t *ids, int64_t n_chunks, void *stream_to_wait_on,
+                       uint64_t *ticket_out) {
+    if (!c || n_chunks < 0 || !kv_layers || (n_chunks > 0 && (!slot_mapping || !ids)))
+        return LMC_ERR_INVAL;
+    if (!c->has_device) return LMC_ERR_NODEVICE;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    reap(c);
+    lmc::LayerPtrs ptrs;
+    lmc_status_t rc = build_layer_ptrs(c, kv_layers, &ptrs);
+    if (rc != LMC_OK) return rc;
+    hipStream_t user = static_cast<hipStream_t>(stream_to_wait_on);
+    const int64_t CT = c->cfg.geom.chunk_tokens;
+    if (n_chunks > 0 && (rc = order_after(c, c->s_gather, user)) != LMC_OK) return rc;
+    if ((rc = validate_slots(c, slot_mapping, n_chunks * CT, c->s_gather)) != LMC_OK) return rc;
+
+    Op op;
+    op.ticket = c->next_ticket++;
+    op.is_store = true;
+    // token processor: which chunks are new, and where they go
+    std::vector<int64_t> new_chunk, new_slot;
+    bool nomem = false;
+    for (int64_t i = 0; i < n_chunks; i++) {
+        if (c->index.find(ids[i]) >= 0) {
+            c->stats.chunks_skipped_dup++;
+            continue;
+        }
+        const int64_t s = c->index.insert(ids[i]);
+        if (s < 0) {
+            nomem = true;
+            c->stats.alloc_failures++;
+            break;
+        }
+        lmc::SlotMeta &m = c->index.meta(s);
+        m.inflight = 1;
+        m.ready_ticket = op.ticket;
+        new_chunk.push_back(i);
+        new_slot.push_back(s);
+    }
+    op.slots = new_slot;
+    c->stats.chunks_stored += new_chunk.size();
+
+    Ring &ring = c->store_ring;
+    const size_t per = size_t(c->cfg.staging_chunks);
+    for (size_t j0 = 0; j0 < new_chunk.size();) {
+        // one launch covers chunks that are consecutive in the caller's slot mapping
+        size_t k = 1;
+        while (k < per && j0 + k < new_chunk.size() && new_chunk[j0 + k] == new_chunk[j0] + int64_t(k)) k++;
+        const size_t b = size_t(ring.pos++ % ring.buf.size());
+        if (ring.used[b]) HIPCHK(c, hipStreamWaitEvent(c->s_gather, ring.drained[b], 0));
+        rc = timed_launch(c, true, ptrs, slot_mapping + new_chunk[j0] * CT, uint32_t(k), ring.buf[b], c->s_gather);
+        if (rc != LMC_OK) return rc;
+        HIPCHK(c, hipEventRecord(ring.filled[b], c->s_gather));
+        if ((rc = force_sync(c, c->s_gather)) != LMC_OK) return rc;
+        HIPCHK(c, hipStreamWaitEvent(c->s_d2h, ring.filled[b], 0));
+        rc = copy_group(c, true, ring.buf[b], &new_slot[j0], int64_t(k), c->s_d2h);
+        if (rc != LMC_OK) return rc;
+        if (c->cfg.flags & LMC_FLAG_POISON_STAGING)
+            HIPCHK(c, lmc::launch_fill(ring.buf[b], 0xA5, uint64_t(k) * uint64_t(c->chunk_bytes), c->s_d2h));
+        HIPCHK(c, hipEventRecord(ring.drained[b], c->s_d2h));
+        ring.used[b] = 1;
+        if ((rc = force_sync(c, c->s_d2h)) != LMC_OK) return rc;
+        j0 += k;
+    }
+    rc = finish_op(c, std::move(op), c->s_d2h, !new_chunk.empty(), ticket_out);
+    if (rc != LMC_OK) return rc;
+    return nomem ? LMC_ERR_NOMEM : LMC_OK;
+}
+
+lmc_status_t lmc_retrieve(lmc_ctx_t *c, const uint64_t *ids, int64_t n_chunks,
+                          const int64_t *slot_mapping, void *const *kv_layers,
+                          void *stream_to_signal, uint64_t *ticket_out) {
+    if (!c || n_chunks < 0 || !kv_layers || (n_chunks > 0 && (!slot_mapping || !ids)))
+        return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    return do_retrieve(c, ids, n_chunks, slot_mapping, kv_layers, stream_to_signal, ticket_out);
+}
+
+lmc_status_t lmc_retrieve_batch(lmc_ctx_t *c, int64_t n_req, const int64_t *off,
+                                const uint64_t *ids, const int64_t *slot_mapping,
+                                void *const *kv_layers, void *stream_to_signal,
+                                uint64_t *ticket_out) {
+    if (!c || n_req < 0 || !off || !kv_layers || off[0] != 0) return LMC_ERR_INVAL;
+    for (int64_t r = 0; r < n_req; r++)
+        if (off[r + 1] < off[r]) return LMC_ERR_INVAL;
+    const int64_t total = off[n_req];
+    if (total > 0 && (!ids || !slot_mapping)) return LMC_ERR_INVAL;
+    // The requests' chunks and slot mappings are already back to back, so the batch is
+    // one stream of chunks: kernel launches and copies run across request borders.
+    std::lock_guard<std::mutex> lock(c->mu);
+    return do_retrieve(c, ids, total, slot_mapping, kv_layers, stream_to_signal, ticket_out);
+}
+
+lmc_status_t lmc_wait(lmc_ctx_t *c, uint64_t ticket) {
+    if (!c) return LMC_ERR_INVAL;
+    std::unique_lock<std::mutex> lock(c->mu);
+    if (ticket == 0) ticket = c->next_ticket - 1;
+    if (ticket >= c->next_ticket) return LMC_ERR_INVAL;
+    if (!c->has_device) return LMC_OK;
+    DeviceScope dev(c);
+    hipEvent_t last = nullptr;
+    for (const Op &o : c->ops)
+        if (o.ticket <= ticket && o.done != nullptr) last = o.done;
+    if (last != nullptr) {
+        lock.unlock();
+        hipError_t e = hipEventSynchronize(last);
+        lock.lock();
+        if (e != hipSuccess) {
+            c->last_hip_error = int32_t(e);
+            return LMC_ERR_HIP;
+        }
+    }
+    reap(c);
+    if (*c->bad_flag_host != 0) {
+        *c->bad_flag_host = 0;
+        return LMC_ERR_BADSLOT;
+    }
+    return LMC_OK;
+}
+
+static lmc_status_t device_only(lmc_ctx_t *c, bool gather, void *const *kv_layers,
+                                const int64_t *slot_mapping, int64_t n_chunks, uint8_t *staging,
+                                void *stream) {
+    if (!c || n_chunks < 0 || !kv_layers || (n_chunks > 0 && (!slot_mapping || !staging)))
+        return LMC_ERR_INVAL;
+    if (!c->has_device) return LMC_ERR_NODEVICE;
+    if (reinterpret_cast<uintptr_t>(staging) % c->kg.vec) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    reap(c);
+    lmc::LayerPtrs ptrs;
+    lmc_status_t rc = build_layer_ptrs(c, kv_layers, &ptrs);
+    if (rc != LMC_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t CT = c->cfg.geom.chunk_tokens;
+    if ((rc = validate_slots(c, slot_mapping, n_chunks * CT, s)) != LMC_OK) return rc;
+    const int64_t per = int64_t(lmc::max_chunks_per_launch(c->kg));
+    for (int64_t i0 = 0; i0 < n_chunks; i0 += per) {
+        const int64_t k = std::min(per, n_chunks - i0);
+        rc = timed_launch(c, gather, ptrs, slot_mapping + i0 * CT, uint32_t(k),
+                          staging + i0 * c->chunk_bytes, s);
+        if (rc != LMC_OK) return rc;
+    }
+    return LMC_OK;
+}
+
+lmc_status_t lmc_gather(lmc_ctx_t *c, void *const *kv_layers, const int64_t *slot_mapping,
+                        int64_t n_chunks, void *staging_dev, void *stream) {
+    return device_only(c, true, kv_layers, slot_mapping, n_chunks, static_cast<uint8_t *>(staging_dev), stream);
+}
+
+lmc_status_t lmc_scatter(lmc_ctx_t *c, const void *staging_dev, const int64_t *slot_mapping,
+                         int64_t n_chunks, void *const *kv_layers, void *stream) {
+    return device_only(c, false, kv_layers, slot_mapping, n_chunks,
+                       static_cast<uint8_t *>(const_cast<void *>(staging_dev)), stream);
+}
+
+lmc_status_t lmc_put_host(lmc_ctx_t *c, const uint64_t *ids, int64_t n, const void *host_src) {
+    if (!c || n < 0 || (n > 0 && (!ids || !host_src))) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    if (c->has_device) reap(c);
+    const uint8_t *src = static_cast<const uint8_t *>(host_src);
+    for (int64_t i = 0; i < n; i++) {
+        if (c->index.find(ids[i]) >= 0) {
+            c->stats.chunks_skipped_dup++;
+            continue;
+        }
+        const int64_t s = c->index.insert(ids[i]);
+        if (s < 0) {
+            c->stats.alloc_failures++;
+            return LMC_ERR_NOMEM;
+        }
+        std::memcpy(c->pool + s * c->chunk_bytes, src + i * c->chunk_bytes, size_t(c->chunk_bytes));
+        c->stats.chunks_stored++;
+    }
+    return LMC_OK;
+}
+
+lmc_status_t lmc_get_host(lmc_ctx_t *c, uint64_t id, void *host_dst) {
+    if (!c || !host_dst) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    if (c->has_device) reap(c);
+    const int64_t s = c->index.find(id);
+    if (s < 0) return LMC_ERR_MISS;
+    const uint64_t pending = c->index.meta(s).ready_ticket;
+    if (pending != 0)
+        for (const Op &o : c->ops)
+            if (o.ticket == pending && o.done != nullptr) HIPCHK(c, hipEventSynchronize(o.done));
+    std::memcpy(host_dst, c->pool + s * c->chunk_bytes, size_t(c->chunk_bytes));
+    return LMC_OK;
+}
+
+lmc_status_t lmc_find_slot(lmc_ctx_t *c, uint64_t id, int64_t *slot_out) {
+    if (!c || !slot_out) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    const int64_t s = c->index.find(id);
+    if (s < 0) return LMC_ERR_MISS;
+    *slot_out = s;
+    return LMC_OK;
+}
+
+lmc_status_t lmc_pin(lmc_ctx_t *c, const uint64_t *ids, int64_t n) {
+    if (!c || n < 0 || (n > 0 && !ids)) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    for (int64_t i = 0; i < n; i++)
+        if (c->index.find(ids[i]) < 0) return LMC_ERR_MISS;
+    for (int64_t i = 0; i < n; i++) c->index.meta(c->index.find(ids[i])).pins++;
+    return LMC_OK;
+}
+
+lmc_status_t lmc_unpin(lmc_ctx_t *c, const uint64_t *ids, int64_t n) {
+    if (!c || n < 0 || (n > 0 && !ids)) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    for (int64_t i = 0; i < n; i++)
+        if (c->index.find(ids[i]) < 0) return LMC_ERR_MISS;
+    // take the pins one by one; if one is missing, give back what was taken
+    for (int64_t i = 0; i < n; i++) {
+        lmc::SlotMeta &m = c->index.meta(c->index.find(ids[i]));
+        if (m.pins == 0) {
+            for (int64_t j = 0; j < i; j++) c->index.meta(c->index.find(ids[j])).pins++;
+            return LMC_ERR_INVAL;
+        }
+        m.pins--;
+    }
+    return LMC_OK;
+}
+
+lmc_status_t lmc_clear(lmc_ctx_t *c, const uint64_t *ids, int64_t n) {
+    if (!c || n < 0 || (n > 0 && !ids)) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    if (c->has_device) reap(c);
+    for (int64_t i = 0; i < n; i++) {
+        const int64_t s = c->index.find(ids[i]);
+        if (s >= 0 && (c->index.meta(s).pins > 0 || c->index.meta(s).inflight > 0)) return LMC_ERR_BUSY;
+    }
+    for (int64_t i = 0; i < n; i++) c->index.erase(ids[i]);
+    return LMC_OK;
+}
+
+lmc_status_t lmc_get_stats(lmc_ctx_t *c, lmc_stats_t *out) {
+    if (!c || !out) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    if (c->has_device) reap(c);
+    c->stats.pool_slots_used = uint64_t(c->index.used());
+    *out = c->stats;
+    return LMC_OK;
+}
+
+lmc_status_t lmc_reset_stats(lmc_ctx_t *c) {
+    if (!c) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    if (c->has_device) reap(c);
+    const uint64_t total = c->stats.pool_slots_total;
+    c->stats = lmc_stats_t{};
+    c->stats.pool_slots_total = total;
+    return LMC_OK;
+}
+
+lmc_status_t lmc_measure_link(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, double *h2d_out,
+                              double *d2h_out) {
+    if (!c || !h2d_out || !d2h_out || reps < 1 || nbytes == 0) return LMC_ERR_INVAL;
+    if (!c->has_device) return LMC_ERR_NODEVICE;
+    if (nbytes > uint64_t(c->n_pool_slots) * uint64_t(c->chunk_bytes)) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    HIPCHK(c, hipDeviceSynchronize());
+    reap(c);
+    uint8_t *devbuf = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&devbuf), nbytes);
+    if (e != hipSuccess) {
+        c->last_hip_error = int32_t(e);
+        return LMC_ERR_NOMEM;
+    }
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    lmc_status_t rc = get_event(c, true, &e0);
+    if (rc == LMC_OK) rc = get_event(c, true, &e1);
+    double best[2] = {0.0, 0.0};
+    // upload first, then download the same bytes: the pool ends as it started
+    for (int dir = 0; dir < 2 && rc == LMC_OK; dir++) {
+        hipStream_t s = dir == 0 ? c->s_h2d : c->s_d2h;
+        for (int r = 0; r < reps + 1; r++) {  // first pass warms up
+            hipError_t a = hipEventRecord(e0, s);
+            hipError_t b = dir == 0 ? hipMemcpyAsync(devbuf, c->pool, nbytes, hipMemcpyHostToDevice, s)
+                                    : hipMemcpyAsync(c->pool, devbuf, nbytes, hipMemcpyDeviceToHost, s);
+            hipError_t d = hipEventRecord(e1, s);
+            hipError_t f = hipEventSynchronize(e1);
+            float ms = 0.f;
+            hipError_t g = hipEventElapsedTime(&ms, e0, e1);
+            for (hipError_t x : {a, b, d, f, g})
+                if (x != hipSuccess) {
+                    c->last_hip_error = int32_t(x);
+                    rc = LMC_ERR_HIP;
+                }
+            if (rc != LMC_OK) break;
+            if (r > 0 && ms > 0.f) best[dir] = std::max(best[dir], double(nbytes) / (double(ms) * 1e6));
+        }
+    }
+    if (e0) c->free_time_events.push_back(e0);
+    if (e1) c->free_time_events.push_back(e1);
+    (void)hipFree(devbuf);
+    *h2d_out = best[0];
+    *d2h_out = best[1];
+    return rc;
+}
+
+lmc_status_t lmc_copy(lmc_ctx_t *c, void *dst, const void *src, uint64_t nbytes, void *stream) {
+    if (!c || !dst || !src || (nbytes % 16) != 0 || (reinterpret_cast<uintptr_t>(dst) % 16) != 0 ||
+        (reinterpret_cast<uintptr_t>(src) % 16) != 0)
+        return LMC_ERR_INVAL;
+    if (!c->has_device) return LMC_ERR_NODEVICE;
+    DeviceScope dev(c);
+    HIPCHK(c, lmc::launch_copy(static_cast<uint8_t *>(dst), static_cast<const uint8_t *>(src), nbytes,
+                               static_cast<hipStream_t>(stream)));
+    return LMC_OK;
+}
+
+lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
+    if (!c || !key || value < 0) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    const std::string k(key);
+    if (k == "lp_per_block") {
+        if (value > lmc::kMaxLayerPlanes) return LMC_ERR_INVAL;
+        c->tune_lp_per_block = uint32_t(value);
+    } else if (k == "target_blocks") {
+        if (value < 1 || value > (1 << 24)) return LMC_ERR_INVAL;
+        c->target_blocks = uint32_t(value);
+    } else if (k == "nt_load" && value <= 1) {
+        c->shape.nt_load = value != 0;
+    } else if (k == "nt_store" && value <= 1) {
+        c->shape.nt_store = value != 0;
+    } else {
+        return LMC_ERR_INVAL;
+    }
+    return LMC_OK;
+}
+
+const char *lmc_strerror(lmc_status_t s) {
+    switch (s) {
+        case LMC_OK: return "ok";
+        case LMC_ERR_INVAL: return "invalid argument";
+        case LMC_ERR_NOMEM: return "out of memory / pool full";
+        case LMC_ERR_MISS: return "chunk not present";
+        case LMC_ERR_BADSLOT: return "slot outside the paged KV memory";
+        case LMC_ERR_HIP: return "HIP call failed";
+        case LMC_ERR_BUSY: return "chunk pinned or in flight";
+        case LMC_ERR_NODEVICE: return "context has no device";
+    }
+    return "unknown status";
+}
+
+int32_t lmc_last_hip_error(const lmc_ctx_t *c) { return c ? c->last_hip_error : 0; }
+
+}  // extern "C"

@@ -1,0 +1,302 @@
+"""ctypes binding of liblmc (include/lmc.h).  Argument marshalling only: every step of
+the store / retrieve path runs inside the library.
+
+Device buffers are passed as objects with a ``data_ptr()`` method (torch tensors) or as
+integer addresses; streams as objects with a ``cuda_stream`` attribute (torch streams;
+ROCm PyTorch exposes HIP streams under that name), integer handles, or None for the
+null stream.  Host arrays are numpy.  A status other than LMC_OK raises LMCError.
+
+The library must have been built (``python -m paper_2510_09665_amd.build``); there is
+no fallback of any kind when it is missing.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+LMC_OK, LMC_ERR_INVAL, LMC_ERR_NOMEM, LMC_ERR_MISS, LMC_ERR_BADSLOT = 0, -1, -2, -3, -4
+LMC_ERR_HIP, LMC_ERR_BUSY, LMC_ERR_NODEVICE = -5, -6, -7
+LMC_MAX_LAYERS = 160
+LMC_DEVICE_NONE = -1
+LMC_FLAG_VALIDATE_SLOTS, LMC_FLAG_FORCE_SYNC, LMC_FLAG_POISON_STAGING, LMC_FLAG_TIMING = 1, 2, 4, 8
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblmc.so")
+
+EXPORTS = [
+    "lmc_create", "lmc_destroy", "lmc_chunk_bytes", "lmc_pool_slots", "lmc_hash_chunks",
+    "lmc_lookup", "lmc_store", "lmc_retrieve", "lmc_retrieve_batch", "lmc_wait", "lmc_gather",
+    "lmc_scatter", "lmc_put_host", "lmc_get_host", "lmc_find_slot", "lmc_pin", "lmc_unpin",
+    "lmc_clear", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_copy", "lmc_tune",
+    "lmc_strerror", "lmc_last_hip_error",
+]
+
+
+class lmc_kv_geom_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("num_layers", "num_planes", "num_heads", "head_dim", "elem_bytes", "block_size",
+                 "num_blocks", "chunk_tokens")] + \
+               [(n, ctypes.c_int64) for n in
+                ("plane_stride", "block_stride", "token_stride", "head_stride")]
+
+
+class lmc_config_t(ctypes.Structure):
+    _fields_ = [("geom", lmc_kv_geom_t), ("host_pool_bytes", ctypes.c_uint64),
+                ("num_staging", ctypes.c_int32), ("staging_chunks", ctypes.c_int32),
+                ("device", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("hash_seed", ctypes.c_uint64)]
+
+
+class lmc_stats_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint64) for n in
+                ("pool_slots_total", "pool_slots_used", "chunks_stored", "chunks_skipped_dup",
+                 "chunks_retrieved", "retrieve_misses", "alloc_failures", "bytes_gathered",
+                 "bytes_scattered", "bytes_d2h", "bytes_h2d", "gather_launches",
+                 "scatter_launches", "timed_gather_launches", "timed_scatter_launches")] + \
+               [("gather_ms", ctypes.c_double), ("scatter_ms", ctypes.c_double)]
+
+
+class LMCError(RuntimeError):
+    def __init__(self, status, what, ticket=None, hip_error=0):
+        self.status, self.ticket, self.hip_error = status, ticket, hip_error
+        msg = "%s: %s (%d)" % (what, _lib().lmc_strerror(status).decode(), status)
+        if status == LMC_ERR_HIP:
+            msg += " hipError_t=%d" % hip_error
+        super().__init__(msg)
+
+
+_LIB = None
+
+
+def _lib():
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("liblmc.so is not built: run `python -m paper_2510_09665_amd.build` "
+                              "(needs hipcc); there is no fallback path")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i64, u64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64, ctypes.c_int32
+        st = ctypes.c_int32
+        sig = {
+            "lmc_create": (st, [ctypes.POINTER(lmc_config_t), ctypes.POINTER(vp)]),
+            "lmc_destroy": (st, [vp]),
+            "lmc_chunk_bytes": (i64, [vp]),
+            "lmc_pool_slots": (i64, [vp]),
+            "lmc_hash_chunks": (st, [vp, vp, i64, vp, ctypes.POINTER(i64)]),
+            "lmc_lookup": (st, [vp, vp, i64, ctypes.POINTER(i64)]),
+            "lmc_store": (st, [vp, vp, vp, vp, i64, vp, ctypes.POINTER(u64)]),
+            "lmc_retrieve": (st, [vp, vp, i64, vp, vp, vp, ctypes.POINTER(u64)]),
+            "lmc_retrieve_batch": (st, [vp, i64, vp, vp, vp, vp, vp, ctypes.POINTER(u64)]),
+            "lmc_wait": (st, [vp, u64]),
+            "lmc_gather": (st, [vp, vp, vp, i64, vp, vp]),
+            "lmc_scatter": (st, [vp, vp, vp, i64, vp, vp]),
+            "lmc_put_host": (st, [vp, vp, i64, vp]),
+            "lmc_get_host": (st, [vp, u64, vp]),
+            "lmc_find_slot": (st, [vp, u64, ctypes.POINTER(i64)]),
+            "lmc_pin": (st, [vp, vp, i64]),
+            "lmc_unpin": (st, [vp, vp, i64]),
+            "lmc_clear": (st, [vp, vp, i64]),
+            "lmc_get_stats": (st, [vp, ctypes.POINTER(lmc_stats_t)]),
+            "lmc_reset_stats": (st, [vp]),
+            "lmc_measure_link": (st, [vp, u64, i32, ctypes.POINTER(ctypes.c_double),
+                                      ctypes.POINTER(ctypes.c_double)]),
+            "lmc_copy": (st, [vp, vp, vp, u64, vp]),
+            "lmc_tune": (st, [vp, ctypes.c_char_p, i64]),
+            "lmc_strerror": (ctypes.c_char_p, [st]),
+            "lmc_last_hip_error": (i32, [vp]),
+        }
+        assert sorted(sig) == sorted(EXPORTS)
+        for name, (res, args) in sig.items():
+            f = getattr(lib, name)
+            f.restype, f.argtypes = res, args
+        _LIB = lib
+    return _LIB
+
+
+def _dev(x):
+    """device address of a tensor-like or an int"""
+    if x is None:
+        return None
+    return ctypes.c_void_p(x.data_ptr() if hasattr(x, "data_ptr") else int(x))
+
+
+def _stream(s):
+    if s is None:
+        return None
+    return ctypes.c_void_p(getattr(s, "cuda_stream", s))
+
+
+def _host(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a, ctypes.c_void_p(a.ctypes.data)
+
+
+def make_geom(g):
+    """lmc_kv_geom_t from any object with L P H D e BS NB CT and the four strides."""
+    return lmc_kv_geom_t(g.L, g.P, g.H, g.D, g.e, g.BS, g.NB, g.CT, g.plane_stride,
+                         g.block_stride, g.token_stride, g.head_stride)
+
+
+class Context:
+    """One lmc_ctx_t.  Methods carry the C names without the lmc_ prefix."""
+
+    def __init__(self, geom, host_pool_bytes, num_staging=2, staging_chunks=1, device=0, flags=0,
+                 hash_seed=0):
+        self._h = None
+        g = geom if isinstance(geom, lmc_kv_geom_t) else make_geom(geom)
+        cfg = lmc_config_t(g, host_pool_bytes, num_staging, staging_chunks, device, flags,
+                           hash_seed)
+        h = ctypes.c_void_p()
+        rc = _lib().lmc_create(ctypes.byref(cfg), ctypes.byref(h))
+        if rc != LMC_OK:
+            raise LMCError(rc, "lmc_create")
+        self._h = h
+        self.chunk_tokens = g.chunk_tokens
+        self.num_layers = g.num_layers
+
+    # -- lifetime ---------------------------------------------------------------
+    def destroy(self):
+        if self._h is not None:
+            _lib().lmc_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.destroy()
+
+    def _check(self, rc, what, ticket=None):
+        if rc != LMC_OK:
+            raise LMCError(rc, what, ticket, _lib().lmc_last_hip_error(self._h))
+
+    def _layers(self, kv_layers):
+        if len(kv_layers) != self.num_layers:
+            raise ValueError("expected %d layer pointers" % self.num_layers)
+        return (ctypes.c_void_p * len(kv_layers))(
+            *[(x.data_ptr() if hasattr(x, "data_ptr") else int(x)) for x in kv_layers])
+
+    # -- sizes ------------------------------------------------------------------
+    def chunk_bytes(self):
+        return int(_lib().lmc_chunk_bytes(self._h))
+
+    def pool_slots(self):
+        return int(_lib().lmc_pool_slots(self._h))
+
+    # -- token processor / index --------------------------------------------------
+    def hash_chunks(self, tokens):
+        tok, tp = _host(tokens, np.int32)
+        out = np.empty(tok.size // self.chunk_tokens, dtype=np.uint64)
+        n = ctypes.c_int64()
+        self._check(_lib().lmc_hash_chunks(self._h, tp, tok.size, ctypes.c_void_p(out.ctypes.data),
+                                           ctypes.byref(n)), "lmc_hash_chunks")
+        return out[:n.value]
+
+    def lookup(self, chunk_ids):
+        ids, ip = _host(chunk_ids, np.uint64)
+        n = ctypes.c_int64()
+        self._check(_lib().lmc_lookup(self._h, ip, ids.size, ctypes.byref(n)), "lmc_lookup")
+        return n.value
+
+    # -- the path -----------------------------------------------------------------
+    def store(self, kv_layers, slot_mapping, chunk_ids, stream_to_wait_on=None):
+        """Enqueue; returns the ticket.  On LMC_ERR_NOMEM the error carries the ticket."""
+        ids, ip = _host(chunk_ids, np.uint64)
+        t = ctypes.c_uint64()
+        rc = _lib().lmc_store(self._h, self._layers(kv_layers), _dev(slot_mapping), ip, ids.size,
+                              _stream(stream_to_wait_on), ctypes.byref(t))
+        self._check(rc, "lmc_store", t.value)
+        return t.value
+
+    def retrieve(self, chunk_ids, slot_mapping, kv_layers, stream_to_signal=None):
+        ids, ip = _host(chunk_ids, np.uint64)
+        t = ctypes.c_uint64()
+        rc = _lib().lmc_retrieve(self._h, ip, ids.size, _dev(slot_mapping), self._layers(kv_layers),
+                                 _stream(stream_to_signal), ctypes.byref(t))
+        self._check(rc, "lmc_retrieve", t.value)
+        return t.value
+
+    def retrieve_batch(self, req_chunk_offsets, chunk_ids, slot_mapping, kv_layers,
+                       stream_to_signal=None):
+        off, op = _host(req_chunk_offsets, np.int64)
+        ids, ip = _host(chunk_ids, np.uint64)
+        t = ctypes.c_uint64()
+        rc = _lib().lmc_retrieve_batch(self._h, off.size - 1, op, ip, _dev(slot_mapping),
+                                       self._layers(kv_layers), _stream(stream_to_signal),
+                                       ctypes.byref(t))
+        self._check(rc, "lmc_retrieve_batch", t.value)
+        return t.value
+
+    def wait(self, ticket=0):
+        self._check(_lib().lmc_wait(self._h, ticket), "lmc_wait")
+
+    def gather(self, kv_layers, slot_mapping, n_chunks, staging_dev, stream=None):
+        self._check(_lib().lmc_gather(self._h, self._layers(kv_layers), _dev(slot_mapping), n_chunks,
+                                      _dev(staging_dev), _stream(stream)), "lmc_gather")
+
+    def scatter(self, staging_dev, slot_mapping, n_chunks, kv_layers, stream=None):
+        self._check(_lib().lmc_scatter(self._h, _dev(staging_dev), _dev(slot_mapping), n_chunks,
+                                       self._layers(kv_layers), _stream(stream)), "lmc_scatter")
+
+    # -- host-side chunk access -----------------------------------------------------
+    def put_host(self, chunk_ids, host_src):
+        ids, ip = _host(chunk_ids, np.uint64)
+        src, sp = _host(host_src, np.uint8)
+        if src.size != ids.size * self.chunk_bytes():
+            raise ValueError("host_src must hold %d chunks" % ids.size)
+        self._check(_lib().lmc_put_host(self._h, ip, ids.size, sp), "lmc_put_host")
+
+    def get_host(self, chunk_id):
+        out = np.empty(self.chunk_bytes(), dtype=np.uint8)
+        self._check(_lib().lmc_get_host(self._h, int(chunk_id), ctypes.c_void_p(out.ctypes.data)),
+                    "lmc_get_host")
+        return out
+
+    def find_slot(self, chunk_id):
+        s = ctypes.c_int64()
+        self._check(_lib().lmc_find_slot(self._h, int(chunk_id), ctypes.byref(s)), "lmc_find_slot")
+        return s.value
+
+    def pin(self, chunk_ids):
+        ids, ip = _host(chunk_ids, np.uint64)
+        self._check(_lib().lmc_pin(self._h, ip, ids.size), "lmc_pin")
+
+    def unpin(self, chunk_ids):
+        ids, ip = _host(chunk_ids, np.uint64)
+        self._check(_lib().lmc_unpin(self._h, ip, ids.size), "lmc_unpin")
+
+    def clear(self, chunk_ids):
+        ids, ip = _host(chunk_ids, np.uint64)
+        self._check(_lib().lmc_clear(self._h, ip, ids.size), "lmc_clear")
+
+    # -- stats, measurement, tuning ---------------------------------------------------
+    def get_stats(self):
+        s = lmc_stats_t()
+        self._check(_lib().lmc_get_stats(self._h, ctypes.byref(s)), "lmc_get_stats")
+        return {n: getattr(s, n) for n, _ in lmc_stats_t._fields_}
+
+    def reset_stats(self):
+        self._check(_lib().lmc_reset_stats(self._h), "lmc_reset_stats")
+
+    def measure_link(self, nbytes, reps=3):
+        """(h2d GB/s, d2h GB/s) of hipMemcpyAsync between the pinned pool and the GPU."""
+        a, b = ctypes.c_double(), ctypes.c_double()
+        self._check(_lib().lmc_measure_link(self._h, nbytes, reps, ctypes.byref(a), ctypes.byref(b)),
+                    "lmc_measure_link")
+        return a.value, b.value
+
+    def copy(self, dst_dev, src_dev, nbytes, stream=None):
+        self._check(_lib().lmc_copy(self._h, _dev(dst_dev), _dev(src_dev), nbytes, _stream(stream)),
+                    "lmc_copy")
+
+    def tune(self, key, value):
+        self._check(_lib().lmc_tune(self._h, key.encode(), int(value)), "lmc_tune")
+
+
+def strerror(status):
+    return _lib().lmc_strerror(status).decode()

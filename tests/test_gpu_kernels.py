@@ -1,0 +1,175 @@
+"""GPU parity of the two kernels alone (lmc_gather / lmc_scatter, paper section 5.1)
+against the CPU oracle, byte for byte, through the C ABI."""
+import zlib
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2510_09665_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+# shapes chosen to cross every kernel path: 16-byte vectors with contiguous rows,
+# per-head runs (HND), padded blocks, rows that are not a multiple of a wavefront
+# (MLA: 72 and 36 vectors), narrow vectors (8/4/2/1 bytes), a block size that is not a
+# power of two, a layer-plane count that is not a multiple of the unroll, P=1 and P=2.
+SHAPES = {
+    "tiny_cfg1": dict(L=2, P=2, H=4, D=64, e=2, BS=16, NB=64, CT=256),
+    "hnd": dict(L=5, P=2, H=8, D=64, e=2, BS=16, NB=40, CT=64, layout="HND"),
+    "padded": dict(L=3, P=2, H=2, D=64, e=2, BS=8, NB=50, CT=64, block_pad=32),
+    "mla_bf16_like": dict(L=7, P=1, H=1, D=576, e=2, BS=64, NB=12, CT=256),
+    "mla_fp8_like": dict(L=9, P=1, H=1, D=576, e=1, BS=64, NB=12, CT=256),
+    "vec8": dict(L=3, P=2, H=3, D=12, e=2, BS=4, NB=64, CT=32),
+    "vec4_hnd": dict(L=3, P=2, H=3, D=6, e=2, BS=4, NB=64, CT=32, layout="HND"),
+    "vec2": dict(L=2, P=2, H=3, D=7, e=2, BS=4, NB=64, CT=32),
+    "vec1_pad": dict(L=2, P=1, H=2, D=5, e=1, BS=3, NB=70, CT=24, block_pad=1),
+    "bs_not_pow2": dict(L=17, P=2, H=2, D=32, e=2, BS=12, NB=30, CT=48),
+    "many_lp": dict(L=37, P=2, H=1, D=64, e=2, BS=16, NB=32, CT=128),
+}
+
+
+def _ctx(g, **kw):
+    from paper_2510_09665_amd import lmc
+    return lmc.Context(g, 4 * g.chunk_bytes, **kw)
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+@pytest.mark.parametrize("lp_per_block", [0, 3])
+def test_gather_and_scatter_match_oracle(name, lp_per_block):
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    g = W.KVGeometry(**SHAPES[name])
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    n_chunks = 3
+    n_tok = n_chunks * g.CT
+    assert n_tok <= g.n_slots
+    slots = rng.permutation(g.n_slots)[:n_tok].astype(np.int64)
+    slots[rng.integers(0, n_tok, 5)] = -1                 # tokens without a page
+    slots[rng.integers(0, n_tok)] = -(2**40)
+    src = PagedKV(g, np.arange(g.NB), rng)
+    d_slots = slots_to_device(slots)
+    with _ctx(g) as c:
+        if lp_per_block:
+            c.tune("lp_per_block", lp_per_block)
+        staging = torch.full((n_chunks * g.chunk_bytes + 64,), 0xCD, dtype=torch.uint8, device="cuda")
+        c.gather(src.dev, d_slots, n_chunks, staging, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        c.wait()
+        want = oracle.gather(g, src.host, slots)
+        got = staging.cpu().numpy()
+        assert np.array_equal(got[:n_chunks * g.chunk_bytes].reshape(n_chunks, -1), want)
+        assert (got[n_chunks * g.chunk_bytes:] == 0xCD).all()      # nothing past the last chunk
+
+        # scatter the oracle's chunks into fresh pages under another mapping
+        tau = rng.permutation(g.n_slots)[:n_tok].astype(np.int64)
+        tau[rng.integers(0, n_tok, 4)] = -3
+        dst = PagedKV(g, np.arange(g.NB), fill="sentinel")
+        chunks_dev = torch.from_numpy(want.reshape(-1)).cuda()
+        c.scatter(chunks_dev, slots_to_device(tau), n_chunks, dst.dev, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        c.wait()
+        oracle.scatter(g, want, tau, dst.host)
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host, name)
+
+
+def test_empty_and_single_token_edge_cases():
+    import torch
+    from gpu_util import PagedKV, slots_to_device
+    g = W.KVGeometry(**SHAPES["tiny_cfg1"])
+    rng = np.random.default_rng(0)
+    src = PagedKV(g, np.arange(g.NB), rng)
+    with _ctx(g) as c:
+        staging = torch.full((g.chunk_bytes,), 0x11, dtype=torch.uint8, device="cuda")
+        c.gather(src.dev, slots_to_device(np.zeros(0)), 0, staging)       # zero chunks: no-op
+        torch.cuda.synchronize()
+        assert bool((staging == 0x11).all())
+        # every token without a page: the chunk is all zeros
+        c.gather(src.dev, slots_to_device(np.full(g.CT, -1)), 1, staging)
+        torch.cuda.synchronize()
+        assert bool((staging == 0).all())
+        # all tokens in one page position (a gather may repeat slots)
+        s = np.full(g.CT, 5, dtype=np.int64)
+        c.gather(src.dev, slots_to_device(s), 1, staging)
+        torch.cuda.synchronize()
+        assert np.array_equal(staging.cpu().numpy(), oracle.gather_chunk(g, src.host, s))
+        # the last slot of the pool
+        s = np.full(g.CT, -1, dtype=np.int64)
+        s[-1] = g.n_slots - 1
+        c.gather(src.dev, slots_to_device(s), 1, staging)
+        torch.cuda.synchronize()
+        assert np.array_equal(staging.cpu().numpy(), oracle.gather_chunk(g, src.host, s))
+        c.wait()
+
+
+def test_bad_slot_is_skipped_and_reported():
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    from paper_2510_09665_amd import lmc
+    g = W.KVGeometry(**SHAPES["tiny_cfg1"])
+    rng = np.random.default_rng(1)
+    src = PagedKV(g, np.arange(g.NB), rng)
+    slots = rng.permutation(g.n_slots)[:g.CT].astype(np.int64)
+    bad = slots.copy()
+    bad[7] = g.n_slots
+    bad[100] = 2**45
+    as_skip = slots.copy()
+    as_skip[[7, 100]] = -1
+    chunk = oracle.gather_chunk(g, src.host, slots)
+    with _ctx(g) as c:
+        staging = torch.empty(g.chunk_bytes, dtype=torch.uint8, device="cuda")
+        c.gather(src.dev, slots_to_device(bad), 1, staging)
+        torch.cuda.synchronize()
+        with pytest.raises(lmc.LMCError) as e:
+            c.wait()
+        assert e.value.status == lmc.LMC_ERR_BADSLOT
+        c.wait()                                           # reported once
+        assert np.array_equal(staging.cpu().numpy(), oracle.gather_chunk(g, src.host, as_skip))
+        dst = PagedKV(g, np.arange(g.NB), fill="sentinel")
+        c.scatter(torch.from_numpy(chunk).cuda(), slots_to_device(bad), 1, dst.dev)
+        torch.cuda.synchronize()
+        with pytest.raises(lmc.LMCError) as e:
+            c.wait()
+        assert e.value.status == lmc.LMC_ERR_BADSLOT
+        oracle.scatter_chunk(g, chunk, as_skip, dst.host)
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host)
+    # with validation the call itself fails and nothing is written
+    with _ctx(g, flags=lmc.LMC_FLAG_VALIDATE_SLOTS) as c:
+        dst = PagedKV(g, np.arange(g.NB), fill="sentinel")
+        with pytest.raises(lmc.LMCError) as e:
+            c.scatter(torch.from_numpy(chunk).cuda(), slots_to_device(bad), 1, dst.dev)
+        assert e.value.status == lmc.LMC_ERR_BADSLOT
+        torch.cuda.synchronize()
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host)
+        c.scatter(torch.from_numpy(chunk).cuda(), slots_to_device(slots), 1, dst.dev)
+        torch.cuda.synchronize()
+        c.wait()
+
+
+def test_misaligned_arguments_are_refused():
+    import torch
+    from gpu_util import PagedKV, slots_to_device
+    from paper_2510_09665_amd import lmc
+    g = W.KVGeometry(**SHAPES["tiny_cfg1"])
+    src = PagedKV(g, np.arange(g.NB), np.random.default_rng(2))
+    with _ctx(g) as c:
+        staging = torch.empty(g.chunk_bytes + 16, dtype=torch.uint8, device="cuda")
+        s = slots_to_device(np.arange(g.CT))
+        with pytest.raises(lmc.LMCError) as e:
+            c.gather(src.dev, s, 1, staging.data_ptr() + 4)
+        assert e.value.status == lmc.LMC_ERR_INVAL
+        with pytest.raises(lmc.LMCError) as e:
+            c.gather([src.dev[0].data_ptr() + 8, src.dev[1]], s, 1, staging)
+        assert e.value.status == lmc.LMC_ERR_INVAL
+
+
+def test_copy_kernel():
+    import torch
+    g = W.KVGeometry(**SHAPES["tiny_cfg1"])
+    with _ctx(g) as c:
+        for n in (16, 4096 + 16, 3 * 2**20 + 48):
+            src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
+            dst = torch.zeros(n + 16, dtype=torch.uint8, device="cuda")
+            c.copy(dst, src, n, torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            assert torch.equal(dst[:n], src) and bool((dst[n:] == 0).all())

@@ -1,0 +1,308 @@
+"""GPU parity of the whole path (hash -> lookup -> store -> retrieve, paper sections 4
+and 5.1) against the CPU oracle on the benchmark configurations, byte for byte, plus
+the pipeline's hazards and error paths.  Everything goes through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2510_09665_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _lmc():
+    from paper_2510_09665_amd import lmc
+    return lmc
+
+
+def _run_sequence(name, geom=None, flags=0, num_staging=2, staging_chunks=1, n_tokens=None,
+                  pool_chunks=None):
+    """Store a whole request, retrieve it into fresh blocks, compare pool and pages."""
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    lmc = _lmc()
+    g = geom or W.geometry(name)
+    seq = W.sequence(name, g, n_tokens=n_tokens)
+    rng = W.rng_for(name, stream=1)
+    src = PagedKV(g, seq["store_blocks"], rng)
+    dst = PagedKV(g, seq["load_blocks"], fill="sentinel")
+    n_chunks = seq["tokens"].size // g.CT
+    pool_chunks = pool_chunks or n_chunks
+    stream = torch.cuda.current_stream()
+    with lmc.Context(g, pool_chunks * g.chunk_bytes, num_staging=num_staging,
+                     staging_chunks=staging_chunks, flags=flags | lmc.LMC_FLAG_TIMING) as c:
+        ids = c.hash_chunks(seq["tokens"])
+        assert np.array_equal(ids, oracle.hash_chunks(seq["tokens"], g.CT, 0))
+        assert c.lookup(ids) == 0
+        t = c.store(src.dev, slots_to_device(seq["store_slots"]), ids, stream)
+        assert c.lookup(ids) == n_chunks          # visible at once
+        # retrieve is enqueued without waiting for the store: ordered on the device
+        t2 = c.retrieve(ids, slots_to_device(seq["load_slots"]), dst.dev, stream)
+        c.wait(t)
+        c.wait(t2)
+        torch.cuda.synchronize()
+
+        ora = oracle.OracleStore(src.gc, pool_chunks)
+        rc, n_new = ora.store(src.host, src.compact_slots(seq["store_slots"]), ids)
+        assert (rc, n_new) == (0, n_chunks)
+        for i in ids.tolist():                    # pool image: same slot, same bytes
+            assert c.find_slot(i) == ora.find(i)
+            assert np.array_equal(c.get_host(i), ora.slot_bytes(ora.find(i))), "pool chunk"
+        # the oracle retrieves from its own pool into the compact destination
+        for k, i in enumerate(ids.tolist()):
+            oracle.scatter_chunk(dst.gc, ora.slot_bytes(ora.find(i)),
+                                 dst.compact_slots(seq["load_slots"][k * g.CT:(k + 1) * g.CT]),
+                                 dst.host)
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host, name + " retrieve")
+        assert dst.untracked_blocks_untouched()
+        assert src.untracked_blocks_untouched()
+        assert_layers_equal(src.device_blocks_to_host(), src.host, name + " source unchanged")
+        st = c.get_stats()
+        assert st["chunks_stored"] == n_chunks and st["chunks_retrieved"] == n_chunks
+        assert st["bytes_d2h"] == st["bytes_h2d"] == n_chunks * g.chunk_bytes
+        assert st["timed_gather_launches"] == st["gather_launches"] > 0
+        assert st["gather_ms"] > 0 and st["scatter_ms"] > 0
+        ora.close()
+        return st
+
+
+def test_config1_tiny():
+    _run_sequence("tiny")
+
+
+def test_config2_llama3_8b_full():
+    st = _run_sequence("llama3_8b", staging_chunks=4)
+    assert st["gather_launches"] == 4
+
+
+def test_config5_mla_bf16_full():
+    _run_sequence("mla_bf16", staging_chunks=2)
+
+
+def test_config5_mla_fp8_full():
+    _run_sequence("mla_fp8", staging_chunks=3)      # 32 chunks in groups of 3: ragged last group
+
+
+@pytest.mark.parametrize("flags", ["poison", "force_sync", "validate"])
+def test_pipeline_modes_give_identical_results(flags):
+    lmc = _lmc()
+    f = {"poison": lmc.LMC_FLAG_POISON_STAGING, "force_sync": lmc.LMC_FLAG_FORCE_SYNC,
+         "validate": lmc.LMC_FLAG_VALIDATE_SLOTS}[flags]
+    # 24 chunks through a ring of 2 single-chunk buffers: every buffer is reused 12 times
+    g = W.geometry("llama3_8b", L=4, NB=1024)
+    _run_sequence("llama3_8b", g, flags=f, n_tokens=24 * 256)
+    _run_sequence("llama3_8b", g, flags=f, n_tokens=24 * 256, num_staging=3, staging_chunks=5)
+
+
+def test_hnd_layout_through_the_pipeline():
+    g = W.geometry("llama3_8b", L=6, NB=512, layout="HND")
+    _run_sequence("llama3_8b", g, n_tokens=8 * 256, staging_chunks=3)
+
+
+def test_config3_llama3_70b_full_size_sampled_oracle():
+    """Full size on the device (40 GiB of pages, 128 chunks = 10 GiB through the pinned
+    pool).  The oracle checks sampled chunks byte for byte; the whole result is checked
+    by a property that holds at any size: every destination block equals its source
+    block, and no other block changed."""
+    import torch
+    from gpu_util import PagedKV, sentinel_byte, slots_to_device
+    lmc = _lmc()
+    name = "llama3_70b"
+    g = W.geometry(name)
+    seq = W.sequence(name, g)
+    n_chunks = seq["tokens"].size // g.CT
+    assert n_chunks == 128 and g.chunk_bytes == 80 * 2**20
+    bpc = g.CT // g.BS                                      # blocks per chunk
+    sample = [0, 1, 63, 64, 127]
+    rng = W.rng_for(name, stream=1)
+    # sampled chunks: host-generated payload; all other source blocks: device RNG
+    sb = np.concatenate([seq["store_blocks"][k * bpc:(k + 1) * bpc] for k in sample])
+    lb = np.concatenate([seq["load_blocks"][k * bpc:(k + 1) * bpc] for k in sample])
+    src = PagedKV(g, sb, rng)
+    dst = PagedKV(g, lb, fill="sentinel")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(W.SEED_BASE + 3)
+    others = torch.from_numpy(np.setdiff1d(seq["store_blocks"], sb)).cuda()
+    for d in src.dev:
+        v = d.view(g.P, g.NB, g.block_stride)
+        r = (torch.rand((g.P, others.numel(), g.block_stride // 2), device="cuda", generator=gen) * 2 - 1)
+        v[:, others] = r.to(torch.bfloat16).view(torch.uint8).view(g.P, others.numel(), g.block_stride)
+    stream = torch.cuda.current_stream()
+    with lmc.Context(g, n_chunks * g.chunk_bytes, staging_chunks=2) as c:
+        ids = c.hash_chunks(seq["tokens"])
+        t = c.store(src.dev, slots_to_device(seq["store_slots"]), ids, stream)
+        t2 = c.retrieve(ids, slots_to_device(seq["load_slots"]), dst.dev, stream)
+        c.wait(t2)
+        torch.cuda.synchronize()
+        for k in sample:
+            sl = src.compact_slots(seq["store_slots"][k * g.CT:(k + 1) * g.CT])
+            want = oracle.gather_chunk(src.gc, src.host, sl)
+            assert np.array_equal(c.get_host(ids[k]), want), "pool chunk %d" % k
+            oracle.scatter_chunk(dst.gc, want, dst.compact_slots(seq["load_slots"][k * g.CT:(k + 1) * g.CT]),
+                                 dst.host)
+        from gpu_util import assert_layers_equal
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host, "sampled chunks")
+    # whole-result property on the device
+    s_all = torch.from_numpy(seq["store_blocks"]).cuda()
+    l_all = torch.from_numpy(seq["load_blocks"]).cuda()
+    keep = torch.ones(g.NB, dtype=torch.bool, device="cuda")
+    keep[l_all] = False
+    for l in range(g.L):
+        sv = src.dev[l].view(g.P, g.NB, g.block_stride)
+        dv = dst.dev[l].view(g.P, g.NB, g.block_stride)
+        assert torch.equal(dv[:, l_all], sv[:, s_all]), "layer %d round trip" % l
+        assert bool((dv[:, keep] == sentinel_byte(l)).all()), "layer %d untouched blocks" % l
+
+
+def test_config4_batched_multi_request_retrieve():
+    """64 requests, lognormal prefix lengths, only the leading hit chunks are loaded, in
+    one lmc_retrieve_batch call; pool slots in shuffled order; every byte checked."""
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    lmc = _lmc()
+    name = "batch_8b"
+    g = W.geometry(name)
+    reqs = W.request_mix(name, g)
+    rng = W.rng_for(name, stream=2)
+    n_hit = sum(r["n_hit"] for r in reqs)
+    assert 100 < n_hit <= g.NB // (g.CT // g.BS)
+    all_blocks = np.concatenate([r["load_blocks"] for r in reqs])
+    dst = PagedKV(g, all_blocks, fill="sentinel")
+    base = W.payload_bytes(rng, g, g.chunk_bytes).view(np.uint64)
+    with lmc.Context(g, (n_hit + 3) * g.chunk_bytes, staging_chunks=8) as c:
+        ids_per_req = [c.hash_chunks(r["tokens"]) for r in reqs]
+        for r, ids in zip(reqs, ids_per_req):
+            assert np.array_equal(ids, oracle.hash_chunks(r["tokens"], g.CT, 0))
+        # the hit chunks reach the host pool from "a lower tier", in shuffled order
+        hit = [(ri, k) for ri, r in enumerate(reqs) for k in range(r["n_hit"])]
+        chunk_of = {}
+        for j in rng.permutation(len(hit)):
+            ri, k = hit[j]
+            payload = (base ^ np.uint64((ri * 1000003 + k * 7919 + 1) * 0x9E3779B97F4A7C15 % 2**64)) \
+                .view(np.uint8)
+            c.put_host([ids_per_req[ri][k]], payload)
+            chunk_of[(ri, k)] = payload
+        # scheduler side: prefix match per request
+        off, ids, slots = [0], [], []
+        for ri, r in enumerate(reqs):
+            assert c.lookup(ids_per_req[ri]) == r["n_hit"]
+            ids.append(ids_per_req[ri][:r["n_hit"]])
+            slots.append(r["load_slots"])
+            off.append(off[-1] + r["n_hit"])
+        ids, slots = np.concatenate(ids), np.concatenate(slots)
+        t = c.retrieve_batch(off, ids, slots_to_device(slots), dst.dev, torch.cuda.current_stream())
+        c.wait(t)
+        torch.cuda.synchronize()
+        st = c.get_stats()
+        assert st["chunks_retrieved"] == n_hit and st["scatter_launches"] == -(-n_hit // 8)
+        cs = dst.compact_slots(slots)
+        j = 0
+        for ri, r in enumerate(reqs):
+            for k in range(r["n_hit"]):
+                oracle.scatter_chunk(dst.gc, chunk_of[(ri, k)], cs[j * g.CT:(j + 1) * g.CT], dst.host)
+                j += 1
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host, "batched retrieve")
+        assert dst.untracked_blocks_untouched()
+        # one missing chunk anywhere: nothing is written
+        before = dst.device_blocks_to_host()
+        bad_ids = ids.copy()
+        bad_ids[len(bad_ids) // 2] ^= np.uint64(1)
+        with pytest.raises(lmc.LMCError) as e:
+            c.retrieve_batch(off, bad_ids, slots_to_device(slots), dst.dev)
+        assert e.value.status == lmc.LMC_ERR_MISS
+        torch.cuda.synchronize()
+        assert_layers_equal(dst.device_blocks_to_host(), before)
+
+
+def _status(fn):
+    lmc = _lmc()
+    try:
+        fn()
+        return 0
+    except lmc.LMCError as e:
+        return e.status
+
+
+def test_store_semantics_against_oracle_store():
+    """Duplicate ids are skipped (first writer wins), lowest free slot first, NOMEM keeps
+    what was stored, MISS writes nothing, pinned chunks cannot be cleared: statuses, slot
+    numbers and pool bytes all equal the oracle's chunk store."""
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    lmc = _lmc()
+    g = W.geometry("tiny")
+    rng = np.random.default_rng(77)
+    kv = PagedKV(g, np.arange(g.NB), rng)
+    slots = rng.permutation(g.n_slots)[:4 * g.CT].reshape(4, g.CT)
+    stream = torch.cuda.current_stream()
+    ora = oracle.OracleStore(g, 3)
+
+    def both_store(c, ids, sl):
+        want_rc, _ = ora.store(kv.host, sl, ids)
+        got_rc = _status(lambda: c.store(kv.dev, slots_to_device(sl), ids, stream))
+        assert got_rc == want_rc
+        c.wait()
+        for i in range(1, 12):
+            if ora.find(i) < 0:
+                assert _status(lambda: c.find_slot(i)) == lmc.LMC_ERR_MISS
+            else:
+                assert c.find_slot(i) == ora.find(i)
+                assert np.array_equal(c.get_host(i), ora.slot_bytes(ora.find(i))), i
+
+    with lmc.Context(g, 3 * g.chunk_bytes) as c:
+        both_store(c, [1, 2], slots[:2])
+        both_store(c, [1, 3, 1], slots[1:4])          # 1 is present: other pages, not rewritten
+        assert c.get_stats()["chunks_skipped_dup"] == 2
+        both_store(c, [4], slots[:1])                 # pool full: NOMEM, nothing changes
+        assert c.get_stats()["alloc_failures"] == 1
+        assert c.clear([2]) is None and ora.clear([2]) == 0
+        both_store(c, [5, 6, 7], slots[:3])           # 5 takes slot 1, then NOMEM at 6
+        assert c.lookup([1, 5, 9, 3]) == ora.lookup([1, 5, 9, 3]) == 2
+        # retrieve with a missing id writes nothing
+        dst = PagedKV(g, np.arange(g.NB), fill="sentinel")
+        assert _status(lambda: c.retrieve([1, 6], slots_to_device(slots[:2]), dst.dev, stream)) \
+            == lmc.LMC_ERR_MISS == ora.retrieve([1, 6], slots[:2], dst.host)
+        torch.cuda.synchronize()
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host)
+        assert c.get_stats()["retrieve_misses"] == 1
+        # the same chunk twice in one retrieve, to different pages
+        t = c.retrieve([3, 3], slots_to_device(slots[2:4]), dst.dev, stream)
+        c.wait(t)
+        assert ora.retrieve([3, 3], slots[2:4], dst.host) == 0
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host)
+        # pin / clear / unpin
+        c.pin([5])
+        assert _status(lambda: c.clear([1, 5])) == lmc.LMC_ERR_BUSY
+        assert c.lookup([1]) == 1
+        c.unpin([5])
+        assert _status(lambda: c.unpin([5])) == lmc.LMC_ERR_INVAL
+        c.clear([1, 5, 3, 999])
+        assert c.get_stats()["pool_slots_used"] == 0
+    ora.close()
+
+
+def test_partial_skip_store_launches_per_run_of_new_chunks():
+    """Chunks 0,1 and 4 are present; 2,3 and 5,6,7 are new: two runs, gathered from the
+    right parts of the slot mapping."""
+    import torch
+    from gpu_util import PagedKV, slots_to_device
+    lmc = _lmc()
+    g = W.geometry("tiny", NB=256)
+    rng = np.random.default_rng(5)
+    kv = PagedKV(g, np.arange(g.NB), rng)
+    toks = W.tokens_for(rng, 8 * g.CT)
+    slots = rng.permutation(g.n_slots)[:8 * g.CT].reshape(8, g.CT)
+    other = rng.permutation(g.n_slots)[:8 * g.CT].reshape(8, g.CT)
+    with lmc.Context(g, 8 * g.chunk_bytes, staging_chunks=4) as c:
+        ids = c.hash_chunks(toks)
+        c.store(kv.dev, slots_to_device(other[[0, 1, 4]]), ids[[0, 1, 4]], torch.cuda.current_stream())
+        c.wait()
+        c.reset_stats()
+        c.store(kv.dev, slots_to_device(slots), ids, torch.cuda.current_stream())
+        c.wait()
+        st = c.get_stats()
+        assert st["chunks_stored"] == 5 and st["chunks_skipped_dup"] == 3
+        assert st["gather_launches"] == 2
+        for k in range(8):
+            src_slots = other[k] if k in (0, 1, 4) else slots[k]
+            assert np.array_equal(c.get_host(ids[k]), oracle.gather_chunk(g, kv.host, src_slots)), k
