@@ -34,10 +34,12 @@ def _run_sequence(name, geom=None, flags=0, num_staging=2, staging_chunks=1, n_t
         ids = c.hash_chunks(seq["tokens"])
         assert np.array_equal(ids, oracle.hash_chunks(seq["tokens"], g.CT, 0))
         assert c.lookup(ids) == 0
-        t = c.store(src.dev, slots_to_device(seq["store_slots"]), ids, stream)
+        # the slot mappings must stay alive until lmc_wait: keep the tensors referenced
+        d_store, d_load = slots_to_device(seq["store_slots"]), slots_to_device(seq["load_slots"])
+        t = c.store(src.dev, d_store, ids, stream)
         assert c.lookup(ids) == n_chunks          # visible at once
         # retrieve is enqueued without waiting for the store: ordered on the device
-        t2 = c.retrieve(ids, slots_to_device(seq["load_slots"]), dst.dev, stream)
+        t2 = c.retrieve(ids, d_load, dst.dev, stream)
         c.wait(t)
         c.wait(t2)
         torch.cuda.synchronize()
@@ -130,8 +132,9 @@ def test_config3_llama3_70b_full_size_sampled_oracle():
     stream = torch.cuda.current_stream()
     with lmc.Context(g, n_chunks * g.chunk_bytes, staging_chunks=2) as c:
         ids = c.hash_chunks(seq["tokens"])
-        t = c.store(src.dev, slots_to_device(seq["store_slots"]), ids, stream)
-        t2 = c.retrieve(ids, slots_to_device(seq["load_slots"]), dst.dev, stream)
+        d_store, d_load = slots_to_device(seq["store_slots"]), slots_to_device(seq["load_slots"])
+        t = c.store(src.dev, d_store, ids, stream)
+        t2 = c.retrieve(ids, d_load, dst.dev, stream)
         c.wait(t2)
         torch.cuda.synchronize()
         for k in sample:
@@ -190,7 +193,8 @@ def test_config4_batched_multi_request_retrieve():
             slots.append(r["load_slots"])
             off.append(off[-1] + r["n_hit"])
         ids, slots = np.concatenate(ids), np.concatenate(slots)
-        t = c.retrieve_batch(off, ids, slots_to_device(slots), dst.dev, torch.cuda.current_stream())
+        d_slots = slots_to_device(slots)
+        t = c.retrieve_batch(off, ids, d_slots, dst.dev, torch.cuda.current_stream())
         c.wait(t)
         torch.cuda.synchronize()
         st = c.get_stats()
@@ -208,7 +212,7 @@ def test_config4_batched_multi_request_retrieve():
         bad_ids = ids.copy()
         bad_ids[len(bad_ids) // 2] ^= np.uint64(1)
         with pytest.raises(lmc.LMCError) as e:
-            c.retrieve_batch(off, bad_ids, slots_to_device(slots), dst.dev)
+            c.retrieve_batch(off, bad_ids, d_slots, dst.dev)
         assert e.value.status == lmc.LMC_ERR_MISS
         torch.cuda.synchronize()
         assert_layers_equal(dst.device_blocks_to_host(), before)
@@ -239,7 +243,8 @@ def test_store_semantics_against_oracle_store():
 
     def both_store(c, ids, sl):
         want_rc, _ = ora.store(kv.host, sl, ids)
-        got_rc = _status(lambda: c.store(kv.dev, slots_to_device(sl), ids, stream))
+        d_sl = slots_to_device(sl)
+        got_rc = _status(lambda: c.store(kv.dev, d_sl, ids, stream))
         assert got_rc == want_rc
         c.wait()
         for i in range(1, 12):
@@ -266,7 +271,8 @@ def test_store_semantics_against_oracle_store():
         assert_layers_equal(dst.device_blocks_to_host(), dst.host)
         assert c.get_stats()["retrieve_misses"] == 1
         # the same chunk twice in one retrieve, to different pages
-        t = c.retrieve([3, 3], slots_to_device(slots[2:4]), dst.dev, stream)
+        d_sl = slots_to_device(slots[2:4])
+        t = c.retrieve([3, 3], d_sl, dst.dev, stream)
         c.wait(t)
         assert ora.retrieve([3, 3], slots[2:4], dst.host) == 0
         assert_layers_equal(dst.device_blocks_to_host(), dst.host)
@@ -295,10 +301,11 @@ def test_partial_skip_store_launches_per_run_of_new_chunks():
     other = rng.permutation(g.n_slots)[:8 * g.CT].reshape(8, g.CT)
     with lmc.Context(g, 8 * g.chunk_bytes, staging_chunks=4) as c:
         ids = c.hash_chunks(toks)
-        c.store(kv.dev, slots_to_device(other[[0, 1, 4]]), ids[[0, 1, 4]], torch.cuda.current_stream())
+        d_other, d_slots = slots_to_device(other[[0, 1, 4]]), slots_to_device(slots)
+        c.store(kv.dev, d_other, ids[[0, 1, 4]], torch.cuda.current_stream())
         c.wait()
         c.reset_stats()
-        c.store(kv.dev, slots_to_device(slots), ids, torch.cuda.current_stream())
+        c.store(kv.dev, d_slots, ids, torch.cuda.current_stream())
         c.wait()
         st = c.get_stats()
         assert st["chunks_stored"] == 5 and st["chunks_skipped_dup"] == 3
