@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the KV store / retrieve path on one MI355X.
+
+One step is one pass of the whole path over one request of the Llama-3-8B-shaped
+configuration (32 layers, K and V, 8 KV heads x 128, bf16, 16-token pages in a pool of
+8192 blocks; a 4096-token prefix = 16 chunks of 256 tokens = 512 MiB of KV):
+  hash the tokens -> prefix lookup -> store every chunk (gather kernel + D2H per group,
+  pipelined) -> wait -> prefix lookup -> retrieve every chunk into freshly permuted
+  blocks (H2D + scatter kernel, pipelined) -> wait -> clear the chunks.
+Inputs are synthetic and resident in HBM before the timed region.  `value` is payload
+bytes moved (store + retrieve) per second of wall time.
+
+Also reported in the same JSON line:
+  roofline     the gather / scatter kernel launches of the timed steps, timed with HIP
+               events on the library's own streams, against the 8 TB/s HBM peak;
+               algorithmic bytes = 2 x chunk bytes per chunk (each byte read once and
+               written once)
+  device       both kernels alone over all 16 chunks in one launch, sources rotated so
+               the working set exceeds the 256 MB Infinity Cache, and a plain copy
+               kernel of the same size as the achievable ceiling
+  link         hipMemcpyAsync peak between the pinned pool and the GPU per direction,
+               and store / retrieve payload rate as a fraction of it
+  cpu_baseline the CPU oracle doing the same store + retrieve on the same 16 chunks,
+               chunks fanned out over host threads
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published
+WORKLOAD = "llama3_8b"
+
+
+def cpu_baseline(g, seq, budget_s=8.0):
+    """The oracle, as it stands, doing store (gather into a pool) and retrieve (scatter
+    from the pool) for the request's 16 chunks; chunks spread over threads."""
+    import dataclasses
+    from concurrent.futures import ThreadPoolExecutor
+    import oracle
+    from paper_2510_09665_amd import workloads as W
+    rng = W.rng_for(WORKLOAD, stream=7)
+    nb = seq["store_blocks"].size
+    gc = dataclasses.replace(g, NB=nb)                      # only the touched blocks
+    src = [W.payload_bytes(rng, g, gc.layer_bytes) for _ in range(g.L)]
+    dst = [np.zeros(gc.layer_bytes, dtype=np.uint8) for _ in range(g.L)]
+    n_chunks = seq["tokens"].size // g.CT
+    t = np.arange(n_chunks * g.CT, dtype=np.int64)          # block i of the request = compact block i
+    s_slots = t.reshape(n_chunks, g.CT)
+    d_slots = t[::-1].copy().reshape(n_chunks, g.CT)
+    pool = [None] * n_chunks
+
+    def one(i):
+        pool[i] = oracle.gather_chunk(gc, src, s_slots[i])
+        oracle.scatter_chunk(gc, pool[i], d_slots[i], dst)
+
+    cores = max(1, min(len(os.sched_getaffinity(0)), 16))
+    payload = 2 * n_chunks * g.chunk_bytes
+    out = {}
+    for label, n_thr in (("single", 1), ("all", cores)):
+        reps, t0 = 0, time.perf_counter()
+        with ThreadPoolExecutor(n_thr) as ex:
+            while True:
+                list(ex.map(one, range(n_chunks)))
+                reps += 1
+                dt = time.perf_counter() - t0
+                if dt > budget_s / 2 or reps >= 20:
+                    break
+        out[label] = payload * reps / dt / 1e9
+    return {
+        "value": round(out["all"], 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+        "single_thread_value": round(out["single"], 3),
+        "sample": "the same 16 chunks (512 MiB) stored and retrieved by oracle gather_chunk + "
+                  "scatter_chunk, one chunk per task on a thread pool; payload bytes / wall time",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--staging-chunks", type=int, default=4)
+    ap.add_argument("--num-staging", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", action="append", default=[], help="key=value for lmc_tune")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on one GPU only (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2510_09665_amd import lmc
+    from paper_2510_09665_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    g = W.geometry(WORKLOAD)
+    seq = W.sequence(WORKLOAD, g)
+    n_chunks = seq["tokens"].size // g.CT
+    payload_one_way = n_chunks * g.chunk_bytes
+
+    # paged KV resident in HBM: bf16 uniform(-1, 1) in the request's blocks
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(W.SEED_BASE + W.CONFIGS[WORKLOAD]["id"])
+    src, dst = [], []
+    sb = torch.from_numpy(seq["store_blocks"]).to(dev)
+    for _ in range(g.L):
+        a = torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev)
+        r = torch.rand((g.P, sb.numel(), g.block_stride // 2), device=dev, generator=gen) * 2 - 1
+        a.view(g.P, g.NB, g.block_stride)[:, sb] = \
+            r.to(torch.bfloat16).view(torch.uint8).view(g.P, sb.numel(), g.block_stride)
+        src.append(a)
+        dst.append(torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev))
+    d_store = torch.from_numpy(seq["store_slots"]).to(dev)
+    d_load = torch.from_numpy(seq["load_slots"]).to(dev)
+    stream = torch.cuda.current_stream()
+
+    ctx = lmc.Context(g, max(n_chunks * g.chunk_bytes, 1 << 30), num_staging=args.num_staging,
+                      staging_chunks=args.staging_chunks, device=0, flags=lmc.LMC_FLAG_TIMING)
+    for kv in args.tune:
+        k, v = kv.split("=")
+        ctx.tune(k, int(v))
+
+    def step():
+        ids = ctx.hash_chunks(seq["tokens"])
+        assert ctx.lookup(ids) == 0
+        t = ctx.store(src, d_store, ids, stream)
+        ctx.wait(t)
+        assert ctx.lookup(ids) == n_chunks
+        t = ctx.retrieve(ids, d_load, dst, stream)
+        ctx.wait(t)
+        ctx.clear(ids)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.reset_stats()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    st = ctx.get_stats()
+
+    # the result of the last step: every destination block equals its source block
+    lb = torch.from_numpy(seq["load_blocks"]).to(dev)
+    for l in range(g.L):
+        assert torch.equal(dst[l].view(g.P, g.NB, g.block_stride)[:, lb],
+                           src[l].view(g.P, g.NB, g.block_stride)[:, sb]), "round trip differs"
+
+    value = 2 * payload_one_way * args.steps / dt / 1e9
+    ms_per_step = dt / args.steps * 1e3
+
+    # dominant kernel of the timed region
+    def kern(kind):
+        n = st["timed_%s_launches" % kind]
+        ms = st["%s_ms" % kind]
+        moved = st["bytes_gathered" if kind == "gather" else "bytes_scattered"]
+        avg_ms = ms / max(n, 1)
+        return dict(launches=n, avg_us=round(avg_ms * 1e3, 2), chunks_per_launch=args.staging_chunks,
+                    bytes_per_launch=2 * moved // max(n, 1),
+                    hbm_gbps=round(2 * moved / max(ms, 1e-9) / 1e6, 1))
+    kg, ks = kern("gather"), kern("scatter")
+    dom_name, dom = ("gather", kg) if st["gather_ms"] >= st["scatter_ms"] else ("scatter", ks)
+    roofline = {
+        "bound": "hbm", "kernel": "move_rows<16," + ("gather" if dom_name == "gather" else "scatter") + ">",
+        "achieved": dom["hbm_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": round(dom["hbm_gbps"] / HBM_PEAK_GBPS, 4), "traffic": None,
+        "bytes_per_launch": dom["bytes_per_launch"], "avg_launch_us": dom["avg_us"],
+        "launches": dom["launches"], "gather": kg, "scatter": ks,
+    }
+
+    # store and retrieve separately, and the link peak
+    def timed(fn, reps=5):
+        best = 1e30
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            a = time.perf_counter()
+            fn()
+            best = min(best, time.perf_counter() - a)
+        return best
+    ids = ctx.hash_chunks(seq["tokens"])
+
+    def store_only():
+        ctx.clear(ids)
+        ctx.wait(ctx.store(src, d_store, ids, stream))
+    t_store = timed(store_only)
+    t_load = timed(lambda: ctx.wait(ctx.retrieve(ids, d_load, dst, stream)))
+    ctx.clear(ids)
+    h2d, d2h = ctx.measure_link(512 << 20, reps=4)
+    link = {
+        "h2d_peak_gbps": round(h2d, 2), "d2h_peak_gbps": round(d2h, 2),
+        "store_gbps": round(payload_one_way / t_store / 1e9, 2),
+        "retrieve_gbps": round(payload_one_way / t_load / 1e9, 2),
+        "store_frac_of_d2h_peak": round(payload_one_way / t_store / 1e9 / d2h, 4),
+        "retrieve_frac_of_h2d_peak": round(payload_one_way / t_load / 1e9 / h2d, 4),
+    }
+
+    # kernels alone: all 16 chunks per launch, rotating over 4 block sets (4 x 512 MiB of
+    # sources + 4 staging buffers) so that nothing is served from the Infinity Cache
+    n_rot = 4
+    rot_slots, stagings = [], []
+    for r in range(n_rot):
+        s = W.sequence(WORKLOAD, g, stream=10 + r)
+        rot_slots.append(torch.from_numpy(s["store_slots"]).to(dev))
+        stagings.append(torch.empty(payload_one_way, dtype=torch.uint8, device=dev))
+
+    def dev_time(fn, iters=12):
+        for r in range(n_rot):
+            fn(r)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(iters):
+            fn(i % n_rot)
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e-3
+    tg = dev_time(lambda r: ctx.gather(src, rot_slots[r], n_chunks, stagings[r], stream))
+    tsc = dev_time(lambda r: ctx.scatter(stagings[r], rot_slots[r], n_chunks, dst, stream))
+    tc = dev_time(lambda r: ctx.copy(stagings[r], stagings[(r + 1) % n_rot], payload_one_way, stream))
+    ctx.wait()
+    device = {
+        "chunks_per_launch": n_chunks, "bytes_per_launch": 2 * payload_one_way,
+        "gather_hbm_gbps": round(2 * payload_one_way / tg / 1e9, 1),
+        "scatter_hbm_gbps": round(2 * payload_one_way / tsc / 1e9, 1),
+        "copy_kernel_hbm_gbps": round(2 * payload_one_way / tc / 1e9, 1),
+        "gather_frac_of_hbm_peak": round(2 * payload_one_way / tg / 1e9 / HBM_PEAK_GBPS, 4),
+        "scatter_frac_of_hbm_peak": round(2 * payload_one_way / tsc / 1e9 / HBM_PEAK_GBPS, 4),
+    }
+    ctx.destroy()
+    del src, dst, stagings
+    torch.cuda.empty_cache()
+
+    out = {
+        "metric": "KV store/retrieve GB/s", "value": round(value, 3), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "Llama-3-8B-shaped KV: 32 layers, 8 KV heads, head_dim 128, bf16, "
+                               "block_size 16, pool of 8192 blocks; 4096-token prefix = 16 chunks of "
+                               "256 tokens; store all chunks then retrieve into freshly permuted blocks",
+                   "payload_bytes_per_step": 2 * payload_one_way, "chunk_bytes": g.chunk_bytes,
+                   "staging_chunks": args.staging_chunks, "num_staging": args.num_staging},
+        "roofline": roofline, "device": device, "link": link,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(g, seq)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

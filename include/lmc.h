@@ -247,9 +247,10 @@ lmc_status_t lmc_measure_link(lmc_ctx_t *ctx, uint64_t nbytes, int32_t reps,
 lmc_status_t lmc_copy(lmc_ctx_t *ctx, void *dst_dev, const void *src_dev, uint64_t nbytes,
                       void *stream);
 
-/* Launch-shape knobs for experiments; defaults are chosen per geometry at lmc_create.
- * Keys: "lp_per_block" (layer-planes walked by one workgroup), "nt_load", "nt_store"
- * (0/1: non-temporal hints).  Unknown key or out-of-range value: LMC_ERR_INVAL. */
+/* Launch knobs for experiments; the defaults are the measured best.  Keys: "nt_load",
+ * "nt_store" (0/1: non-temporal hints on the kernels' streaming accesses), "xcd_run"
+ * (consecutive tiles handed to one XCD, 0 = hardware round-robin).  Unknown key or
+ * out-of-range value: LMC_ERR_INVAL. */
 lmc_status_t lmc_tune(lmc_ctx_t *ctx, const char *key, int64_t value);
 
 const char *lmc_strerror(lmc_status_t status);

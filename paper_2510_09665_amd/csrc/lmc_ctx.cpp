@@ -52,8 +52,6 @@ struct lmc_ctx {
     lmc_config_t cfg{};
     lmc::KernelGeom kg{};
     lmc::LaunchShape shape{};
-    uint32_t tune_lp_per_block = 0;  // 0 = choose per launch
-    uint32_t target_blocks = 4096;
     int64_t chunk_bytes = 0;
     int64_t n_pool_slots = 0;
     uint8_t *pool = nullptr;
@@ -145,20 +143,19 @@ lmc_status_t derive_geometry(const lmc_kv_geom_t &g, lmc::KernelGeom *k, int64_t
     k->block_stride = g.block_stride;
     k->token_stride = g.token_stride;
     k->run_stride = row_contiguous ? 0 : g.head_stride;
-    k->row_stride_lp = uint64_t(g.chunk_tokens) * uint64_t(row);
-    k->chunk_bytes = k->row_stride_lp * uint64_t(g.num_layers) * uint64_t(g.num_planes);
+    k->plane_bytes = uint64_t(g.chunk_tokens) * uint64_t(row);
+    k->chunk_bytes = k->plane_bytes * uint64_t(g.num_layers) * uint64_t(g.num_planes);
     k->n_slots = uint32_t(n_slots);
-    k->block_size = uint32_t(g.block_size);
-    k->block_shift = -1;
-    for (int sh = 0; sh < 31; sh++)
-        if ((int64_t(1) << sh) == g.block_size) k->block_shift = sh;
     k->chunk_tokens = uint32_t(g.chunk_tokens);
+    k->vec_per_plane = uint32_t(pairs);
     k->runs_per_row = row_contiguous ? 1u : uint32_t(g.num_heads);
-    k->vec_per_run = uint32_t((row_contiguous ? row : run) / vec);
-    k->vec_per_row = uint32_t(row / vec);
-    k->pairs_per_chunk = uint32_t(pairs);
     k->n_layer_planes = uint32_t(g.num_layers * g.num_planes);
     k->vec = uint32_t(vec);
+    k->by_tiles_per_plane = lmc::make_fastdiv(uint32_t((pairs + 255) / 256));
+    k->by_layer_planes = lmc::make_fastdiv(k->n_layer_planes);
+    k->by_vec_per_row = lmc::make_fastdiv(uint32_t(row / vec));
+    k->by_vec_per_run = lmc::make_fastdiv(uint32_t((row_contiguous ? row : run) / vec));
+    k->by_block_size = lmc::make_fastdiv(uint32_t(g.block_size));
     *chunk_bytes = int64_t(k->chunk_bytes);
     return LMC_OK;
 }
@@ -173,24 +170,6 @@ lmc_status_t build_layer_ptrs(const lmc_ctx *c, void *const *kv_layers, lmc::Lay
             out->p[l * g.num_planes + p] = base + int64_t(p) * g.plane_stride;
     }
     return LMC_OK;
-}
-
-lmc::LaunchShape shape_for(const lmc_ctx *c, uint32_t n_chunks) {
-    lmc::LaunchShape s = c->shape;
-    const uint32_t lp = c->kg.n_layer_planes;
-    if (c->tune_lp_per_block > 0) {
-        s.lp_per_block = std::min(c->tune_lp_per_block, lp);
-        return s;
-    }
-    // enough workgroups to fill 256 CUs several times over, but never fewer than one
-    // unrolled step (8 layer-planes) per workgroup
-    const uint64_t xb = (uint64_t(n_chunks) * c->kg.pairs_per_chunk + 255) / 256;
-    uint64_t groups = (c->target_blocks + xb - 1) / std::max<uint64_t>(xb, 1);
-    groups = std::max<uint64_t>(1, std::min<uint64_t>(groups, (lp + 7) / 8));
-    uint32_t per = uint32_t((lp + groups - 1) / groups);
-    per = (per + 7) / 8 * 8;
-    s.lp_per_block = std::min(per, lp);
-    return s;
 }
 
 // Finish every operation whose last device step has completed: drop its in-flight
@@ -271,7 +250,7 @@ lmc_status_t timed_launch(lmc_ctx *c, bool gather, const lmc::LayerPtrs &ptrs,
         if (rc != LMC_OK) return rc;
         HIPCHK(c, hipEventRecord(e0, stream));
     }
-    const lmc::LaunchShape s = shape_for(c, n_chunks);
+    const lmc::LaunchShape &s = c->shape;
     if (gather) {
         HIPCHK(c, lmc::launch_gather(c->kg, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream));
         c->stats.gather_launches++;
@@ -457,9 +436,9 @@ lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out) {
         delete c;
         return rc;
     }
-    c->shape.lp_per_block = 8;
     c->shape.nt_load = true;
-    c->shape.nt_store = false;
+    c->shape.nt_store = true;
+    c->shape.xcd_run = 32;
     c->has_device = cfg->device != LMC_DEVICE_NONE;
     const size_t pool_bytes = size_t(c->n_pool_slots) * size_t(c->chunk_bytes);
     if (!c->has_device) {
@@ -865,12 +844,9 @@ lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
     if (!c || !key || value < 0) return LMC_ERR_INVAL;
     std::lock_guard<std::mutex> lock(c->mu);
     const std::string k(key);
-    if (k == "lp_per_block") {
-        if (value > lmc::kMaxLayerPlanes) return LMC_ERR_INVAL;
-        c->tune_lp_per_block = uint32_t(value);
-    } else if (k == "target_blocks") {
-        if (value < 1 || value > (1 << 24)) return LMC_ERR_INVAL;
-        c->target_blocks = uint32_t(value);
+    if (k == "xcd_run") {
+        if (value > (1 << 20)) return LMC_ERR_INVAL;
+        c->shape.xcd_run = uint32_t(value);
     } else if (k == "nt_load" && value <= 1) {
         c->shape.nt_load = value != 0;
     } else if (k == "nt_store" && value <= 1) {

@@ -2,27 +2,27 @@
 // and scatter (load direction) that the paper's section 5.1 places between the
 // engine's pages and the contiguous streaming GPU buffer, plus small helpers.
 //
-// Both kernels are pure byte movement and HBM-bound.  Work split:
-//   - a lane owns one `vec`-byte vector of one token's row: the pair (token t, vector w)
-//     of chunk c.  It reads the token's slot once, turns it into a byte offset inside
-//     a layer-plane once, and then walks the layer-planes of its workgroup's range:
-//     per step one scalar load of the plane's base pointer, one 64-bit add, one
-//     16-byte load and one 16-byte store.  The slot lookup and the division by the
-//     block size are amortised over every layer and plane.
-//   - consecutive lanes own consecutive vectors of a row and then the next token, so a
-//     wavefront's access is 1 KiB contiguous on the chunk side and, on the page side,
-//     contiguous for as long as the row (or head run) and the page go on.
-//   - kUnroll independent loads are issued before the first store, which is what keeps
-//     enough bytes in flight per CU to cover HBM latency.
-//   - grid = (pairs / 256, layer-plane groups): the second dimension exists so that a
-//     launch over one chunk still gives several workgroups per CU.
+// Both kernels are pure byte movement and HBM-bound; there is no reuse, so neither LDS
+// nor MFMA has a role.  What was measured to matter on this part, and shapes the code:
+//   - One 16-byte vector per lane and a very large grid.  Occupancy, not unrolling,
+//     supplies the bytes in flight: with a handful of VGPRs every SIMD holds its full
+//     8 wavefronts.  Unrolled variants that walk several layer-planes per lane were
+//     10-15 % slower: their accesses sit power-of-two distances apart (planes of a
+//     chunk, layers of the cache) and collide on memory channels.
+//   - Workgroup order follows the chunk buffer: tile, then layer-plane, then chunk.
+//     The contiguous side of the copy is then swept linearly by the launch as a
+//     whole, and the paged side is touched page by page (a page's tokens are
+//     consecutive rows).  Ordering by layer-plane first cost 5-10 %.
+//   - Non-temporal loads and stores: nothing is read twice.
+//   - Index arithmetic (which chunk, plane, token, vector; slot -> block and offset)
+//     uses multiply-high division by host-precomputed constants; the workgroup-level
+//     part is wave-uniform and runs on the scalar unit.
 #include "lmc_kernels.hpp"
 
 namespace lmc {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kUnroll = 8;
 
 template <int N> struct VecOf;
 template <> struct VecOf<16> { typedef unsigned int type __attribute__((ext_vector_type(4))); };
@@ -40,80 +40,56 @@ template <typename V, bool NT> __device__ __forceinline__ void store_vec(uint8_t
     else *reinterpret_cast<V *>(p) = v;
 }
 
-// One pass of the path's copy in either direction.
-//   GATHER: chunk[c][lp][t][w] = valid ? page(lp, slot)[w] : 0
-//   else  : if (valid) page(lp, slot)[w] = chunk[c][lp][t][w]
+// One pass of the path's copy in either direction; lane = one vector r of plane lp of
+// chunk c, token t = r / vec_per_row:
+//   GATHER: chunk[c][lp][r] = valid(slot[c][t]) ? page(lp, slot[c][t])[r % vec_per_row] : 0
+//   else  : if valid(slot[c][t]):  page(lp, slot[c][t])[r % vec_per_row] = chunk[c][lp][r]
 template <int VEC, bool GATHER, bool NT_LD, bool NT_ST>
 __global__ __launch_bounds__(kThreads) void move_rows(const KernelGeom g, const LayerPtrs layers,
                                                       const int64_t *__restrict__ slot_mapping,
-                                                      uint32_t n_pairs, uint8_t *staging,
-                                                      int32_t *bad_flag, uint32_t lp_per_block) {
+                                                      uint8_t *staging, int32_t *bad_flag,
+                                                      uint32_t n_blocks_permuted, uint32_t xcd_shift) {
     typedef typename VecOf<VEC>::type V;
-    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
-    if (i >= n_pairs) return;
-    const uint32_t c = i / g.pairs_per_chunk;
-    const uint32_t r = i - c * g.pairs_per_chunk;  // vector index inside one layer-plane of the chunk
-    const uint32_t t = r / g.vec_per_row;
-    const uint32_t w = r - t * g.vec_per_row;
+    uint32_t blk = blockIdx.x;
+    if (blk < n_blocks_permuted) {
+        // hardware deals consecutive workgroup ids to the 8 XCDs in turn; give each XCD
+        // runs of 2^xcd_shift consecutive tiles instead of every eighth tile.  This is a
+        // permutation inside every group of 8 << xcd_shift ids, and n_blocks_permuted is
+        // a multiple of that, so the result stays below it.
+        const uint32_t xcd = blk & 7u, local = blk >> 3;
+        const uint32_t grp = local >> xcd_shift;
+        blk = (((grp << 3) + xcd) << xcd_shift) + (local & ((1u << xcd_shift) - 1u));
+    }
+    const uint32_t q = g.by_tiles_per_plane.div(blk);
+    const uint32_t tile = blk - q * g.by_tiles_per_plane.d;
+    const uint32_t c = g.by_layer_planes.div(q);
+    const uint32_t lp = q - c * g.n_layer_planes;
+    const uint32_t r = tile * kThreads + threadIdx.x;
+    if (r >= g.vec_per_plane) return;
+    const uint32_t t = g.by_vec_per_row.div(r);
+    const uint32_t w = r - t * g.by_vec_per_row.d;
 
     const int64_t s = slot_mapping[uint64_t(c) * g.chunk_tokens + t];
     const bool valid = uint64_t(s) < uint64_t(g.n_slots);  // negative wraps to huge
     if (s >= int64_t(g.n_slots)) *bad_flag = 1;
     const uint32_t su = valid ? uint32_t(s) : 0u;  // slot 0 is always inside the pages
-    uint32_t b, o;
-    if (g.block_shift >= 0) {
-        b = su >> g.block_shift;
-        o = su & (g.block_size - 1u);
-    } else {
-        b = su / g.block_size;
-        o = su - b * g.block_size;
-    }
+    const uint32_t b = g.by_block_size.div(su);
+    const uint32_t o = su - b * g.by_block_size.d;
     uint32_t run = 0, dv = w;
     if (g.runs_per_row > 1) {
-        run = w / g.vec_per_run;
-        dv = w - run * g.vec_per_run;
+        run = g.by_vec_per_run.div(w);
+        dv = w - run * g.by_vec_per_run.d;
     }
-    const int64_t page_off = int64_t(b) * g.block_stride + int64_t(o) * g.token_stride +
-                             int64_t(run) * g.run_stride + int64_t(dv) * VEC;
-
-    const uint32_t lp0 = blockIdx.y * lp_per_block;
-    const uint32_t lp1 = min(lp0 + lp_per_block, g.n_layer_planes);
-    uint8_t *st = staging + uint64_t(c) * g.chunk_bytes + uint64_t(lp0) * g.row_stride_lp +
+    uint8_t *page = layers.p[lp] + int64_t(b) * g.block_stride + int64_t(o) * g.token_stride +
+                    int64_t(run) * g.run_stride + int64_t(dv) * VEC;
+    uint8_t *st = staging + uint64_t(c) * g.chunk_bytes + uint64_t(lp) * g.plane_bytes +
                   uint64_t(r) * VEC;
-
-    uint32_t lp = lp0;
-    for (; lp + kUnroll <= lp1; lp += kUnroll) {
-        V v[kUnroll];
-        if (GATHER) {
-#pragma unroll
-            for (int u = 0; u < kUnroll; u++)
-                v[u] = load_vec<V, NT_LD>(layers.p[lp + u] + page_off);
-#pragma unroll
-            for (int u = 0; u < kUnroll; u++) {
-                if (!valid) v[u] = V(0);
-                store_vec<V, NT_ST>(st + uint64_t(u) * g.row_stride_lp, v[u]);
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < kUnroll; u++)
-                v[u] = load_vec<V, NT_LD>(st + uint64_t(u) * g.row_stride_lp);
-            if (valid) {
-#pragma unroll
-                for (int u = 0; u < kUnroll; u++)
-                    store_vec<V, NT_ST>(layers.p[lp + u] + page_off, v[u]);
-            }
-        }
-        st += uint64_t(kUnroll) * g.row_stride_lp;
-    }
-    for (; lp < lp1; lp++) {
-        if (GATHER) {
-            V v = load_vec<V, NT_LD>(layers.p[lp] + page_off);
-            if (!valid) v = V(0);
-            store_vec<V, NT_ST>(st, v);
-        } else if (valid) {
-            store_vec<V, NT_ST>(layers.p[lp] + page_off, load_vec<V, NT_LD>(st));
-        }
-        st += g.row_stride_lp;
+    if (GATHER) {
+        V v = load_vec<V, NT_LD>(page);
+        if (!valid) v = V(0);
+        store_vec<V, NT_ST>(st, v);
+    } else if (valid) {
+        store_vec<V, NT_ST>(page, load_vec<V, NT_LD>(st));
     }
 }
 
@@ -129,22 +105,12 @@ __global__ __launch_bounds__(kThreads) void check_slots(const int64_t *__restric
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-// Streaming copy: 4 independent 16-byte loads per lane per step, grid-stride.
+// Streaming copy, one 16-byte vector per lane, non-temporal both ways: the fastest of
+// the plain-copy shapes measured on this part.
 __global__ __launch_bounds__(kThreads) void copy_bytes(u32x4 *__restrict__ dst,
                                                        const u32x4 *__restrict__ src, uint64_t n_vec) {
-    const uint64_t step = uint64_t(gridDim.x) * kThreads;
-    uint64_t i = uint64_t(blockIdx.x) * kThreads + threadIdx.x;
-    for (; i + 3 * step < n_vec; i += 4 * step) {
-        u32x4 a = __builtin_nontemporal_load(src + i);
-        u32x4 b = __builtin_nontemporal_load(src + i + step);
-        u32x4 c = __builtin_nontemporal_load(src + i + 2 * step);
-        u32x4 d = __builtin_nontemporal_load(src + i + 3 * step);
-        __builtin_nontemporal_store(a, dst + i);
-        __builtin_nontemporal_store(b, dst + i + step);
-        __builtin_nontemporal_store(c, dst + i + 2 * step);
-        __builtin_nontemporal_store(d, dst + i + 3 * step);
-    }
-    for (; i < n_vec; i += step) dst[i] = src[i];
+    const uint64_t i = uint64_t(blockIdx.x) * kThreads + threadIdx.x;
+    if (i < n_vec) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 __global__ __launch_bounds__(kThreads) void fill_bytes(uint8_t *dst, uint8_t value, uint64_t n) {
@@ -157,14 +123,17 @@ template <int VEC, bool GATHER>
 hipError_t launch_move_v(const KernelGeom &g, const LaunchShape &s, const LayerPtrs &layers,
                          const int64_t *slot_mapping, uint32_t n_chunks, uint8_t *staging,
                          int32_t *bad_flag, hipStream_t stream) {
-    const uint32_t n_pairs = n_chunks * g.pairs_per_chunk;
-    const uint32_t lpb = s.lp_per_block < 1 ? 1 : s.lp_per_block;
-    dim3 grid((n_pairs + kThreads - 1) / kThreads, (g.n_layer_planes + lpb - 1) / lpb);
-    dim3 block(kThreads);
-    if (grid.x == 0) return hipSuccess;
+    const uint32_t n_blocks = n_chunks * g.n_layer_planes * g.by_tiles_per_plane.d;
+    if (n_blocks == 0) return hipSuccess;
+    uint32_t shift = 0, permuted = 0;
+    if (s.xcd_run > 0) {
+        while ((2u << shift) <= s.xcd_run) shift++;                      // floor(log2(xcd_run))
+        permuted = n_blocks & ~((8u << shift) - 1u);                     // the tail keeps its order
+    }
+    dim3 grid(n_blocks), block(kThreads);
 #define LMC_GO(LD, ST)                                                                          \
     hipLaunchKernelGGL((move_rows<VEC, GATHER, LD, ST>), grid, block, 0, stream, g, layers,     \
-                       slot_mapping, n_pairs, staging, bad_flag, lpb)
+                       slot_mapping, staging, bad_flag, permuted, shift)
     if (s.nt_load && s.nt_store) LMC_GO(true, true);
     else if (s.nt_load) LMC_GO(true, false);
     else if (s.nt_store) LMC_GO(false, true);
@@ -189,9 +158,24 @@ hipError_t launch_move(const KernelGeom &g, const LaunchShape &s, const LayerPtr
 
 }  // namespace
 
+FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f;
+    f.d = d;
+    if (d <= 1) {
+        f.mul = 0;
+        f.shift = 0;
+        return f;
+    }
+    uint32_t l = 0;
+    while ((uint64_t(1) << l) < d) l++;
+    f.mul = uint32_t((uint64_t(1) << (31 + l)) / d + 1);
+    f.shift = l - 1;
+    return f;
+}
+
 uint32_t max_chunks_per_launch(const KernelGeom &g) {
-    // the pair index and the x grid dimension are 32-bit
-    return uint32_t(0x7FFFFFFFu / g.pairs_per_chunk);
+    // the workgroup index is 32-bit and must stay below 2^31 for the fast division
+    return uint32_t(0x7FFFFFFFu / (uint64_t(g.n_layer_planes) * g.by_tiles_per_plane.d));
 }
 
 hipError_t launch_gather(const KernelGeom &g, const LaunchShape &s, const LayerPtrs &layers,
@@ -219,11 +203,13 @@ hipError_t launch_check_slots(const int64_t *slot_mapping, uint64_t n, uint32_t 
 
 hipError_t launch_copy(uint8_t *dst, const uint8_t *src, uint64_t nbytes, hipStream_t stream) {
     const uint64_t n_vec = nbytes / 16;
-    if (n_vec == 0) return hipSuccess;
-    uint64_t blocks = (n_vec + kThreads * 4 - 1) / (kThreads * 4);
-    if (blocks > 256 * 32) blocks = 256 * 32;
-    hipLaunchKernelGGL(copy_bytes, dim3(uint32_t(blocks)), dim3(kThreads), 0, stream,
-                       reinterpret_cast<u32x4 *>(dst), reinterpret_cast<const u32x4 *>(src), n_vec);
+    const uint64_t per_launch = uint64_t(0x7FFFFFFFu) * kThreads;   // grid.x limit
+    for (uint64_t v0 = 0; v0 < n_vec; v0 += per_launch) {
+        const uint64_t n = n_vec - v0 < per_launch ? n_vec - v0 : per_launch;
+        hipLaunchKernelGGL(copy_bytes, dim3(uint32_t((n + kThreads - 1) / kThreads)), dim3(kThreads),
+                           0, stream, reinterpret_cast<u32x4 *>(dst) + v0,
+                           reinterpret_cast<const u32x4 *>(src) + v0, n);
+    }
     return hipGetLastError();
 }
 

@@ -19,27 +19,44 @@ struct LayerPtrs {
     uint8_t *p[kMaxLayerPlanes];
 };
 
+// Division of a 31-bit value by a run-time constant as multiply-high and shift.
+// With l = ceil(log2 d), mul = floor(2^(31+l) / d) + 1 and shift = l - 1, the quotient
+// mulhi(n, mul) >> shift is exact for every n < 2^31 (the error term n / 2^(31+l) stays
+// below 1/d).  d == 1 is flagged by mul == 0.
+struct FastDiv {
+    uint32_t mul, shift, d;
+#if defined(__HIPCC__)
+    __host__ __device__
+#endif
+    uint32_t div(uint32_t n) const {
+        return mul == 0 ? n : uint32_t((uint64_t(n) * mul) >> 32) >> shift;
+    }
+};
+FastDiv make_fastdiv(uint32_t d);  // d >= 1
+
 // What the gather / scatter kernels need to know, precomputed on the host.
-// A "row" is one token of one layer and plane in the chunk: vec_per_row vectors of
-// `vec` bytes.  In the pages a row is runs_per_row runs of vec_per_run vectors; when a
-// token's heads are contiguous the host folds them into a single run.
+// A "plane" is one (layer, plane) of one chunk: chunk_tokens rows of vec_per_row vectors
+// of `vec` bytes, contiguous in the chunk.  In the pages a row is runs_per_row runs of
+// vec_per_run vectors; when a token's heads are contiguous the host folds them into a
+// single run.  A workgroup copies one tile of 256 consecutive vectors of a plane.
 struct KernelGeom {
     int64_t block_stride, token_stride, run_stride;  // bytes
-    uint64_t row_stride_lp;   // chunk_tokens * row bytes: distance between layer-planes in a chunk
+    uint64_t plane_bytes;     // chunk_tokens * row bytes
     uint64_t chunk_bytes;
     uint32_t n_slots;         // num_blocks * block_size
-    uint32_t block_size;
-    int32_t block_shift;      // log2(block_size), or -1 when it is not a power of two
     uint32_t chunk_tokens;
-    uint32_t vec_per_run, runs_per_row, vec_per_row;
-    uint32_t pairs_per_chunk; // chunk_tokens * vec_per_row
+    uint32_t vec_per_plane;   // chunk_tokens * vec_per_row
+    uint32_t runs_per_row;
     uint32_t n_layer_planes;  // num_layers * num_planes
     uint32_t vec;             // bytes per lane access: 16, 8, 4, 2 or 1
+    FastDiv by_tiles_per_plane, by_layer_planes, by_vec_per_row, by_vec_per_run, by_block_size;
 };
 
 struct LaunchShape {
-    uint32_t lp_per_block;    // layer-planes walked by one workgroup
-    bool nt_load, nt_store;
+    bool nt_load, nt_store;   // non-temporal hints on the streaming loads / stores
+    uint32_t xcd_run;         // workgroup ids are permuted so that each of the 8 XCDs
+                              // takes runs of this many (rounded down to a power of
+                              // two) consecutive tiles; 0 = off
 };
 
 // pages -> chunks [first_chunk, first_chunk + n_chunks) of the slot mapping, written
@@ -56,7 +73,7 @@ hipError_t launch_check_slots(const int64_t *slot_mapping, uint64_t n, uint32_t 
 hipError_t launch_copy(uint8_t *dst, const uint8_t *src, uint64_t nbytes, hipStream_t stream);
 hipError_t launch_fill(uint8_t *dst, uint8_t value, uint64_t nbytes, hipStream_t stream);
 
-// largest number of chunks one launch may cover (32-bit pair index)
+// largest number of chunks one launch may cover (32-bit workgroup index)
 uint32_t max_chunks_per_launch(const KernelGeom &g);
 
 }  // namespace lmc

@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 # shapes chosen to cross every kernel path: 16-byte vectors with contiguous rows,
 # per-head runs (HND), padded blocks, rows that are not a multiple of a wavefront
 # (MLA: 72 and 36 vectors), narrow vectors (8/4/2/1 bytes), a block size that is not a
-# power of two, a layer-plane count that is not a multiple of the unroll, P=1 and P=2.
+# power of two, planes whose size is not a multiple of a 256-vector tile, P=1 and P=2.
 SHAPES = {
     "tiny_cfg1": dict(L=2, P=2, H=4, D=64, e=2, BS=16, NB=64, CT=256),
     "hnd": dict(L=5, P=2, H=8, D=64, e=2, BS=16, NB=40, CT=64, layout="HND"),
@@ -35,8 +35,8 @@ def _ctx(g, **kw):
 
 
 @pytest.mark.parametrize("name", list(SHAPES))
-@pytest.mark.parametrize("lp_per_block", [0, 3])
-def test_gather_and_scatter_match_oracle(name, lp_per_block):
+@pytest.mark.parametrize("xcd_run", [None, 0, 4])
+def test_gather_and_scatter_match_oracle(name, xcd_run):
     import torch
     from gpu_util import PagedKV, assert_layers_equal, slots_to_device
     g = W.KVGeometry(**SHAPES[name])
@@ -50,8 +50,8 @@ def test_gather_and_scatter_match_oracle(name, lp_per_block):
     src = PagedKV(g, np.arange(g.NB), rng)
     d_slots = slots_to_device(slots)
     with _ctx(g) as c:
-        if lp_per_block:
-            c.tune("lp_per_block", lp_per_block)
+        if xcd_run is not None:
+            c.tune("xcd_run", xcd_run)
         staging = torch.full((n_chunks * g.chunk_bytes + 64,), 0xCD, dtype=torch.uint8, device="cuda")
         c.gather(src.dev, d_slots, n_chunks, staging, torch.cuda.current_stream())
         torch.cuda.synchronize()
