@@ -87,11 +87,17 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--staging-chunks", type=int, default=4)
+    ap.add_argument("--staging-chunks", type=int, default=8)
     ap.add_argument("--num-staging", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--legs", default="pipeline,link,device,cpu",
+                    help="comma list of pipeline (always run), link, device, cpu: the extra "
+                         "measurements to make; profiling runs use a subset")
     ap.add_argument("--tune", action="append", default=[], help="key=value for lmc_tune")
     args = ap.parse_args()
+    legs = set(args.legs.split(","))
+    if args.no_cpu_baseline:
+        legs.discard("cpu")
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on one GPU only (no sharding, no collectives); "
               "run with --gpus 1", file=sys.stderr)
@@ -191,55 +197,61 @@ def main():
             best = min(best, time.perf_counter() - a)
         return best
     ids = ctx.hash_chunks(seq["tokens"])
-
-    def store_only():
+    link = None
+    if "link" in legs:
+        def store_only():
+            ctx.clear(ids)
+            ctx.wait(ctx.store(src, d_store, ids, stream))
+        t_store = timed(store_only)
+        t_load = timed(lambda: ctx.wait(ctx.retrieve(ids, d_load, dst, stream)))
         ctx.clear(ids)
-        ctx.wait(ctx.store(src, d_store, ids, stream))
-    t_store = timed(store_only)
-    t_load = timed(lambda: ctx.wait(ctx.retrieve(ids, d_load, dst, stream)))
-    ctx.clear(ids)
-    h2d, d2h = ctx.measure_link(512 << 20, reps=4)
-    link = {
-        "h2d_peak_gbps": round(h2d, 2), "d2h_peak_gbps": round(d2h, 2),
-        "store_gbps": round(payload_one_way / t_store / 1e9, 2),
-        "retrieve_gbps": round(payload_one_way / t_load / 1e9, 2),
-        "store_frac_of_d2h_peak": round(payload_one_way / t_store / 1e9 / d2h, 4),
-        "retrieve_frac_of_h2d_peak": round(payload_one_way / t_load / 1e9 / h2d, 4),
-    }
+        h2d, d2h = ctx.measure_link(512 << 20, reps=4)
+        link = {
+            "h2d_peak_gbps": round(h2d, 2), "d2h_peak_gbps": round(d2h, 2),
+            "store_gbps": round(payload_one_way / t_store / 1e9, 2),
+            "retrieve_gbps": round(payload_one_way / t_load / 1e9, 2),
+            "store_frac_of_d2h_peak": round(payload_one_way / t_store / 1e9 / d2h, 4),
+            "retrieve_frac_of_h2d_peak": round(payload_one_way / t_load / 1e9 / h2d, 4),
+        }
 
     # kernels alone: all 16 chunks per launch, rotating over 4 block sets (4 x 512 MiB of
     # sources + 4 staging buffers) so that nothing is served from the Infinity Cache
-    n_rot = 4
-    rot_slots, stagings = [], []
-    for r in range(n_rot):
-        s = W.sequence(WORKLOAD, g, stream=10 + r)
-        rot_slots.append(torch.from_numpy(s["store_slots"]).to(dev))
-        stagings.append(torch.empty(payload_one_way, dtype=torch.uint8, device=dev))
-
-    def dev_time(fn, iters=12):
+    device = None
+    if "device" in legs:
+        n_rot = 4
+        rot_slots, stagings = [], []
         for r in range(n_rot):
-            fn(r)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for i in range(iters):
-            fn(i % n_rot)
-        e1.record(stream)
-        e1.synchronize()
-        return e0.elapsed_time(e1) / iters * 1e-3
-    tg = dev_time(lambda r: ctx.gather(src, rot_slots[r], n_chunks, stagings[r], stream))
-    tsc = dev_time(lambda r: ctx.scatter(stagings[r], rot_slots[r], n_chunks, dst, stream))
-    tc = dev_time(lambda r: ctx.copy(stagings[r], stagings[(r + 1) % n_rot], payload_one_way, stream))
-    ctx.wait()
-    device = {
-        "chunks_per_launch": n_chunks, "bytes_per_launch": 2 * payload_one_way,
-        "gather_hbm_gbps": round(2 * payload_one_way / tg / 1e9, 1),
-        "scatter_hbm_gbps": round(2 * payload_one_way / tsc / 1e9, 1),
-        "copy_kernel_hbm_gbps": round(2 * payload_one_way / tc / 1e9, 1),
-        "gather_frac_of_hbm_peak": round(2 * payload_one_way / tg / 1e9 / HBM_PEAK_GBPS, 4),
-        "scatter_frac_of_hbm_peak": round(2 * payload_one_way / tsc / 1e9 / HBM_PEAK_GBPS, 4),
-    }
+            s = W.sequence(WORKLOAD, g, stream=10 + r)
+            rot_slots.append(torch.from_numpy(s["store_slots"]).to(dev))
+            stagings.append(torch.empty(payload_one_way, dtype=torch.uint8, device=dev))
+
+        def dev_time(fn, iters=12):
+            for r in range(n_rot):
+                fn(r)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for i in range(iters):
+                fn(i % n_rot)
+            e1.record(stream)
+            e1.synchronize()
+            return e0.elapsed_time(e1) / iters * 1e-3
+        tg = dev_time(lambda r: ctx.gather(src, rot_slots[r], n_chunks, stagings[r], stream))
+        tsc = dev_time(lambda r: ctx.scatter(stagings[r], rot_slots[r], n_chunks, dst, stream))
+        tc = dev_time(lambda r: ctx.copy(stagings[r], stagings[(r + 1) % n_rot], payload_one_way, stream))
+        ctx.wait()
+        device = {
+            "chunks_per_launch": n_chunks, "bytes_per_launch": 2 * payload_one_way,
+            "gather_us": round(tg * 1e6, 1), "scatter_us": round(tsc * 1e6, 1),
+            "copy_kernel_us": round(tc * 1e6, 1),
+            "gather_hbm_gbps": round(2 * payload_one_way / tg / 1e9, 1),
+            "scatter_hbm_gbps": round(2 * payload_one_way / tsc / 1e9, 1),
+            "copy_kernel_hbm_gbps": round(2 * payload_one_way / tc / 1e9, 1),
+            "gather_frac_of_hbm_peak": round(2 * payload_one_way / tg / 1e9 / HBM_PEAK_GBPS, 4),
+            "scatter_frac_of_hbm_peak": round(2 * payload_one_way / tsc / 1e9 / HBM_PEAK_GBPS, 4),
+        }
+        del stagings
     ctx.destroy()
-    del src, dst, stagings
+    del src, dst
     torch.cuda.empty_cache()
 
     out = {
@@ -252,9 +264,13 @@ def main():
                                "256 tokens; store all chunks then retrieve into freshly permuted blocks",
                    "payload_bytes_per_step": 2 * payload_one_way, "chunk_bytes": g.chunk_bytes,
                    "staging_chunks": args.staging_chunks, "num_staging": args.num_staging},
-        "roofline": roofline, "device": device, "link": link,
+        "roofline": roofline,
     }
-    if not args.no_cpu_baseline:
+    if device:
+        out["device"] = device
+    if link:
+        out["link"] = link
+    if "cpu" in legs:
         out["cpu_baseline"] = cpu_baseline(g, seq)
     print(json.dumps(out), flush=True)
 

@@ -106,7 +106,9 @@ typedef struct {
     uint64_t host_pool_bytes; /* pinned pool; holds host_pool_bytes / chunk_bytes chunks */
     int32_t num_staging;      /* staging buffers per direction, >= 2 (double buffering) */
     int32_t staging_chunks;   /* chunks per staging buffer, >= 1: one kernel launch covers
-                                 up to this many chunks */
+                                 up to this many chunks.  The group at the exposed end of
+                                 a pipeline (first of a store, last of a retrieve) is a
+                                 single chunk. */
     int32_t device;           /* HIP device ordinal, or LMC_DEVICE_NONE */
     uint32_t flags;           /* LMC_FLAG_* */
     uint64_t hash_seed;       /* "hash before the first chunk" of lmc_hash_chunks */

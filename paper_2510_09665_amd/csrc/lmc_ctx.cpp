@@ -52,6 +52,7 @@ struct lmc_ctx {
     lmc_config_t cfg{};
     lmc::KernelGeom kg{};
     lmc::LaunchShape shape{};
+    int64_t edge_chunks = 1;  // size of the group at the exposed end of a pipeline; 0 = no special group
     int64_t chunk_bytes = 0;
     int64_t n_pool_slots = 0;
     uint8_t *pool = nullptr;
@@ -344,8 +345,12 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
 
     Ring &ring = c->load_ring;
     const int64_t per = c->cfg.staging_chunks;
-    for (int64_t i0 = 0; i0 < n_chunks; i0 += per) {
-        const int64_t k = std::min(per, n_chunks - i0);
+    // The link is the bottleneck and every scatter but the last hides behind the next
+    // copy, so the last group is a single chunk: only its scatter is exposed.
+    const int64_t edge = std::min<int64_t>(c->edge_chunks, per);
+    const int64_t body = (edge > 0 && n_chunks > edge) ? n_chunks - edge : n_chunks;
+    for (int64_t i0 = 0, k = 0; i0 < n_chunks; i0 += k) {
+        k = i0 < body ? std::min(per, body - i0) : n_chunks - i0;
         const size_t b = size_t(ring.pos++ % ring.buf.size());
         if (ring.used[b]) HIPCHK(c, hipStreamWaitEvent(c->s_h2d, ring.drained[b], 0));
         rc = copy_group(c, false, ring.buf[b], &pool_slots[size_t(i0)], k, c->s_h2d);
@@ -564,9 +569,13 @@ lmc_status_t lmc_store(lmc_ctx_t *c, void *const *kv_layers, const int64_t *slot
     Ring &ring = c->store_ring;
     const size_t per = size_t(c->cfg.staging_chunks);
     for (size_t j0 = 0; j0 < new_chunk.size();) {
-        // one launch covers chunks that are consecutive in the caller's slot mapping
+        // one launch covers chunks that are consecutive in the caller's slot mapping.
+        // Only the first gather is exposed (later ones hide behind the previous copy),
+        // so the first group is a single chunk and the link starts working at once.
+        const size_t edge = size_t(std::min<int64_t>(c->edge_chunks, int64_t(per)));
+        const size_t cap = (j0 == 0 && edge > 0 && new_chunk.size() > edge) ? edge : per;
         size_t k = 1;
-        while (k < per && j0 + k < new_chunk.size() && new_chunk[j0 + k] == new_chunk[j0] + int64_t(k)) k++;
+        while (k < cap && j0 + k < new_chunk.size() && new_chunk[j0 + k] == new_chunk[j0] + int64_t(k)) k++;
         const size_t b = size_t(ring.pos++ % ring.buf.size());
         if (ring.used[b]) HIPCHK(c, hipStreamWaitEvent(c->s_gather, ring.drained[b], 0));
         rc = timed_launch(c, true, ptrs, slot_mapping + new_chunk[j0] * CT, uint32_t(k), ring.buf[b], c->s_gather);
@@ -844,7 +853,9 @@ lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
     if (!c || !key || value < 0) return LMC_ERR_INVAL;
     std::lock_guard<std::mutex> lock(c->mu);
     const std::string k(key);
-    if (k == "xcd_run") {
+    if (k == "edge_chunks") {
+        c->edge_chunks = value;
+    } else if (k == "xcd_run") {
         if (value > (1 << 20)) return LMC_ERR_INVAL;
         c->shape.xcd_run = uint32_t(value);
     } else if (k == "nt_load" && value <= 1) {

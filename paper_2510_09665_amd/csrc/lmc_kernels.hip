@@ -31,13 +31,31 @@ template <> struct VecOf<4> { typedef unsigned int type; };
 template <> struct VecOf<2> { typedef unsigned short type; };
 template <> struct VecOf<1> { typedef unsigned char type; };
 
-template <typename V, bool NT> __device__ __forceinline__ V load_vec(const uint8_t *p) {
-    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const V *>(p));
-    return *reinterpret_cast<const V *>(p);
+#define LMC_GLOBAL __attribute__((address_space(1)))
+
+// Addresses are carried as integers (so they can be pinned in scalar registers) and
+// dereferenced as global-memory pointers, never as flat ones.
+template <typename V, bool NT> __device__ __forceinline__ V load_vec(uint64_t addr) {
+    const LMC_GLOBAL V *p = (const LMC_GLOBAL V *)addr;
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
 }
-template <typename V, bool NT> __device__ __forceinline__ void store_vec(uint8_t *p, V v) {
-    if (NT) __builtin_nontemporal_store(v, reinterpret_cast<V *>(p));
-    else *reinterpret_cast<V *>(p) = v;
+template <typename V, bool NT> __device__ __forceinline__ void store_vec(uint64_t addr, V v) {
+    LMC_GLOBAL V *p = (LMC_GLOBAL V *)addr;
+    if (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// Keeps a wave-uniform value in scalar registers from this point on.
+template <typename T> __device__ __forceinline__ T pin(T v) {
+    asm volatile("" : "+s"(v));
+    return v;
+}
+__device__ __forceinline__ FastDiv pin(FastDiv f) {
+    f.mul = pin(f.mul);
+    f.shift = pin(f.shift);
+    f.d = pin(f.d);
+    return f;
 }
 
 // One pass of the path's copy in either direction; lane = one vector r of plane lp of
@@ -50,6 +68,20 @@ __global__ __launch_bounds__(kThreads) void move_rows(const KernelGeom g, const 
                                                       uint8_t *staging, int32_t *bad_flag,
                                                       uint32_t n_blocks_permuted, uint32_t xcd_shift) {
     typedef typename VecOf<VEC>::type V;
+    // Fetch every kernel argument now, in one batch of scalar loads.  Left alone the
+    // compiler loads each field just before its first use, which puts four scalar-load
+    // round trips behind the slot load on every wavefront's critical path.
+    const FastDiv by_tiles = pin(g.by_tiles_per_plane), by_lp = pin(g.by_layer_planes),
+                  by_row = pin(g.by_vec_per_row), by_run = pin(g.by_vec_per_run),
+                  by_bs = pin(g.by_block_size);
+    const uint32_t vec_per_plane = pin(g.vec_per_plane), chunk_tokens = pin(g.chunk_tokens),
+                   n_slots = pin(g.n_slots), runs_per_row = pin(g.runs_per_row);
+    const int64_t block_stride = pin(g.block_stride), token_stride = pin(g.token_stride),
+                  run_stride = pin(g.run_stride);
+    const uint64_t plane_bytes = pin(g.plane_bytes), chunk_bytes = pin(g.chunk_bytes);
+    const uint64_t slots_at = pin(uint64_t(slot_mapping)), staging_at = pin(uint64_t(staging)),
+                   bad_flag_at = pin(uint64_t(bad_flag));
+
     uint32_t blk = blockIdx.x;
     if (blk < n_blocks_permuted) {
         // hardware deals consecutive workgroup ids to the 8 XCDs in turn; give each XCD
@@ -60,30 +92,32 @@ __global__ __launch_bounds__(kThreads) void move_rows(const KernelGeom g, const 
         const uint32_t grp = local >> xcd_shift;
         blk = (((grp << 3) + xcd) << xcd_shift) + (local & ((1u << xcd_shift) - 1u));
     }
-    const uint32_t q = g.by_tiles_per_plane.div(blk);
-    const uint32_t tile = blk - q * g.by_tiles_per_plane.d;
-    const uint32_t c = g.by_layer_planes.div(q);
-    const uint32_t lp = q - c * g.n_layer_planes;
+    const uint32_t q = by_tiles.div(blk);
+    const uint32_t tile = blk - q * by_tiles.d;
+    const uint32_t c = by_lp.div(q);
+    const uint32_t lp = q - c * by_lp.d;
     const uint32_t r = tile * kThreads + threadIdx.x;
-    if (r >= g.vec_per_plane) return;
-    const uint32_t t = g.by_vec_per_row.div(r);
-    const uint32_t w = r - t * g.by_vec_per_row.d;
+    if (r >= vec_per_plane) return;
+    const uint32_t t = by_row.div(r);
+    const uint32_t w = r - t * by_row.d;
 
-    const int64_t s = slot_mapping[uint64_t(c) * g.chunk_tokens + t];
-    const bool valid = uint64_t(s) < uint64_t(g.n_slots);  // negative wraps to huge
-    if (s >= int64_t(g.n_slots)) *bad_flag = 1;
+    const int64_t s = load_vec<int64_t, false>(slots_at + (uint64_t(c) * chunk_tokens + t) * 8u);
+    // the plane's base pointer is fetched while the slot is on its way
+    const uint64_t layer = pin(uint64_t(layers.p[lp]));
+    const bool valid = uint64_t(s) < uint64_t(n_slots);  // negative wraps to huge
+    if (s >= int64_t(n_slots)) store_vec<int32_t, false>(bad_flag_at, 1);
     const uint32_t su = valid ? uint32_t(s) : 0u;  // slot 0 is always inside the pages
-    const uint32_t b = g.by_block_size.div(su);
-    const uint32_t o = su - b * g.by_block_size.d;
+    const uint32_t b = by_bs.div(su);
+    const uint32_t o = su - b * by_bs.d;
     uint32_t run = 0, dv = w;
-    if (g.runs_per_row > 1) {
-        run = g.by_vec_per_run.div(w);
-        dv = w - run * g.by_vec_per_run.d;
+    if (runs_per_row > 1) {
+        run = by_run.div(w);
+        dv = w - run * by_run.d;
     }
-    uint8_t *page = layers.p[lp] + int64_t(b) * g.block_stride + int64_t(o) * g.token_stride +
-                    int64_t(run) * g.run_stride + int64_t(dv) * VEC;
-    uint8_t *st = staging + uint64_t(c) * g.chunk_bytes + uint64_t(lp) * g.plane_bytes +
-                  uint64_t(r) * VEC;
+    const uint64_t page = layer + uint64_t(int64_t(b) * block_stride + int64_t(o) * token_stride +
+                                           int64_t(run) * run_stride + int64_t(dv) * VEC);
+    const uint64_t st = staging_at + uint64_t(c) * chunk_bytes + uint64_t(lp) * plane_bytes +
+                        uint64_t(r) * VEC;
     if (GATHER) {
         V v = load_vec<V, NT_LD>(page);
         if (!valid) v = V(0);
