@@ -78,8 +78,9 @@ enum {
 #define LMC_FLAG_POISON_STAGING 4u /* overwrite a staging buffer with 0xA5 as soon as the
                                       pipeline releases it: a reuse that came too early
                                       then shows as corrupt data.  For tests. */
-#define LMC_FLAG_TIMING 8u         /* bracket every gather / scatter launch with HIP events
-                                      on its own stream; durations appear in lmc_stats_t. */
+#define LMC_FLAG_TIMING 8u         /* give every gather / scatter launch a start and a stop
+                                      HIP event (kernel begin / end on its own stream);
+                                      durations appear in lmc_stats_t. */
 
 /* Geometry of the engine's paged KV memory (section 5: a page is block_size tokens of
  * one layer) and the chunk length (section 5.1).  All strides are in bytes. */
@@ -249,10 +250,11 @@ lmc_status_t lmc_measure_link(lmc_ctx_t *ctx, uint64_t nbytes, int32_t reps,
 lmc_status_t lmc_copy(lmc_ctx_t *ctx, void *dst_dev, const void *src_dev, uint64_t nbytes,
                       void *stream);
 
-/* Launch knobs for experiments; the defaults are the measured best.  Keys: "nt_load",
+/* Run-time knobs for experiments; the defaults are the measured best.  Keys: "nt_load",
  * "nt_store" (0/1: non-temporal hints on the kernels' streaming accesses), "xcd_run"
- * (consecutive tiles handed to one XCD, 0 = hardware round-robin).  Unknown key or
- * out-of-range value: LMC_ERR_INVAL. */
+ * (consecutive tiles handed to one XCD, 0 = hardware round-robin), "edge_chunks" (size
+ * of the group at the exposed end of a pipeline, 0 = none), "timing" (0/1: switches
+ * LMC_FLAG_TIMING).  Unknown key or out-of-range value: LMC_ERR_INVAL. */
 lmc_status_t lmc_tune(lmc_ctx_t *ctx, const char *key, int64_t value);
 
 const char *lmc_strerror(lmc_status_t status);

@@ -243,28 +243,25 @@ lmc_status_t validate_slots(lmc_ctx *c, const int64_t *slot_mapping, int64_t n_t
 lmc_status_t timed_launch(lmc_ctx *c, bool gather, const lmc::LayerPtrs &ptrs,
                           const int64_t *slots, uint32_t n_chunks, uint8_t *staging,
                           hipStream_t stream) {
-    const bool timing = (c->cfg.flags & LMC_FLAG_TIMING) != 0;
+    // LMC_FLAG_TIMING: the launch itself carries a start and a stop event, which receive
+    // the kernel's own begin / end time stamps; the stream gets no extra marker.
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (timing) {
+    if (c->cfg.flags & LMC_FLAG_TIMING) {
         lmc_status_t rc = get_event(c, true, &e0);
         if (rc == LMC_OK) rc = get_event(c, true, &e1);
         if (rc != LMC_OK) return rc;
-        HIPCHK(c, hipEventRecord(e0, stream));
     }
     const lmc::LaunchShape &s = c->shape;
     if (gather) {
-        HIPCHK(c, lmc::launch_gather(c->kg, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream));
+        HIPCHK(c, lmc::launch_gather(c->kg, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1));
         c->stats.gather_launches++;
         c->stats.bytes_gathered += uint64_t(n_chunks) * uint64_t(c->chunk_bytes);
     } else {
-        HIPCHK(c, lmc::launch_scatter(c->kg, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream));
+        HIPCHK(c, lmc::launch_scatter(c->kg, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1));
         c->stats.scatter_launches++;
         c->stats.bytes_scattered += uint64_t(n_chunks) * uint64_t(c->chunk_bytes);
     }
-    if (timing) {
-        HIPCHK(c, hipEventRecord(e1, stream));
-        c->timings.push_back(Timing{e0, e1, gather});
-    }
+    if (e0 != nullptr) c->timings.push_back(Timing{e0, e1, gather});
     return LMC_OK;
 }
 
@@ -853,7 +850,9 @@ lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
     if (!c || !key || value < 0) return LMC_ERR_INVAL;
     std::lock_guard<std::mutex> lock(c->mu);
     const std::string k(key);
-    if (k == "edge_chunks") {
+    if (k == "timing" && value <= 1) {
+        c->cfg.flags = value ? (c->cfg.flags | LMC_FLAG_TIMING) : (c->cfg.flags & ~LMC_FLAG_TIMING);
+    } else if (k == "edge_chunks") {
         c->edge_chunks = value;
     } else if (k == "xcd_run") {
         if (value > (1 << 20)) return LMC_ERR_INVAL;

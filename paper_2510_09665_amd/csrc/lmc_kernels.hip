@@ -19,6 +19,8 @@
 //     part is wave-uniform and runs on the scalar unit.
 #include "lmc_kernels.hpp"
 
+#include <hip/hip_ext.h>
+
 namespace lmc {
 namespace {
 
@@ -156,7 +158,7 @@ __global__ __launch_bounds__(kThreads) void fill_bytes(uint8_t *dst, uint8_t val
 template <int VEC, bool GATHER>
 hipError_t launch_move_v(const KernelGeom &g, const LaunchShape &s, const LayerPtrs &layers,
                          const int64_t *slot_mapping, uint32_t n_chunks, uint8_t *staging,
-                         int32_t *bad_flag, hipStream_t stream) {
+                         int32_t *bad_flag, hipStream_t stream, hipEvent_t start, hipEvent_t stop) {
     const uint32_t n_blocks = n_chunks * g.n_layer_planes * g.by_tiles_per_plane.d;
     if (n_blocks == 0) return hipSuccess;
     uint32_t shift = 0, permuted = 0;
@@ -166,8 +168,8 @@ hipError_t launch_move_v(const KernelGeom &g, const LaunchShape &s, const LayerP
     }
     dim3 grid(n_blocks), block(kThreads);
 #define LMC_GO(LD, ST)                                                                          \
-    hipLaunchKernelGGL((move_rows<VEC, GATHER, LD, ST>), grid, block, 0, stream, g, layers,     \
-                       slot_mapping, staging, bad_flag, permuted, shift)
+    hipExtLaunchKernelGGL((move_rows<VEC, GATHER, LD, ST>), grid, block, 0, stream, start, stop, \
+                          0, g, layers, slot_mapping, staging, bad_flag, permuted, shift)
     if (s.nt_load && s.nt_store) LMC_GO(true, true);
     else if (s.nt_load) LMC_GO(true, false);
     else if (s.nt_store) LMC_GO(false, true);
@@ -179,13 +181,13 @@ hipError_t launch_move_v(const KernelGeom &g, const LaunchShape &s, const LayerP
 template <bool GATHER>
 hipError_t launch_move(const KernelGeom &g, const LaunchShape &s, const LayerPtrs &layers,
                        const int64_t *slot_mapping, uint32_t n_chunks, uint8_t *staging,
-                       int32_t *bad_flag, hipStream_t stream) {
+                       int32_t *bad_flag, hipStream_t stream, hipEvent_t start, hipEvent_t stop) {
     switch (g.vec) {
-        case 16: return launch_move_v<16, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream);
-        case 8: return launch_move_v<8, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream);
-        case 4: return launch_move_v<4, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream);
-        case 2: return launch_move_v<2, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream);
-        case 1: return launch_move_v<1, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream);
+        case 16: return launch_move_v<16, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
+        case 8: return launch_move_v<8, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
+        case 4: return launch_move_v<4, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
+        case 2: return launch_move_v<2, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
+        case 1: return launch_move_v<1, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
     }
     return hipErrorInvalidValue;
 }
@@ -214,15 +216,16 @@ uint32_t max_chunks_per_launch(const KernelGeom &g) {
 
 hipError_t launch_gather(const KernelGeom &g, const LaunchShape &s, const LayerPtrs &layers,
                          const int64_t *slot_mapping, uint32_t n_chunks, uint8_t *staging,
-                         int32_t *bad_flag, hipStream_t stream) {
-    return launch_move<true>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream);
+                         int32_t *bad_flag, hipStream_t stream, hipEvent_t start, hipEvent_t stop) {
+    return launch_move<true>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start,
+                             stop);
 }
 
 hipError_t launch_scatter(const KernelGeom &g, const LaunchShape &s, const LayerPtrs &layers,
                           const int64_t *slot_mapping, uint32_t n_chunks, const uint8_t *staging,
-                          int32_t *bad_flag, hipStream_t stream) {
+                          int32_t *bad_flag, hipStream_t stream, hipEvent_t start, hipEvent_t stop) {
     return launch_move<false>(g, s, layers, slot_mapping, n_chunks, const_cast<uint8_t *>(staging),
-                              bad_flag, stream);
+                              bad_flag, stream, start, stop);
 }
 
 hipError_t launch_check_slots(const int64_t *slot_mapping, uint64_t n, uint32_t n_slots,

@@ -59,14 +59,18 @@ struct LaunchShape {
                               // two) consecutive tiles; 0 = off
 };
 
-// pages -> chunks [first_chunk, first_chunk + n_chunks) of the slot mapping, written
-// back to back from `staging`.  bad_flag: device-visible int set to 1 on a slot >= n_slots.
+// pages -> n_chunks chunks of the slot mapping, written back to back from `staging`
+// (gather), or the reverse (scatter).  bad_flag: device-visible int set to 1 on a slot
+// >= n_slots.  start / stop: optional events (timing enabled) that receive the
+// kernel's own begin and end time stamps; no marker is put on the stream for them.
 hipError_t launch_gather(const KernelGeom &g, const LaunchShape &s, const LayerPtrs &layers,
                          const int64_t *slot_mapping, uint32_t n_chunks, uint8_t *staging,
-                         int32_t *bad_flag, hipStream_t stream);
+                         int32_t *bad_flag, hipStream_t stream, hipEvent_t start = nullptr,
+                         hipEvent_t stop = nullptr);
 hipError_t launch_scatter(const KernelGeom &g, const LaunchShape &s, const LayerPtrs &layers,
                           const int64_t *slot_mapping, uint32_t n_chunks, const uint8_t *staging,
-                          int32_t *bad_flag, hipStream_t stream);
+                          int32_t *bad_flag, hipStream_t stream, hipEvent_t start = nullptr,
+                          hipEvent_t stop = nullptr);
 // *bad_flag = 1 if any of the n slots is >= n_slots
 hipError_t launch_check_slots(const int64_t *slot_mapping, uint64_t n, uint32_t n_slots,
                               int32_t *bad_flag, hipStream_t stream);
