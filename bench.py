@@ -36,6 +36,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published
+# HBM bytes per algorithmic byte of a gather / scatter launch, from rocprofv3 --pmc
+# FETCH_SIZE and WRITE_SIZE of this benchmark's device leg, each calibrated on the plain
+# copy kernel (profiles/move_rows_llama3_8b_device_leg.md): counters cannot be read from
+# inside this process, so the measured ratio is applied to the launch size.
+PMC_TRAFFIC_RATIO = 1.0001
 WORKLOAD = "llama3_8b"
 
 
@@ -183,7 +188,8 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": "move_rows<16," + ("gather" if dom_name == "gather" else "scatter") + ">",
         "achieved": dom["hbm_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": round(dom["hbm_gbps"] / HBM_PEAK_GBPS, 4), "traffic": None,
+        "frac": round(dom["hbm_gbps"] / HBM_PEAK_GBPS, 4),
+        "traffic": int(dom["bytes_per_launch"] * PMC_TRAFFIC_RATIO),
         "bytes_per_launch": dom["bytes_per_launch"], "avg_launch_us": dom["avg_us"],
         "launches": dom["launches"], "gather": kg, "scatter": ks,
     }
