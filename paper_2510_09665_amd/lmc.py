@@ -73,6 +73,13 @@ def _lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError("liblmc.so is not built: run `python -m paper_2510_09665_amd.build` "
                               "(needs hipcc); there is no fallback path")
+        # PyTorch wheels ship their own HIP runtime.  A process must not end up with two:
+        # if PyTorch is present, let it load its runtime first so that liblmc binds to the
+        # same one and device pointers and streams mean the same thing on both sides.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         lib = ctypes.CDLL(LIB_PATH)
         vp, i64, u64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64, ctypes.c_int32
         st = ctypes.c_int32

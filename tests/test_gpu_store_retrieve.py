@@ -78,6 +78,12 @@ def test_config2_llama3_8b_full():
     assert st["gather_launches"] == 1 + 4 and st["scatter_launches"] == 4 + 1
 
 
+def test_config2_llama3_8b_full_in_the_benchmarks_launch_configuration():
+    # bench.py's defaults: two staging buffers of 16 chunks -> launches of 1 and 15 chunks
+    st = _run_sequence("llama3_8b", staging_chunks=16, num_staging=2)
+    assert st["gather_launches"] == 2 and st["scatter_launches"] == 2
+
+
 def test_config5_mla_bf16_full():
     _run_sequence("mla_bf16", staging_chunks=2)
 
