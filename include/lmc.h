@@ -196,10 +196,52 @@ lmc_status_t lmc_retrieve_batch(lmc_ctx_t *ctx, int64_t n_req, const int64_t *re
                                 void *const *kv_layers, void *stream_to_signal,
                                 uint64_t *ticket_out);
 
+/* Layer-wise retrieve (section 5.2 "Layer-wise pipelining"; start_load_kv / wait_load_kv
+ * of section 6, Table 2).  Same contract as lmc_retrieve, but the work is ordered by
+ * layer: for layers_per_step layers at a time, the share of every chunk in those layers
+ * is copied to the staging buffer (one rectangle copy per run of consecutive pool
+ * slots) and scattered, then the next layers follow, so that layer l's pages are
+ * complete long before the last layer's.  The consumer orders itself per layer with
+ * lmc_wait_layer; unlike lmc_retrieve, no stream is made to wait for the whole call.
+ * stream_to_wait_on: the call is ordered after work already on it (old users of the
+ * pages, producer of the slot mapping).  layers_per_step >= 1 (values above num_layers
+ * mean "all").  Errors as lmc_retrieve, and LMC_ERR_BUSY if one of the chunks belongs
+ * to a layer-wise store whose layers have not all been submitted. */
+lmc_status_t lmc_retrieve_layerwise(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n_chunks,
+                                    const int64_t *slot_mapping, void *const *kv_layers,
+                                    int32_t layers_per_step, void *stream_to_wait_on,
+                                    uint64_t *ticket_out);
+
+/* Layer-wise store (section 5.2; start_store_kv / wait_store_kv of Table 2): the KV of a
+ * forward pass becomes available layer by layer, and each layer is offloaded as soon as
+ * it exists.  lmc_store_begin runs the token processor (which chunks are new, where they
+ * go; same rules and errors as lmc_store) and returns a ticket; nothing moves yet.  The
+ * slot mapping (DEVICE) must stay alive until lmc_wait(ticket) returns.
+ * lmc_store_layers then submits layers [first_layer, first_layer + n_layers): they are
+ * gathered from kv_layers and copied into the layer's place inside every new chunk's
+ * pool slot, ordered after work already on stream_to_wait_on (the kernels that produced
+ * those layers).  Layers must be submitted in ascending order without gaps, else
+ * LMC_ERR_INVAL; when the last layer has been submitted the ticket behaves like any
+ * other.  Until then lmc_wait on it, lmc_get_host and a retrieve of its chunks return
+ * LMC_ERR_BUSY, and its chunks cannot be cleared. */
+lmc_status_t lmc_store_begin(lmc_ctx_t *ctx, const int64_t *slot_mapping, const uint64_t *chunk_ids,
+                             int64_t n_chunks, void *stream_to_wait_on, uint64_t *ticket_out);
+lmc_status_t lmc_store_layers(lmc_ctx_t *ctx, uint64_t ticket, int32_t first_layer,
+                              int32_t n_layers, void *const *kv_layers, void *stream_to_wait_on);
+
+/* Make `stream` (hipStream_t, NULL = null stream) wait, on the device, until layer
+ * `layer` of a layer-wise ticket is in place: loaded into its pages (retrieve) or
+ * arrived in the pool (store).  The host does not block.  A finished ticket needs no
+ * wait and returns LMC_OK.  LMC_ERR_INVAL for a ticket that is not layer-wise or a
+ * layer out of range; LMC_ERR_BUSY for a store layer that has not been submitted. */
+lmc_status_t lmc_wait_layer(lmc_ctx_t *ctx, uint64_t ticket, int32_t layer, void *stream);
+
 /* Block until the work of `ticket` (and of every earlier ticket) has finished on the
  * device; ticket 0 means everything enqueued so far.  Returns LMC_ERR_BADSLOT if a
  * kernel since the last lmc_wait met a slot >= num_blocks*block_size (that token was
- * skipped, the rest of the call was carried out), LMC_ERR_HIP on a device error. */
+ * skipped, the rest of the call was carried out), LMC_ERR_HIP on a device error.
+ * A layer-wise store that still lacks layers cannot be waited for: LMC_ERR_BUSY if it
+ * is the ticket named (or ticket is 0); an older one is left out of the wait. */
 lmc_status_t lmc_wait(lmc_ctx_t *ctx, uint64_t ticket);
 
 /* The two kernels alone, for unit parity and for measuring them against HBM

@@ -36,9 +36,17 @@ struct Ring {
 
 struct Op {
     uint64_t ticket = 0;
-    hipEvent_t done = nullptr;       // null: nothing was enqueued for this ticket
+    hipEvent_t done = nullptr;       // null: nothing enqueued (yet) for this ticket
     std::vector<int64_t> slots;      // pool slots whose in-flight count this op holds
     bool is_store = false;
+    // layer-wise operations (paper section 5.2)
+    bool layerwise = false;
+    bool pending = false;                 // a store whose layers have not all been submitted
+    int32_t next_layer = 0;               // first layer not yet submitted
+    std::vector<int64_t> new_chunk;       // pending store: chunk numbers that are new
+    const int64_t *slot_mapping = nullptr;  // pending store: the caller's slot mapping
+    std::vector<hipEvent_t> layer_done;   // per layer: event after which the layer is in place
+    std::vector<hipEvent_t> owned_events; // the distinct events behind layer_done
 };
 
 struct Timing {
@@ -64,7 +72,7 @@ struct lmc_ctx {
     int32_t *bad_flag_host = nullptr, *bad_flag_dev = nullptr;
     std::deque<Op> ops;
     std::deque<Timing> timings;
-    uint64_t next_ticket = 1, completed_ticket = 0;
+    uint64_t next_ticket = 1;
     std::vector<hipEvent_t> free_sync_events, free_time_events, all_events;
     lmc_stats_t stats{};
     int32_t last_hip_error = 0;
@@ -153,7 +161,6 @@ lmc_status_t derive_geometry(const lmc_kv_geom_t &g, lmc::KernelGeom *k, int64_t
     k->n_layer_planes = uint32_t(g.num_layers * g.num_planes);
     k->vec = uint32_t(vec);
     k->by_tiles_per_plane = lmc::make_fastdiv(uint32_t((pairs + 255) / 256));
-    k->by_layer_planes = lmc::make_fastdiv(k->n_layer_planes);
     k->by_vec_per_row = lmc::make_fastdiv(uint32_t(row / vec));
     k->by_vec_per_run = lmc::make_fastdiv(uint32_t((row_contiguous ? row : run) / vec));
     k->by_block_size = lmc::make_fastdiv(uint32_t(g.block_size));
@@ -173,22 +180,30 @@ lmc_status_t build_layer_ptrs(const lmc_ctx *c, void *const *kv_layers, lmc::Lay
     return LMC_OK;
 }
 
+Op *find_op(lmc_ctx *c, uint64_t ticket) {
+    for (Op &o : c->ops)
+        if (o.ticket == ticket) return &o;
+    return nullptr;
+}
+
 // Finish every operation whose last device step has completed: drop its in-flight
 // counts, collect kernel timings, recycle events.
 void reap(lmc_ctx *c) {
-    while (!c->ops.empty()) {
-        Op &op = c->ops.front();
-        if (op.done != nullptr) {
-            if (hipEventQuery(op.done) != hipSuccess) break;
-            c->free_sync_events.push_back(op.done);
+    for (size_t i = 0; i < c->ops.size();) {
+        Op &op = c->ops[i];
+        const bool finished = op.done != nullptr ? hipEventQuery(op.done) == hipSuccess : !op.pending;
+        if (!finished) {
+            i++;
+            continue;
         }
+        if (op.done != nullptr) c->free_sync_events.push_back(op.done);
+        for (hipEvent_t e : op.owned_events) c->free_sync_events.push_back(e);
         for (int64_t s : op.slots) {
             lmc::SlotMeta &m = c->index.meta(s);
             m.inflight--;
             if (m.ready_ticket == op.ticket) m.ready_ticket = 0;
         }
-        c->completed_ticket = op.ticket;
-        c->ops.pop_front();
+        c->ops.erase(c->ops.begin() + long(i));
     }
     for (size_t i = 0; i < c->timings.size();) {
         Timing &t = c->timings[i];
@@ -240,9 +255,9 @@ lmc_status_t validate_slots(lmc_ctx *c, const int64_t *slot_mapping, int64_t n_t
     return bad ? LMC_ERR_BADSLOT : LMC_OK;
 }
 
-lmc_status_t timed_launch(lmc_ctx *c, bool gather, const lmc::LayerPtrs &ptrs,
-                          const int64_t *slots, uint32_t n_chunks, uint8_t *staging,
-                          hipStream_t stream) {
+lmc_status_t timed_launch(lmc_ctx *c, bool gather, const lmc::LaunchView &view,
+                          const lmc::LayerPtrs &ptrs, const int64_t *slots, uint32_t n_chunks,
+                          uint8_t *staging, hipStream_t stream) {
     // LMC_FLAG_TIMING: the launch itself carries a start and a stop event, which receive
     // the kernel's own begin / end time stamps; the stream gets no extra marker.
     hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -252,14 +267,15 @@ lmc_status_t timed_launch(lmc_ctx *c, bool gather, const lmc::LayerPtrs &ptrs,
         if (rc != LMC_OK) return rc;
     }
     const lmc::LaunchShape &s = c->shape;
+    const uint64_t moved = uint64_t(n_chunks) * view.chunk_stride;
     if (gather) {
-        HIPCHK(c, lmc::launch_gather(c->kg, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1));
+        HIPCHK(c, lmc::launch_gather(c->kg, view, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1));
         c->stats.gather_launches++;
-        c->stats.bytes_gathered += uint64_t(n_chunks) * uint64_t(c->chunk_bytes);
+        c->stats.bytes_gathered += moved;
     } else {
-        HIPCHK(c, lmc::launch_scatter(c->kg, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1));
+        HIPCHK(c, lmc::launch_scatter(c->kg, view, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1));
         c->stats.scatter_launches++;
-        c->stats.bytes_scattered += uint64_t(n_chunks) * uint64_t(c->chunk_bytes);
+        c->stats.bytes_scattered += moved;
     }
     if (e0 != nullptr) c->timings.push_back(Timing{e0, e1, gather});
     return LMC_OK;
@@ -270,22 +286,30 @@ lmc_status_t force_sync(lmc_ctx *c, hipStream_t s) {
     return LMC_OK;
 }
 
-// Copies between staging and pool, one hipMemcpyAsync per run of consecutive pool slots.
-lmc_status_t copy_group(lmc_ctx *c, bool to_host, uint8_t *staging, const int64_t *pool_slots,
-                        int64_t k, hipStream_t stream) {
-    const int64_t cb = c->chunk_bytes;
+// Copies `width` bytes per chunk between staging (chunks `stride` bytes apart) and the
+// pool (offset `pool_off` inside each slot), one transfer per run of consecutive pool
+// slots: a plain copy when the extents are back to back on both sides (whole chunks),
+// else a rectangle copy whose rows are the chunks (layer-wise mode).
+lmc_status_t copy_group(lmc_ctx *c, bool to_host, uint8_t *staging, uint64_t stride,
+                        const int64_t *pool_slots, int64_t k, uint64_t pool_off, uint64_t width,
+                        hipStream_t stream) {
+    const uint64_t cb = uint64_t(c->chunk_bytes);
+    const hipMemcpyKind kind = to_host ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice;
     for (int64_t j = 0; j < k;) {
         int64_t m = 1;
         while (j + m < k && pool_slots[j + m] == pool_slots[j] + m) m++;
-        uint8_t *host = c->pool + pool_slots[j] * cb;
-        uint8_t *dev = staging + j * cb;
-        if (to_host) {
-            HIPCHK(c, hipMemcpyAsync(host, dev, size_t(m * cb), hipMemcpyDeviceToHost, stream));
-            c->stats.bytes_d2h += uint64_t(m * cb);
+        uint8_t *host = c->pool + uint64_t(pool_slots[j]) * cb + pool_off;
+        uint8_t *dev = staging + uint64_t(j) * stride;
+        if (m == 1 || (width == cb && stride == cb)) {
+            if (to_host) HIPCHK(c, hipMemcpyAsync(host, dev, size_t(m * width), kind, stream));
+            else HIPCHK(c, hipMemcpyAsync(dev, host, size_t(m * width), kind, stream));
+        } else if (to_host) {
+            HIPCHK(c, hipMemcpy2DAsync(host, cb, dev, stride, width, size_t(m), kind, stream));
         } else {
-            HIPCHK(c, hipMemcpyAsync(dev, host, size_t(m * cb), hipMemcpyHostToDevice, stream));
-            c->stats.bytes_h2d += uint64_t(m * cb);
+            HIPCHK(c, hipMemcpy2DAsync(dev, stride, host, cb, width, size_t(m), kind, stream));
         }
+        if (to_host) c->stats.bytes_d2h += uint64_t(m) * width;
+        else c->stats.bytes_h2d += uint64_t(m) * width;
         j += m;
     }
     return LMC_OK;
@@ -303,9 +327,31 @@ lmc_status_t finish_op(lmc_ctx *c, Op &&op, hipStream_t last_stream, bool enqueu
     return LMC_OK;
 }
 
+// A chunk whose store is still on its way to the pool must be loaded after that store:
+// the H2D stream waits for the newest such store (stores complete in order on one
+// stream).  A layer-wise store that has not been submitted completely cannot be waited
+// for on the device: LMC_ERR_BUSY.
+lmc_status_t after_stores(lmc_ctx *c, const std::vector<int64_t> &pool_slots) {
+    uint64_t newest = 0;
+    for (int64_t s : pool_slots) {
+        const uint64_t t = c->index.meta(s).ready_ticket;
+        if (t == 0) continue;
+        const Op *o = find_op(c, t);
+        if (o == nullptr) continue;  // finished
+        if (o->pending) return LMC_ERR_BUSY;
+        newest = std::max(newest, t);
+    }
+    if (newest != 0) {
+        const Op *o = find_op(c, newest);
+        if (o != nullptr && o->done != nullptr) HIPCHK(c, hipStreamWaitEvent(c->s_h2d, o->done, 0));
+    }
+    return LMC_OK;
+}
+
+// Retrieve, bulk (layers_per_step == 0) or layer by layer (paper section 5.2).
 lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
                          const int64_t *slot_mapping, void *const *kv_layers, void *user_stream,
-                         uint64_t *ticket_out) {
+                         int32_t layers_per_step, uint64_t *ticket_out) {
     if (!c->has_device) return LMC_ERR_NODEVICE;
     DeviceScope dev(c);
     reap(c);
@@ -321,54 +367,83 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
     lmc_status_t rc = build_layer_ptrs(c, kv_layers, &ptrs);
     if (rc != LMC_OK) return rc;
     hipStream_t user = static_cast<hipStream_t>(user_stream);
-    const int64_t CT = c->cfg.geom.chunk_tokens;
+    const lmc_kv_geom_t &geom = c->cfg.geom;
+    const int64_t CT = geom.chunk_tokens;
     // the pages may still be in use, and the slot mapping still be on its way, by work
     // already on the caller's stream
     if (n_chunks > 0 && (rc = order_after(c, c->s_scatter, user)) != LMC_OK) return rc;
     rc = validate_slots(c, slot_mapping, n_chunks * CT, c->s_scatter);
     if (rc != LMC_OK) return rc;
 
+    if ((rc = after_stores(c, pool_slots)) != LMC_OK) return rc;
     Op op;
     op.ticket = c->next_ticket++;
+    op.layerwise = layers_per_step > 0;
     if (n_chunks == 0) return finish_op(c, std::move(op), nullptr, false, ticket_out);
 
-    // a chunk whose store is still on its way to the pool: load after that store
-    uint64_t newest_store = 0;
-    for (int64_t s : pool_slots) newest_store = std::max(newest_store, c->index.meta(s).ready_ticket);
-    if (newest_store > c->completed_ticket)
-        for (const Op &o : c->ops)
-            if (o.ticket == newest_store && o.done != nullptr)
-                HIPCHK(c, hipStreamWaitEvent(c->s_h2d, o.done, 0));
-
     Ring &ring = c->load_ring;
+    const uint64_t cb = uint64_t(c->chunk_bytes);
     const int64_t per = c->cfg.staging_chunks;
-    // The link is the bottleneck and every scatter but the last hides behind the next
-    // copy, so the last group is a single chunk: only its scatter is exposed.
-    const int64_t edge = std::min<int64_t>(c->edge_chunks, per);
-    const int64_t body = (edge > 0 && n_chunks > edge) ? n_chunks - edge : n_chunks;
-    for (int64_t i0 = 0, k = 0; i0 < n_chunks; i0 += k) {
-        k = i0 < body ? std::min(per, body - i0) : n_chunks - i0;
+    // one group: copies into the next ring buffer on the H2D stream, scatter on the
+    // scatter stream; the buffer is released when the scatter has read it
+    auto load_group = [&](const lmc::LaunchView &view, uint64_t pool_off, int64_t i0, int64_t k) -> lmc_status_t {
         const size_t b = size_t(ring.pos++ % ring.buf.size());
         if (ring.used[b]) HIPCHK(c, hipStreamWaitEvent(c->s_h2d, ring.drained[b], 0));
-        rc = copy_group(c, false, ring.buf[b], &pool_slots[size_t(i0)], k, c->s_h2d);
-        if (rc != LMC_OK) return rc;
+        lmc_status_t r = copy_group(c, false, ring.buf[b], view.chunk_stride, &pool_slots[size_t(i0)], k,
+                                    pool_off, view.chunk_stride, c->s_h2d);
+        if (r != LMC_OK) return r;
         HIPCHK(c, hipEventRecord(ring.filled[b], c->s_h2d));
-        if ((rc = force_sync(c, c->s_h2d)) != LMC_OK) return rc;
+        if ((r = force_sync(c, c->s_h2d)) != LMC_OK) return r;
         HIPCHK(c, hipStreamWaitEvent(c->s_scatter, ring.filled[b], 0));
-        rc = timed_launch(c, false, ptrs, slot_mapping + i0 * CT, uint32_t(k), ring.buf[b], c->s_scatter);
-        if (rc != LMC_OK) return rc;
+        r = timed_launch(c, false, view, ptrs, slot_mapping + i0 * CT, uint32_t(k), ring.buf[b], c->s_scatter);
+        if (r != LMC_OK) return r;
         if (c->cfg.flags & LMC_FLAG_POISON_STAGING)
-            HIPCHK(c, lmc::launch_fill(ring.buf[b], 0xA5, uint64_t(k * c->chunk_bytes), c->s_scatter));
+            HIPCHK(c, lmc::launch_fill(ring.buf[b], 0xA5, uint64_t(k) * view.chunk_stride, c->s_scatter));
         HIPCHK(c, hipEventRecord(ring.drained[b], c->s_scatter));
         ring.used[b] = 1;
-        if ((rc = force_sync(c, c->s_scatter)) != LMC_OK) return rc;
+        return force_sync(c, c->s_scatter);
+    };
+
+    if (!op.layerwise) {
+        const lmc::LaunchView view = lmc::bulk_view(c->kg);
+        // The link is the bottleneck and every scatter but the last hides behind the next
+        // copy, so the last group is a single chunk: only its scatter is exposed.
+        const int64_t edge = std::min<int64_t>(c->edge_chunks, per);
+        const int64_t body = (edge > 0 && n_chunks > edge) ? n_chunks - edge : n_chunks;
+        for (int64_t i0 = 0, k = 0; i0 < n_chunks; i0 += k) {
+            k = i0 < body ? std::min(per, body - i0) : n_chunks - i0;
+            if ((rc = load_group(view, 0, i0, k)) != LMC_OK) return rc;
+        }
+    } else {
+        // All chunks' share of a few layers at a time: one rectangle copy per run of pool
+        // slots, one scatter launch, one event that says "these layers are in place".
+        const int32_t L = geom.num_layers, P = geom.num_planes;
+        const uint64_t layer_bytes = uint64_t(P) * c->kg.plane_bytes;
+        op.layer_done.assign(size_t(L), nullptr);
+        for (int32_t l0 = 0; l0 < L; l0 += layers_per_step) {
+            const int32_t kk = std::min(layers_per_step, L - l0);
+            const lmc::LaunchView view = lmc::layer_view(c->kg, uint32_t(P), uint32_t(l0), uint32_t(kk));
+            const int64_t cap = std::min<int64_t>(int64_t(uint64_t(per) * cb / view.chunk_stride),
+                                                  int64_t(lmc::max_chunks_per_launch(c->kg, view)));
+            for (int64_t i0 = 0; i0 < n_chunks; i0 += cap)
+                if ((rc = load_group(view, uint64_t(l0) * layer_bytes, i0, std::min(cap, n_chunks - i0))) != LMC_OK)
+                    return rc;
+            hipEvent_t e;
+            if ((rc = get_event(c, false, &e)) != LMC_OK) return rc;
+            HIPCHK(c, hipEventRecord(e, c->s_scatter));
+            op.owned_events.push_back(e);
+            for (int32_t l = l0; l < l0 + kk; l++) op.layer_done[size_t(l)] = e;
+        }
     }
     for (int64_t s : pool_slots) c->index.meta(s).inflight++;
     op.slots = pool_slots;
     c->stats.chunks_retrieved += uint64_t(n_chunks);
+    const bool layerwise = op.layerwise;
     rc = finish_op(c, std::move(op), c->s_scatter, true, ticket_out);
     if (rc != LMC_OK) return rc;
-    HIPCHK(c, hipStreamWaitEvent(user, c->ops.back().done, 0));
+    // bulk: the caller's stream continues when everything is in place; layer-wise: the
+    // caller orders its streams per layer with lmc_wait_layer
+    if (!layerwise) HIPCHK(c, hipStreamWaitEvent(user, c->ops.back().done, 0));
     return LMC_OK;
 }
 
@@ -520,6 +595,68 @@ lmc_status_t lmc_lookup(lmc_ctx_t *c, const uint64_t *ids, int64_t n, int64_t *n
     return LMC_OK;
 }
 
+// Token processor of a store: which chunks are new, and where they go (lowest free
+// slot).  Stops at the first chunk that finds the pool full.
+static bool admit_new_chunks(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks, Op *op,
+                             std::vector<int64_t> *new_chunk) {
+    for (int64_t i = 0; i < n_chunks; i++) {
+        if (c->index.find(ids[i]) >= 0) {
+            c->stats.chunks_skipped_dup++;
+            continue;
+        }
+        const int64_t s = c->index.insert(ids[i]);
+        if (s < 0) {
+            c->stats.alloc_failures++;
+            return false;
+        }
+        lmc::SlotMeta &m = c->index.meta(s);
+        m.inflight = 1;
+        m.ready_ticket = op->ticket;
+        new_chunk->push_back(i);
+        op->slots.push_back(s);
+    }
+    return true;
+}
+
+// Gather + D2H of the new chunks' part described by `view` (all layers, or a few),
+// group by group through the store ring.
+static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64_t pool_off,
+                                 const lmc::LayerPtrs &ptrs, const int64_t *slot_mapping,
+                                 const std::vector<int64_t> &new_chunk,
+                                 const std::vector<int64_t> &new_slot, int64_t cap_chunks,
+                                 bool edge_group) {
+    Ring &ring = c->store_ring;
+    const int64_t CT = c->cfg.geom.chunk_tokens;
+    const size_t per = size_t(cap_chunks);
+    for (size_t j0 = 0; j0 < new_chunk.size();) {
+        // one launch covers chunks that are consecutive in the caller's slot mapping.
+        // Only the first gather is exposed (later ones hide behind the previous copy),
+        // so the first group is a single chunk and the link starts working at once.
+        const size_t edge = edge_group ? size_t(std::min<int64_t>(c->edge_chunks, int64_t(per))) : 0;
+        const size_t cap = (j0 == 0 && edge > 0 && new_chunk.size() > edge) ? edge : per;
+        size_t k = 1;
+        while (k < cap && j0 + k < new_chunk.size() && new_chunk[j0 + k] == new_chunk[j0] + int64_t(k)) k++;
+        const size_t b = size_t(ring.pos++ % ring.buf.size());
+        if (ring.used[b]) HIPCHK(c, hipStreamWaitEvent(c->s_gather, ring.drained[b], 0));
+        lmc_status_t rc = timed_launch(c, true, view, ptrs, slot_mapping + new_chunk[j0] * CT, uint32_t(k),
+                                       ring.buf[b], c->s_gather);
+        if (rc != LMC_OK) return rc;
+        HIPCHK(c, hipEventRecord(ring.filled[b], c->s_gather));
+        if ((rc = force_sync(c, c->s_gather)) != LMC_OK) return rc;
+        HIPCHK(c, hipStreamWaitEvent(c->s_d2h, ring.filled[b], 0));
+        rc = copy_group(c, true, ring.buf[b], view.chunk_stride, &new_slot[j0], int64_t(k), pool_off,
+                        view.chunk_stride, c->s_d2h);
+        if (rc != LMC_OK) return rc;
+        if (c->cfg.flags & LMC_FLAG_POISON_STAGING)
+            HIPCHK(c, lmc::launch_fill(ring.buf[b], 0xA5, uint64_t(k) * view.chunk_stride, c->s_d2h));
+        HIPCHK(c, hipEventRecord(ring.drained[b], c->s_d2h));
+        ring.used[b] = 1;
+        if ((rc = force_sync(c, c->s_d2h)) != LMC_OK) return rc;
+        j0 += k;
+    }
+    return LMC_OK;
+}
+
 lmc_status_t lmc_store(lmc_ctx_t *c, void *const *kv_layers, const int64_t *slot_mapping,
                        const uint64_t *ids, int64_t n_chunks, void *stream_to_wait_on,
                        uint64_t *ticket_out) {
@@ -540,58 +677,114 @@ lmc_status_t lmc_store(lmc_ctx_t *c, void *const *kv_layers, const int64_t *slot
     Op op;
     op.ticket = c->next_ticket++;
     op.is_store = true;
-    // token processor: which chunks are new, and where they go
-    std::vector<int64_t> new_chunk, new_slot;
-    bool nomem = false;
-    for (int64_t i = 0; i < n_chunks; i++) {
-        if (c->index.find(ids[i]) >= 0) {
-            c->stats.chunks_skipped_dup++;
-            continue;
-        }
-        const int64_t s = c->index.insert(ids[i]);
-        if (s < 0) {
-            nomem = true;
-            c->stats.alloc_failures++;
-            break;
-        }
-        lmc::SlotMeta &m = c->index.meta(s);
-        m.inflight = 1;
-        m.ready_ticket = op.ticket;
-        new_chunk.push_back(i);
-        new_slot.push_back(s);
-    }
-    op.slots = new_slot;
+    std::vector<int64_t> new_chunk;
+    const bool fits = admit_new_chunks(c, ids, n_chunks, &op, &new_chunk);
     c->stats.chunks_stored += new_chunk.size();
-
-    Ring &ring = c->store_ring;
-    const size_t per = size_t(c->cfg.staging_chunks);
-    for (size_t j0 = 0; j0 < new_chunk.size();) {
-        // one launch covers chunks that are consecutive in the caller's slot mapping.
-        // Only the first gather is exposed (later ones hide behind the previous copy),
-        // so the first group is a single chunk and the link starts working at once.
-        const size_t edge = size_t(std::min<int64_t>(c->edge_chunks, int64_t(per)));
-        const size_t cap = (j0 == 0 && edge > 0 && new_chunk.size() > edge) ? edge : per;
-        size_t k = 1;
-        while (k < cap && j0 + k < new_chunk.size() && new_chunk[j0 + k] == new_chunk[j0] + int64_t(k)) k++;
-        const size_t b = size_t(ring.pos++ % ring.buf.size());
-        if (ring.used[b]) HIPCHK(c, hipStreamWaitEvent(c->s_gather, ring.drained[b], 0));
-        rc = timed_launch(c, true, ptrs, slot_mapping + new_chunk[j0] * CT, uint32_t(k), ring.buf[b], c->s_gather);
-        if (rc != LMC_OK) return rc;
-        HIPCHK(c, hipEventRecord(ring.filled[b], c->s_gather));
-        if ((rc = force_sync(c, c->s_gather)) != LMC_OK) return rc;
-        HIPCHK(c, hipStreamWaitEvent(c->s_d2h, ring.filled[b], 0));
-        rc = copy_group(c, true, ring.buf[b], &new_slot[j0], int64_t(k), c->s_d2h);
-        if (rc != LMC_OK) return rc;
-        if (c->cfg.flags & LMC_FLAG_POISON_STAGING)
-            HIPCHK(c, lmc::launch_fill(ring.buf[b], 0xA5, uint64_t(k) * uint64_t(c->chunk_bytes), c->s_d2h));
-        HIPCHK(c, hipEventRecord(ring.drained[b], c->s_d2h));
-        ring.used[b] = 1;
-        if ((rc = force_sync(c, c->s_d2h)) != LMC_OK) return rc;
-        j0 += k;
-    }
+    rc = store_groups(c, lmc::bulk_view(c->kg), 0, ptrs, slot_mapping, new_chunk, op.slots,
+                      c->cfg.staging_chunks, true);
+    if (rc != LMC_OK) return rc;
     rc = finish_op(c, std::move(op), c->s_d2h, !new_chunk.empty(), ticket_out);
     if (rc != LMC_OK) return rc;
-    return nomem ? LMC_ERR_NOMEM : LMC_OK;
+    return fits ? LMC_OK : LMC_ERR_NOMEM;
+}
+
+lmc_status_t lmc_store_begin(lmc_ctx_t *c, const int64_t *slot_mapping, const uint64_t *ids,
+                             int64_t n_chunks, void *stream_to_wait_on, uint64_t *ticket_out) {
+    if (!c || n_chunks < 0 || (n_chunks > 0 && (!slot_mapping || !ids))) return LMC_ERR_INVAL;
+    if (!c->has_device) return LMC_ERR_NODEVICE;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    reap(c);
+    lmc_status_t rc;
+    hipStream_t user = static_cast<hipStream_t>(stream_to_wait_on);
+    const int64_t CT = c->cfg.geom.chunk_tokens;
+    if (n_chunks > 0 && (rc = order_after(c, c->s_gather, user)) != LMC_OK) return rc;
+    if ((rc = validate_slots(c, slot_mapping, n_chunks * CT, c->s_gather)) != LMC_OK) return rc;
+    Op op;
+    op.ticket = c->next_ticket++;
+    op.is_store = true;
+    op.layerwise = true;
+    const bool fits = admit_new_chunks(c, ids, n_chunks, &op, &op.new_chunk);
+    c->stats.chunks_stored += op.new_chunk.size();
+    op.pending = !op.new_chunk.empty();   // nothing new: the ticket is complete at once
+    op.slot_mapping = slot_mapping;
+    op.layer_done.assign(size_t(c->cfg.geom.num_layers), nullptr);
+    if (ticket_out) *ticket_out = op.ticket;
+    c->ops.push_back(std::move(op));
+    return fits ? LMC_OK : LMC_ERR_NOMEM;
+}
+
+lmc_status_t lmc_store_layers(lmc_ctx_t *c, uint64_t ticket, int32_t first_layer, int32_t n_layers,
+                              void *const *kv_layers, void *stream_to_wait_on) {
+    if (!c || !kv_layers || n_layers < 1 || first_layer < 0) return LMC_ERR_INVAL;
+    if (!c->has_device) return LMC_ERR_NODEVICE;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    reap(c);
+    const lmc_kv_geom_t &geom = c->cfg.geom;
+    Op *op = find_op(c, ticket);
+    if (op == nullptr) {
+        // a layer-wise store with nothing new completes at once; its layers are accepted
+        // and ignored so that the caller's per-layer loop needs no special case
+        return (ticket != 0 && ticket < c->next_ticket && first_layer + n_layers <= geom.num_layers)
+                   ? LMC_OK : LMC_ERR_INVAL;
+    }
+    if (!op->pending || first_layer != op->next_layer || first_layer + n_layers > geom.num_layers)
+        return LMC_ERR_INVAL;
+    lmc::LayerPtrs ptrs;
+    lmc_status_t rc = build_layer_ptrs(c, kv_layers, &ptrs);
+    if (rc != LMC_OK) return rc;
+    // this layer's KV was produced by work already on the caller's stream
+    if ((rc = order_after(c, c->s_gather, static_cast<hipStream_t>(stream_to_wait_on))) != LMC_OK) return rc;
+    const lmc::LaunchView view = lmc::layer_view(c->kg, uint32_t(geom.num_planes), uint32_t(first_layer),
+                                                 uint32_t(n_layers));
+    const uint64_t layer_bytes = uint64_t(geom.num_planes) * c->kg.plane_bytes;
+    const int64_t cap = std::min<int64_t>(
+        int64_t(uint64_t(c->cfg.staging_chunks) * uint64_t(c->chunk_bytes) / view.chunk_stride),
+        int64_t(lmc::max_chunks_per_launch(c->kg, view)));
+    rc = store_groups(c, view, uint64_t(first_layer) * layer_bytes, ptrs, op->slot_mapping, op->new_chunk,
+                      op->slots, cap, false);
+    if (rc != LMC_OK) return rc;
+    hipEvent_t e;
+    if ((rc = get_event(c, false, &e)) != LMC_OK) return rc;
+    HIPCHK(c, hipEventRecord(e, c->s_d2h));
+    op->owned_events.push_back(e);
+    for (int32_t l = first_layer; l < first_layer + n_layers; l++) op->layer_done[size_t(l)] = e;
+    op->next_layer = first_layer + n_layers;
+    if (op->next_layer == geom.num_layers) {
+        if ((rc = get_event(c, false, &op->done)) != LMC_OK) return rc;
+        HIPCHK(c, hipEventRecord(op->done, c->s_d2h));
+        op->pending = false;
+    }
+    return LMC_OK;
+}
+
+lmc_status_t lmc_retrieve_layerwise(lmc_ctx_t *c, const uint64_t *ids, int64_t n_chunks,
+                                    const int64_t *slot_mapping, void *const *kv_layers,
+                                    int32_t layers_per_step, void *stream_to_wait_on,
+                                    uint64_t *ticket_out) {
+    if (!c || n_chunks < 0 || !kv_layers || layers_per_step < 1 ||
+        (n_chunks > 0 && (!slot_mapping || !ids)))
+        return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    return do_retrieve(c, ids, n_chunks, slot_mapping, kv_layers, stream_to_wait_on,
+                       std::min(layers_per_step, c->cfg.geom.num_layers), ticket_out);
+}
+
+lmc_status_t lmc_wait_layer(lmc_ctx_t *c, uint64_t ticket, int32_t layer, void *stream) {
+    if (!c || ticket == 0 || layer < 0 || layer >= c->cfg.geom.num_layers) return LMC_ERR_INVAL;
+    if (!c->has_device) return LMC_ERR_NODEVICE;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    if (ticket >= c->next_ticket) return LMC_ERR_INVAL;
+    const Op *op = find_op(c, ticket);
+    if (op == nullptr) return LMC_OK;                       // finished long ago
+    if (!op->layerwise) return LMC_ERR_INVAL;
+    if (op->layer_done.empty() || (op->layer_done[size_t(layer)] == nullptr && !op->pending))
+        return LMC_OK;                                      // nothing was enqueued for it
+    if (op->layer_done[size_t(layer)] == nullptr) return LMC_ERR_BUSY;  // layer not submitted yet
+    HIPCHK(c, hipStreamWaitEvent(static_cast<hipStream_t>(stream), op->layer_done[size_t(layer)], 0));
+    return LMC_OK;
 }
 
 lmc_status_t lmc_retrieve(lmc_ctx_t *c, const uint64_t *ids, int64_t n_chunks,
@@ -600,7 +793,7 @@ lmc_status_t lmc_retrieve(lmc_ctx_t *c, const uint64_t *ids, int64_t n_chunks,
     if (!c || n_chunks < 0 || !kv_layers || (n_chunks > 0 && (!slot_mapping || !ids)))
         return LMC_ERR_INVAL;
     std::lock_guard<std::mutex> lock(c->mu);
-    return do_retrieve(c, ids, n_chunks, slot_mapping, kv_layers, stream_to_signal, ticket_out);
+    return do_retrieve(c, ids, n_chunks, slot_mapping, kv_layers, stream_to_signal, 0, ticket_out);
 }
 
 lmc_status_t lmc_retrieve_batch(lmc_ctx_t *c, int64_t n_req, const int64_t *off,
@@ -615,19 +808,28 @@ lmc_status_t lmc_retrieve_batch(lmc_ctx_t *c, int64_t n_req, const int64_t *off,
     // The requests' chunks and slot mappings are already back to back, so the batch is
     // one stream of chunks: kernel launches and copies run across request borders.
     std::lock_guard<std::mutex> lock(c->mu);
-    return do_retrieve(c, ids, total, slot_mapping, kv_layers, stream_to_signal, ticket_out);
+    return do_retrieve(c, ids, total, slot_mapping, kv_layers, stream_to_signal, 0, ticket_out);
 }
 
 lmc_status_t lmc_wait(lmc_ctx_t *c, uint64_t ticket) {
     if (!c) return LMC_ERR_INVAL;
     std::unique_lock<std::mutex> lock(c->mu);
-    if (ticket == 0) ticket = c->next_ticket - 1;
+    const bool everything = ticket == 0;
+    if (everything) ticket = c->next_ticket - 1;
     if (ticket >= c->next_ticket) return LMC_ERR_INVAL;
     if (!c->has_device) return LMC_OK;
     DeviceScope dev(c);
     hipEvent_t last = nullptr;
-    for (const Op &o : c->ops)
-        if (o.ticket <= ticket && o.done != nullptr) last = o.done;
+    for (const Op &o : c->ops) {
+        if (o.ticket > ticket) continue;
+        if (o.pending) {
+            // a layer-wise store still short of layers cannot be waited for; when it is
+            // merely older than the ticket asked for, it is left out
+            if (everything || o.ticket == ticket) return LMC_ERR_BUSY;
+            continue;
+        }
+        if (o.done != nullptr) last = o.done;
+    }
     if (last != nullptr) {
         lock.unlock();
         hipError_t e = hipEventSynchronize(last);
@@ -661,10 +863,11 @@ static lmc_status_t device_only(lmc_ctx_t *c, bool gather, void *const *kv_layer
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t CT = c->cfg.geom.chunk_tokens;
     if ((rc = validate_slots(c, slot_mapping, n_chunks * CT, s)) != LMC_OK) return rc;
-    const int64_t per = int64_t(lmc::max_chunks_per_launch(c->kg));
+    const lmc::LaunchView view = lmc::bulk_view(c->kg);
+    const int64_t per = int64_t(lmc::max_chunks_per_launch(c->kg, view));
     for (int64_t i0 = 0; i0 < n_chunks; i0 += per) {
         const int64_t k = std::min(per, n_chunks - i0);
-        rc = timed_launch(c, gather, ptrs, slot_mapping + i0 * CT, uint32_t(k),
+        rc = timed_launch(c, gather, view, ptrs, slot_mapping + i0 * CT, uint32_t(k),
                           staging + i0 * c->chunk_bytes, s);
         if (rc != LMC_OK) return rc;
     }
@@ -711,10 +914,12 @@ lmc_status_t lmc_get_host(lmc_ctx_t *c, uint64_t id, void *host_dst) {
     if (c->has_device) reap(c);
     const int64_t s = c->index.find(id);
     if (s < 0) return LMC_ERR_MISS;
-    const uint64_t pending = c->index.meta(s).ready_ticket;
-    if (pending != 0)
-        for (const Op &o : c->ops)
-            if (o.ticket == pending && o.done != nullptr) HIPCHK(c, hipEventSynchronize(o.done));
+    const uint64_t store_ticket = c->index.meta(s).ready_ticket;
+    if (store_ticket != 0) {
+        const Op *o = find_op(c, store_ticket);
+        if (o != nullptr && o->pending) return LMC_ERR_BUSY;
+        if (o != nullptr && o->done != nullptr) HIPCHK(c, hipEventSynchronize(o->done));
+    }
     std::memcpy(host_dst, c->pool + s * c->chunk_bytes, size_t(c->chunk_bytes));
     return LMC_OK;
 }

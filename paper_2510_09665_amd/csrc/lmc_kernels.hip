@@ -65,7 +65,8 @@ __device__ __forceinline__ FastDiv pin(FastDiv f) {
 //   GATHER: chunk[c][lp][r] = valid(slot[c][t]) ? page(lp, slot[c][t])[r % vec_per_row] : 0
 //   else  : if valid(slot[c][t]):  page(lp, slot[c][t])[r % vec_per_row] = chunk[c][lp][r]
 template <int VEC, bool GATHER, bool NT_LD, bool NT_ST>
-__global__ __launch_bounds__(kThreads) void move_rows(const KernelGeom g, const LayerPtrs layers,
+__global__ __launch_bounds__(kThreads) void move_rows(const KernelGeom g, const LaunchView view,
+                                                      const LayerPtrs layers,
                                                       const int64_t *__restrict__ slot_mapping,
                                                       uint8_t *staging, int32_t *bad_flag,
                                                       uint32_t n_blocks_permuted, uint32_t xcd_shift) {
@@ -73,14 +74,16 @@ __global__ __launch_bounds__(kThreads) void move_rows(const KernelGeom g, const 
     // Fetch every kernel argument now, in one batch of scalar loads.  Left alone the
     // compiler loads each field just before its first use, which puts four scalar-load
     // round trips behind the slot load on every wavefront's critical path.
-    const FastDiv by_tiles = pin(g.by_tiles_per_plane), by_lp = pin(g.by_layer_planes),
+    const FastDiv by_tiles = pin(g.by_tiles_per_plane), by_lp = pin(view.by_n_lp),
                   by_row = pin(g.by_vec_per_row), by_run = pin(g.by_vec_per_run),
                   by_bs = pin(g.by_block_size);
+    const uint32_t lp_base = pin(view.lp_base);
+    const uint64_t chunk_stride = pin(view.chunk_stride);
     const uint32_t vec_per_plane = pin(g.vec_per_plane), chunk_tokens = pin(g.chunk_tokens),
                    n_slots = pin(g.n_slots), runs_per_row = pin(g.runs_per_row);
     const int64_t block_stride = pin(g.block_stride), token_stride = pin(g.token_stride),
                   run_stride = pin(g.run_stride);
-    const uint64_t plane_bytes = pin(g.plane_bytes), chunk_bytes = pin(g.chunk_bytes);
+    const uint64_t plane_bytes = pin(g.plane_bytes);
     const uint64_t slots_at = pin(uint64_t(slot_mapping)), staging_at = pin(uint64_t(staging)),
                    bad_flag_at = pin(uint64_t(bad_flag));
 
@@ -97,7 +100,7 @@ __global__ __launch_bounds__(kThreads) void move_rows(const KernelGeom g, const 
     const uint32_t q = by_tiles.div(blk);
     const uint32_t tile = blk - q * by_tiles.d;
     const uint32_t c = by_lp.div(q);
-    const uint32_t lp = q - c * by_lp.d;
+    const uint32_t lp = q - c * by_lp.d;  // plane inside this launch's part of the chunk
     const uint32_t r = tile * kThreads + threadIdx.x;
     if (r >= vec_per_plane) return;
     const uint32_t t = by_row.div(r);
@@ -105,7 +108,7 @@ __global__ __launch_bounds__(kThreads) void move_rows(const KernelGeom g, const 
 
     const int64_t s = load_vec<int64_t, false>(slots_at + (uint64_t(c) * chunk_tokens + t) * 8u);
     // the plane's base pointer is fetched while the slot is on its way
-    const uint64_t layer = pin(uint64_t(layers.p[lp]));
+    const uint64_t layer = pin(uint64_t(layers.p[lp_base + lp]));
     const bool valid = uint64_t(s) < uint64_t(n_slots);  // negative wraps to huge
     if (s >= int64_t(n_slots)) store_vec<int32_t, false>(bad_flag_at, 1);
     const uint32_t su = valid ? uint32_t(s) : 0u;  // slot 0 is always inside the pages
@@ -118,7 +121,7 @@ __global__ __launch_bounds__(kThreads) void move_rows(const KernelGeom g, const 
     }
     const uint64_t page = layer + uint64_t(int64_t(b) * block_stride + int64_t(o) * token_stride +
                                            int64_t(run) * run_stride + int64_t(dv) * VEC);
-    const uint64_t st = staging_at + uint64_t(c) * chunk_bytes + uint64_t(lp) * plane_bytes +
+    const uint64_t st = staging_at + uint64_t(c) * chunk_stride + uint64_t(lp) * plane_bytes +
                         uint64_t(r) * VEC;
     if (GATHER) {
         V v = load_vec<V, NT_LD>(page);
@@ -156,10 +159,11 @@ __global__ __launch_bounds__(kThreads) void fill_bytes(uint8_t *dst, uint8_t val
 }
 
 template <int VEC, bool GATHER>
-hipError_t launch_move_v(const KernelGeom &g, const LaunchShape &s, const LayerPtrs &layers,
-                         const int64_t *slot_mapping, uint32_t n_chunks, uint8_t *staging,
-                         int32_t *bad_flag, hipStream_t stream, hipEvent_t start, hipEvent_t stop) {
-    const uint32_t n_blocks = n_chunks * g.n_layer_planes * g.by_tiles_per_plane.d;
+hipError_t launch_move_v(const KernelGeom &g, const LaunchView &v, const LaunchShape &s,
+                         const LayerPtrs &layers, const int64_t *slot_mapping, uint32_t n_chunks,
+                         uint8_t *staging, int32_t *bad_flag, hipStream_t stream, hipEvent_t start,
+                         hipEvent_t stop) {
+    const uint32_t n_blocks = n_chunks * v.by_n_lp.d * g.by_tiles_per_plane.d;
     if (n_blocks == 0) return hipSuccess;
     uint32_t shift = 0, permuted = 0;
     if (s.xcd_run > 0) {
@@ -169,7 +173,7 @@ hipError_t launch_move_v(const KernelGeom &g, const LaunchShape &s, const LayerP
     dim3 grid(n_blocks), block(kThreads);
 #define LMC_GO(LD, ST)                                                                          \
     hipExtLaunchKernelGGL((move_rows<VEC, GATHER, LD, ST>), grid, block, 0, stream, start, stop, \
-                          0, g, layers, slot_mapping, staging, bad_flag, permuted, shift)
+                          0, g, v, layers, slot_mapping, staging, bad_flag, permuted, shift)
     if (s.nt_load && s.nt_store) LMC_GO(true, true);
     else if (s.nt_load) LMC_GO(true, false);
     else if (s.nt_store) LMC_GO(false, true);
@@ -179,15 +183,16 @@ hipError_t launch_move_v(const KernelGeom &g, const LaunchShape &s, const LayerP
 }
 
 template <bool GATHER>
-hipError_t launch_move(const KernelGeom &g, const LaunchShape &s, const LayerPtrs &layers,
-                       const int64_t *slot_mapping, uint32_t n_chunks, uint8_t *staging,
-                       int32_t *bad_flag, hipStream_t stream, hipEvent_t start, hipEvent_t stop) {
+hipError_t launch_move(const KernelGeom &g, const LaunchView &v, const LaunchShape &s,
+                       const LayerPtrs &layers, const int64_t *slot_mapping, uint32_t n_chunks,
+                       uint8_t *staging, int32_t *bad_flag, hipStream_t stream, hipEvent_t start,
+                       hipEvent_t stop) {
     switch (g.vec) {
-        case 16: return launch_move_v<16, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
-        case 8: return launch_move_v<8, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
-        case 4: return launch_move_v<4, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
-        case 2: return launch_move_v<2, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
-        case 1: return launch_move_v<1, GATHER>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
+        case 16: return launch_move_v<16, GATHER>(g, v, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
+        case 8: return launch_move_v<8, GATHER>(g, v, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
+        case 4: return launch_move_v<4, GATHER>(g, v, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
+        case 2: return launch_move_v<2, GATHER>(g, v, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
+        case 1: return launch_move_v<1, GATHER>(g, v, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start, stop);
     }
     return hipErrorInvalidValue;
 }
@@ -209,23 +214,42 @@ FastDiv make_fastdiv(uint32_t d) {
     return f;
 }
 
-uint32_t max_chunks_per_launch(const KernelGeom &g) {
+uint32_t max_chunks_per_launch(const KernelGeom &g, const LaunchView &v) {
     // the workgroup index is 32-bit and must stay below 2^31 for the fast division
-    return uint32_t(0x7FFFFFFFu / (uint64_t(g.n_layer_planes) * g.by_tiles_per_plane.d));
+    return uint32_t(0x7FFFFFFFu / (uint64_t(v.by_n_lp.d) * g.by_tiles_per_plane.d));
 }
 
-hipError_t launch_gather(const KernelGeom &g, const LaunchShape &s, const LayerPtrs &layers,
-                         const int64_t *slot_mapping, uint32_t n_chunks, uint8_t *staging,
-                         int32_t *bad_flag, hipStream_t stream, hipEvent_t start, hipEvent_t stop) {
-    return launch_move<true>(g, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream, start,
-                             stop);
+LaunchView bulk_view(const KernelGeom &g) {
+    LaunchView v;
+    v.by_n_lp = make_fastdiv(g.n_layer_planes);
+    v.lp_base = 0;
+    v.chunk_stride = g.chunk_bytes;
+    return v;
 }
 
-hipError_t launch_scatter(const KernelGeom &g, const LaunchShape &s, const LayerPtrs &layers,
-                          const int64_t *slot_mapping, uint32_t n_chunks, const uint8_t *staging,
-                          int32_t *bad_flag, hipStream_t stream, hipEvent_t start, hipEvent_t stop) {
-    return launch_move<false>(g, s, layers, slot_mapping, n_chunks, const_cast<uint8_t *>(staging),
-                              bad_flag, stream, start, stop);
+LaunchView layer_view(const KernelGeom &g, uint32_t planes_per_layer, uint32_t first_layer,
+                      uint32_t n_layers) {
+    LaunchView v;
+    v.by_n_lp = make_fastdiv(n_layers * planes_per_layer);
+    v.lp_base = first_layer * planes_per_layer;
+    v.chunk_stride = uint64_t(n_layers) * planes_per_layer * g.plane_bytes;
+    return v;
+}
+
+hipError_t launch_gather(const KernelGeom &g, const LaunchView &v, const LaunchShape &s,
+                         const LayerPtrs &layers, const int64_t *slot_mapping, uint32_t n_chunks,
+                         uint8_t *staging, int32_t *bad_flag, hipStream_t stream, hipEvent_t start,
+                         hipEvent_t stop) {
+    return launch_move<true>(g, v, s, layers, slot_mapping, n_chunks, staging, bad_flag, stream,
+                             start, stop);
+}
+
+hipError_t launch_scatter(const KernelGeom &g, const LaunchView &v, const LaunchShape &s,
+                          const LayerPtrs &layers, const int64_t *slot_mapping, uint32_t n_chunks,
+                          const uint8_t *staging, int32_t *bad_flag, hipStream_t stream,
+                          hipEvent_t start, hipEvent_t stop) {
+    return launch_move<false>(g, v, s, layers, slot_mapping, n_chunks,
+                              const_cast<uint8_t *>(staging), bad_flag, stream, start, stop);
 }
 
 hipError_t launch_check_slots(const int64_t *slot_mapping, uint64_t n, uint32_t n_slots,

@@ -49,7 +49,16 @@ struct KernelGeom {
     uint32_t runs_per_row;
     uint32_t n_layer_planes;  // num_layers * num_planes
     uint32_t vec;             // bytes per lane access: 16, 8, 4, 2 or 1
-    FastDiv by_tiles_per_plane, by_layer_planes, by_vec_per_row, by_vec_per_run, by_block_size;
+    FastDiv by_tiles_per_plane, by_vec_per_row, by_vec_per_run, by_block_size;
+};
+
+// Which part of every chunk one launch moves, and how the chunks lie in the staging
+// buffer.  Bulk mode moves all layer-planes and chunks are chunk_bytes apart; layer-wise
+// mode moves the planes of a few consecutive layers and packs just those.
+struct LaunchView {
+    FastDiv by_n_lp;        // layer-planes per chunk in this launch
+    uint32_t lp_base;       // first layer-plane (index into LayerPtrs)
+    uint64_t chunk_stride;  // bytes between consecutive chunks in the staging buffer
 };
 
 struct LaunchShape {
@@ -63,14 +72,17 @@ struct LaunchShape {
 // (gather), or the reverse (scatter).  bad_flag: device-visible int set to 1 on a slot
 // >= n_slots.  start / stop: optional events (timing enabled) that receive the
 // kernel's own begin and end time stamps; no marker is put on the stream for them.
-hipError_t launch_gather(const KernelGeom &g, const LaunchShape &s, const LayerPtrs &layers,
-                         const int64_t *slot_mapping, uint32_t n_chunks, uint8_t *staging,
-                         int32_t *bad_flag, hipStream_t stream, hipEvent_t start = nullptr,
-                         hipEvent_t stop = nullptr);
-hipError_t launch_scatter(const KernelGeom &g, const LaunchShape &s, const LayerPtrs &layers,
-                          const int64_t *slot_mapping, uint32_t n_chunks, const uint8_t *staging,
-                          int32_t *bad_flag, hipStream_t stream, hipEvent_t start = nullptr,
-                          hipEvent_t stop = nullptr);
+hipError_t launch_gather(const KernelGeom &g, const LaunchView &v, const LaunchShape &s,
+                         const LayerPtrs &layers, const int64_t *slot_mapping, uint32_t n_chunks,
+                         uint8_t *staging, int32_t *bad_flag, hipStream_t stream,
+                         hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
+hipError_t launch_scatter(const KernelGeom &g, const LaunchView &v, const LaunchShape &s,
+                          const LayerPtrs &layers, const int64_t *slot_mapping, uint32_t n_chunks,
+                          const uint8_t *staging, int32_t *bad_flag, hipStream_t stream,
+                          hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
+LaunchView bulk_view(const KernelGeom &g);
+LaunchView layer_view(const KernelGeom &g, uint32_t planes_per_layer, uint32_t first_layer,
+                      uint32_t n_layers);
 // *bad_flag = 1 if any of the n slots is >= n_slots
 hipError_t launch_check_slots(const int64_t *slot_mapping, uint64_t n, uint32_t n_slots,
                               int32_t *bad_flag, hipStream_t stream);
@@ -78,6 +90,6 @@ hipError_t launch_copy(uint8_t *dst, const uint8_t *src, uint64_t nbytes, hipStr
 hipError_t launch_fill(uint8_t *dst, uint8_t value, uint64_t nbytes, hipStream_t stream);
 
 // largest number of chunks one launch may cover (32-bit workgroup index)
-uint32_t max_chunks_per_launch(const KernelGeom &g);
+uint32_t max_chunks_per_launch(const KernelGeom &g, const LaunchView &v);
 
 }  // namespace lmc

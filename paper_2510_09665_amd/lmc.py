@@ -24,7 +24,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblmc.so")
 
 EXPORTS = [
     "lmc_create", "lmc_destroy", "lmc_chunk_bytes", "lmc_pool_slots", "lmc_hash_chunks",
-    "lmc_lookup", "lmc_store", "lmc_retrieve", "lmc_retrieve_batch", "lmc_wait", "lmc_gather",
+    "lmc_lookup", "lmc_store", "lmc_retrieve", "lmc_retrieve_batch", "lmc_retrieve_layerwise",
+    "lmc_store_begin", "lmc_store_layers", "lmc_wait_layer", "lmc_wait", "lmc_gather",
     "lmc_scatter", "lmc_put_host", "lmc_get_host", "lmc_find_slot", "lmc_pin", "lmc_unpin",
     "lmc_clear", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_copy", "lmc_tune",
     "lmc_strerror", "lmc_last_hip_error",
@@ -93,6 +94,10 @@ def _lib():
             "lmc_store": (st, [vp, vp, vp, vp, i64, vp, ctypes.POINTER(u64)]),
             "lmc_retrieve": (st, [vp, vp, i64, vp, vp, vp, ctypes.POINTER(u64)]),
             "lmc_retrieve_batch": (st, [vp, i64, vp, vp, vp, vp, vp, ctypes.POINTER(u64)]),
+            "lmc_retrieve_layerwise": (st, [vp, vp, i64, vp, vp, i32, vp, ctypes.POINTER(u64)]),
+            "lmc_store_begin": (st, [vp, vp, vp, i64, vp, ctypes.POINTER(u64)]),
+            "lmc_store_layers": (st, [vp, u64, i32, i32, vp, vp]),
+            "lmc_wait_layer": (st, [vp, u64, i32, vp]),
             "lmc_wait": (st, [vp, u64]),
             "lmc_gather": (st, [vp, vp, vp, i64, vp, vp]),
             "lmc_scatter": (st, [vp, vp, vp, i64, vp, vp]),
@@ -238,6 +243,32 @@ class Context:
                                        ctypes.byref(t))
         self._check(rc, "lmc_retrieve_batch", t.value)
         return t.value
+
+    def retrieve_layerwise(self, chunk_ids, slot_mapping, kv_layers, layers_per_step=1,
+                           stream_to_wait_on=None):
+        ids, ip = _host(chunk_ids, np.uint64)
+        t = ctypes.c_uint64()
+        rc = _lib().lmc_retrieve_layerwise(self._h, ip, ids.size, _dev(slot_mapping),
+                                           self._layers(kv_layers), layers_per_step,
+                                           _stream(stream_to_wait_on), ctypes.byref(t))
+        self._check(rc, "lmc_retrieve_layerwise", t.value)
+        return t.value
+
+    def store_begin(self, slot_mapping, chunk_ids, stream_to_wait_on=None):
+        ids, ip = _host(chunk_ids, np.uint64)
+        t = ctypes.c_uint64()
+        rc = _lib().lmc_store_begin(self._h, _dev(slot_mapping), ip, ids.size,
+                                    _stream(stream_to_wait_on), ctypes.byref(t))
+        self._check(rc, "lmc_store_begin", t.value)
+        return t.value
+
+    def store_layers(self, ticket, first_layer, n_layers, kv_layers, stream_to_wait_on=None):
+        self._check(_lib().lmc_store_layers(self._h, ticket, first_layer, n_layers,
+                                            self._layers(kv_layers), _stream(stream_to_wait_on)),
+                    "lmc_store_layers")
+
+    def wait_layer(self, ticket, layer, stream=None):
+        self._check(_lib().lmc_wait_layer(self._h, ticket, layer, _stream(stream)), "lmc_wait_layer")
 
     def wait(self, ticket=0):
         self._check(_lib().lmc_wait(self._h, ticket), "lmc_wait")

@@ -1,0 +1,198 @@
+"""GPU parity of the layer-wise store / retrieve (paper section 5.2 "Layer-wise
+pipelining"; start/wait_load_kv and start/wait_store_kv of section 6, Table 2) against
+the CPU oracle.  Layer-wise mode reaches exactly the bulk result, so the oracle is the
+same; what is added is the per-layer ordering."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2510_09665_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    # name: (config, geometry overrides, tokens, staging_chunks, layers_per_step, flags)
+    "tiny_k1": ("tiny", {}, 256, 1, 1, 0),
+    "llama8b_full_k1": ("llama3_8b", {}, 4096, 2, 1, 0),
+    "llama8b_k5_ragged": ("llama3_8b", dict(NB=1024), 6 * 256, 1, 5, "poison"),
+    "many_groups_per_layer": ("llama3_8b", dict(L=4, NB=1024), 24 * 256, 1, 1, "poison"),
+    "mla_fp8_k3": ("mla_fp8", {}, 8192, 1, 3, 0),
+    "hnd_k2": ("llama3_8b", dict(L=6, NB=512, layout="HND"), 8 * 256, 2, 2, 0),
+    "all_layers_in_one_step": ("tiny", {}, 256, 1, 99, 0),
+}
+
+
+def _setup(case):
+    from gpu_util import PagedKV
+    from paper_2510_09665_amd import lmc
+    name, ov, n_tok, staging, k, flags = CASES[case]
+    g = W.geometry(name, **ov)
+    seq = W.sequence(name, g, n_tokens=n_tok)
+    rng = W.rng_for(name, stream=3)
+    src = PagedKV(g, seq["store_blocks"], rng)
+    dst = PagedKV(g, seq["load_blocks"], fill="sentinel")
+    f = lmc.LMC_FLAG_POISON_STAGING if flags == "poison" else 0
+    n_chunks = n_tok // g.CT
+    ctx = lmc.Context(g, n_chunks * g.chunk_bytes, staging_chunks=staging, flags=f | lmc.LMC_FLAG_TIMING)
+    return lmc, g, seq, src, dst, ctx, k, n_chunks
+
+
+def _expected_chunks(g, src, seq, n_chunks):
+    sl = src.compact_slots(seq["store_slots"]).reshape(n_chunks, g.CT)
+    return [oracle.gather_chunk(src.gc, src.host, s) for s in sl]
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_layerwise_retrieve_matches_oracle(case):
+    import torch
+    from gpu_util import assert_layers_equal, slots_to_device
+    lmc, g, seq, src, dst, ctx, k, n_chunks = _setup(case)
+    stream = torch.cuda.current_stream()
+    with ctx as c:
+        ids = c.hash_chunks(seq["tokens"])
+        d_store, d_load = slots_to_device(seq["store_slots"]), slots_to_device(seq["load_slots"])
+        c.wait(c.store(src.dev, d_store, ids, stream))
+        c.reset_stats()
+        t = c.retrieve_layerwise(ids, d_load, dst.dev, k, stream)
+        c.wait(t)
+        torch.cuda.synchronize()
+        chunks = _expected_chunks(g, src, seq, n_chunks)
+        cs = dst.compact_slots(seq["load_slots"]).reshape(n_chunks, g.CT)
+        for ch, s in zip(chunks, cs):
+            oracle.scatter_chunk(dst.gc, ch, s, dst.host)
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host, case)
+        assert dst.untracked_blocks_untouched()
+        st = c.get_stats()
+        assert st["bytes_h2d"] == st["bytes_scattered"] == n_chunks * g.chunk_bytes
+        steps = -(-g.L // min(k, g.L))
+        assert st["scatter_launches"] >= steps
+
+
+@pytest.mark.parametrize("case", ["llama8b_full_k1", "mla_fp8_k3"])
+def test_each_layer_is_complete_when_its_wait_returns(case):
+    """A consumer stream waits for layer l, then reads layer l's pages at once (while the
+    later layers are still loading).  What it read must already be the final content."""
+    import torch
+    from gpu_util import slots_to_device
+    lmc, g, seq, src, dst, ctx, k, n_chunks = _setup(case)
+    stream = torch.cuda.current_stream()
+    consumer = torch.cuda.Stream()
+    lb = torch.from_numpy(seq["load_blocks"]).cuda()
+    with ctx as c:
+        ids = c.hash_chunks(seq["tokens"])
+        d_store, d_load = slots_to_device(seq["store_slots"]), slots_to_device(seq["load_slots"])
+        c.wait(c.store(src.dev, d_store, ids, stream))
+        torch.cuda.synchronize()
+        t = c.retrieve_layerwise(ids, d_load, dst.dev, k, stream)
+        snaps = []
+        for l in range(g.L):
+            c.wait_layer(t, l, consumer)
+            with torch.cuda.stream(consumer):
+                snaps.append(dst.dev[l].view(g.P, g.NB, g.block_stride)[:, lb].clone())
+        consumer.synchronize()
+        c.wait(t)
+        c.wait_layer(t, g.L - 1, consumer)          # a finished ticket: nothing to wait for
+        chunks = _expected_chunks(g, src, seq, n_chunks)
+        cs = dst.compact_slots(seq["load_slots"]).reshape(n_chunks, g.CT)
+        for ch, s in zip(chunks, cs):
+            oracle.scatter_chunk(dst.gc, ch, s, dst.host)
+        for l in range(g.L):
+            assert np.array_equal(snaps[l].view(-1).cpu().numpy(), dst.host[l]), "layer %d" % l
+        with pytest.raises(lmc.LMCError) as e:
+            c.wait_layer(t, g.L, consumer)
+        assert e.value.status == lmc.LMC_ERR_INVAL
+
+
+def _status(fn):
+    from paper_2510_09665_amd import lmc
+    try:
+        fn()
+        return 0
+    except lmc.LMCError as e:
+        return e.status
+
+
+@pytest.mark.parametrize("case", ["tiny_k1", "llama8b_k5_ragged", "many_groups_per_layer", "mla_fp8_k3", "hnd_k2"])
+def test_layerwise_store_matches_oracle(case):
+    """The 'engine' writes layer l's KV on its stream and submits the layer at once; the
+    pool must end up holding exactly the oracle's chunks."""
+    import torch
+    from gpu_util import PagedKV, slots_to_device
+    lmc, g, seq, src, dst, ctx, k, n_chunks = _setup(case)
+    stream = torch.cuda.current_stream()
+    tb = torch.from_numpy(src.blocks).cuda()
+    live = PagedKV(g, seq["store_blocks"], fill="sentinel")     # pages that fill up layer by layer
+    with ctx as c:
+        ids = c.hash_chunks(seq["tokens"])
+        d_store = slots_to_device(seq["store_slots"])
+        t = c.store_begin(d_store, ids, stream)
+        assert c.lookup(ids) == n_chunks                          # visible at once
+        k = min(k, g.L)
+        for l0 in range(0, g.L, k):
+            kk = min(k, g.L - l0)
+            for l in range(l0, l0 + kk):                          # forward pass produces the layer
+                live.dev[l].view(g.P, g.NB, g.block_stride)[:, tb] = \
+                    src.dev[l].view(g.P, g.NB, g.block_stride)[:, tb]
+            # layers are still missing: the ticket cannot be waited for yet
+            assert _status(lambda: c.wait(t)) == lmc.LMC_ERR_BUSY
+            c.store_layers(t, l0, kk, live.dev, stream)
+            c.wait_layer(t, l0, stream)                           # wait_store_kv(layer): device-side
+        c.wait(t)
+        for i, want in zip(ids.tolist(), _expected_chunks(g, src, seq, n_chunks)):
+            assert np.array_equal(c.get_host(i), want), "pool chunk"
+        st = c.get_stats()
+        assert st["bytes_d2h"] == st["bytes_gathered"] == n_chunks * g.chunk_bytes
+        # the same ids again: nothing is new, the ticket is complete at once
+        t2 = c.store_begin(d_store, ids, stream)
+        c.store_layers(t2, 0, g.L, live.dev, stream)              # accepted and ignored
+        c.wait(t2)
+        assert c.get_stats()["chunks_skipped_dup"] == n_chunks
+
+
+def test_pending_layerwise_store_rules():
+    import torch
+    from gpu_util import PagedKV, slots_to_device
+    from paper_2510_09665_amd import lmc
+    g = W.geometry("tiny", L=4)
+    rng = np.random.default_rng(9)
+    kv = PagedKV(g, np.arange(g.NB), rng)
+    slots = rng.permutation(g.n_slots)[:3 * g.CT].reshape(3, g.CT)
+    stream = torch.cuda.current_stream()
+    with lmc.Context(g, 4 * g.chunk_bytes) as c:
+        d0 = slots_to_device(slots[0])
+        c.wait(c.store(kv.dev, d0, [10], stream))                # chunk 10 is present
+        d = slots_to_device(slots)
+        t = c.store_begin(d, [10, 11, 12], stream)                # 11 and 12 are new
+        assert c.lookup([10, 11, 12]) == 3
+        assert (c.find_slot(11), c.find_slot(12)) == (1, 2)
+        assert _status(lambda: c.store_layers(t, 1, 1, kv.dev, stream)) == lmc.LMC_ERR_INVAL   # gap
+        assert _status(lambda: c.store_layers(t, 0, 5, kv.dev, stream)) == lmc.LMC_ERR_INVAL   # too many
+        c.store_layers(t, 0, 2, kv.dev, stream)
+        assert _status(lambda: c.store_layers(t, 0, 1, kv.dev, stream)) == lmc.LMC_ERR_INVAL   # again
+        assert _status(lambda: c.wait(t)) == lmc.LMC_ERR_BUSY
+        assert _status(lambda: c.wait()) == lmc.LMC_ERR_BUSY
+        assert _status(lambda: c.get_host(11)) == lmc.LMC_ERR_BUSY
+        assert _status(lambda: c.clear([12])) == lmc.LMC_ERR_BUSY
+        dst = PagedKV(g, np.arange(g.NB), fill="sentinel")
+        assert _status(lambda: c.retrieve([11], d0, dst.dev, stream)) == lmc.LMC_ERR_BUSY
+        assert _status(lambda: c.retrieve_layerwise([10, 11], d, dst.dev, 1, stream)) == lmc.LMC_ERR_BUSY
+        c.wait_layer(t, 1, stream)
+        assert _status(lambda: c.wait_layer(t, 2, stream)) == lmc.LMC_ERR_BUSY               # not submitted
+        c.wait(c.retrieve([10], d0, dst.dev, stream))            # an unrelated chunk still works
+        c.store_layers(t, 2, 2, kv.dev, stream)
+        # complete now: retrieve without a host wait, ordered on the device
+        d12 = slots_to_device(slots[1:3])
+        t2 = c.retrieve_layerwise([11, 12], d12, dst.dev, 2, stream)
+        c.wait(t2)
+        c.wait(t)
+        torch.cuda.synchronize()
+        for i, s in ((10, slots[0]), (11, slots[1]), (12, slots[2])):
+            want = oracle.gather_chunk(g, kv.host, s)
+            assert np.array_equal(c.get_host(i), want)
+            oracle.scatter_chunk(g, want, s, dst.host)
+        from gpu_util import assert_layers_equal
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host)
+        assert _status(lambda: c.wait_layer(t + 100, 0, stream)) == lmc.LMC_ERR_INVAL
+        t3 = c.store(kv.dev, d0, [99], stream)
+        assert _status(lambda: c.wait_layer(t3, 0, stream)) in (lmc.LMC_ERR_INVAL, 0)        # not layer-wise (or done)
+        c.wait()

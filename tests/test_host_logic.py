@@ -78,6 +78,10 @@ def test_data_path_refuses_to_run_without_a_device():
         for call in (lambda: c.store(fake, 0x1000, [1]),
                      lambda: c.retrieve([1], 0x1000, fake),
                      lambda: c.retrieve_batch([0, 1], [1], 0x1000, fake),
+                     lambda: c.retrieve_layerwise([1], 0x1000, fake),
+                     lambda: c.store_begin(0x1000, [1]),
+                     lambda: c.store_layers(1, 0, 1, fake),
+                     lambda: c.wait_layer(1, 0),
                      lambda: c.gather(fake, 0x1000, 1, 0x1000),
                      lambda: c.scatter(0x1000, 0x1000, 1, fake),
                      lambda: c.copy(0x1000, 0x2000, 16),
