@@ -20,6 +20,9 @@ Also reported in the same JSON line:
                kernel of the same size as the achievable ceiling
   link         hipMemcpyAsync peak between the pinned pool and the GPU per direction,
                and store / retrieve payload rate as a fraction of it
+  layerwise    the same request moved layer by layer (rectangle copies + kernels over
+               one or four layers), as a fraction of the link peak, and how soon layer 0
+               is usable compared with the bulk retrieve
   cpu_baseline the CPU oracle doing the same store + retrieve on the same 16 chunks,
                chunks fanned out over host threads
 """
@@ -95,9 +98,9 @@ def main():
     ap.add_argument("--staging-chunks", type=int, default=16)
     ap.add_argument("--num-staging", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--legs", default="pipeline,link,device,cpu",
-                    help="comma list of pipeline (always run), link, device, cpu: the extra "
-                         "measurements to make; profiling runs use a subset")
+    ap.add_argument("--legs", default="pipeline,link,device,layerwise,cpu",
+                    help="comma list of pipeline (always run), link, device, layerwise, cpu: the "
+                         "extra measurements to make; profiling runs use a subset")
     ap.add_argument("--tune", action="append", default=[], help="key=value for lmc_tune")
     args = ap.parse_args()
     legs = set(args.legs.split(","))
@@ -262,6 +265,52 @@ def main():
             "scatter_frac_of_hbm_peak": round(2 * payload_one_way / tsc / 1e9 / HBM_PEAK_GBPS, 4),
         }
         del stagings
+    # layer-wise mode: the same request moved layer by layer, alone and with a consumer /
+    # producer that works on each layer as soon as it is there
+    layerwise = None
+    if "layerwise" in legs:
+        ctx.tune("timing", 0)
+        ids = ctx.hash_chunks(seq["tokens"])
+        h2d, d2h = ctx.measure_link(512 << 20, reps=3)
+        consumer = torch.cuda.Stream()
+        layerwise = {}
+        for k in (1, 4):
+            def lw_store():
+                ctx.clear(ids)
+                t = ctx.store_begin(d_store, ids, stream)
+                for l0 in range(0, g.L, k):
+                    ctx.store_layers(t, l0, min(k, g.L - l0), src, stream)
+                ctx.wait(t)
+            def lw_load():
+                t = ctx.retrieve_layerwise(ids, d_load, dst, k, stream)
+                for l in range(g.L):
+                    ctx.wait_layer(t, l, consumer)
+                ctx.wait(t)
+            ts, tl = timed(lw_store), timed(lw_load)
+            layerwise["layers_per_step_%d" % k] = {
+                "store_gbps": round(payload_one_way / ts / 1e9, 2),
+                "retrieve_gbps": round(payload_one_way / tl / 1e9, 2),
+                "store_frac_of_d2h_peak": round(payload_one_way / ts / 1e9 / d2h, 4),
+                "retrieve_frac_of_h2d_peak": round(payload_one_way / tl / 1e9 / h2d, 4),
+            }
+        # time to first layer: how long a consumer waits before it can start on layer 0
+        def first_layer(mode):
+            torch.cuda.synchronize()
+            a = time.perf_counter()
+            if mode == "layerwise":
+                t = ctx.retrieve_layerwise(ids, d_load, dst, 1, stream)
+                ctx.wait_layer(t, 0, consumer)
+            else:
+                t = ctx.retrieve(ids, d_load, dst, consumer)
+            consumer.synchronize()
+            b = time.perf_counter()
+            ctx.wait(t)
+            return (b - a) * 1e3
+        layerwise["ms_until_layer0_usable"] = {
+            "layerwise": round(min(first_layer("layerwise") for _ in range(4)), 3),
+            "bulk": round(min(first_layer("bulk") for _ in range(4)), 3)}
+        ctx.clear(ids)
+
     ctx.destroy()
     del src, dst
     torch.cuda.empty_cache()
@@ -282,6 +331,8 @@ def main():
         out["device"] = device
     if link:
         out["link"] = link
+    if layerwise:
+        out["layerwise"] = layerwise
     if "cpu" in legs:
         out["cpu_baseline"] = cpu_baseline(g, seq)
     print(json.dumps(out), flush=True)

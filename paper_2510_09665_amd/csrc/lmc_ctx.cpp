@@ -27,8 +27,14 @@
 
 namespace {
 
+// Staging ring of one direction.  The memory is num_staging allocations of buf_bytes;
+// it is handed out in slots of slot_bytes (bulk mode: one slot per allocation;
+// layer-wise mode: many small slots, so that a call seldom has to wait for a slot).
+// Each slot has a `filled` event (producer done) and a `drained` event (consumer done).
 struct Ring {
     std::vector<uint8_t *> buf;
+    uint64_t buf_bytes = 0, slot_bytes = 0;
+    uint32_t slots_per_buf = 1;
     std::vector<hipEvent_t> filled, drained;
     std::vector<char> used;
     uint64_t pos = 0;
@@ -327,6 +333,67 @@ lmc_status_t finish_op(lmc_ctx *c, Op &&op, hipStream_t last_stream, bool enqueu
     return LMC_OK;
 }
 
+lmc_status_t free_ring(Ring &r) {
+    for (uint8_t *p : r.buf)
+        if (p) (void)hipFree(p);
+    r.buf.clear();
+    return LMC_OK;
+}
+
+lmc_status_t make_ring(lmc_ctx *c, Ring &r) {
+    const size_t n = size_t(c->cfg.num_staging);
+    r.buf_bytes = uint64_t(c->cfg.staging_chunks) * uint64_t(c->chunk_bytes);
+    r.buf.assign(n, nullptr);
+    for (size_t i = 0; i < n; i++) {
+        hipError_t e = hipMalloc(reinterpret_cast<void **>(&r.buf[i]), r.buf_bytes);
+        if (e != hipSuccess) {
+            c->last_hip_error = int32_t(e);
+            return e == hipErrorOutOfMemory ? LMC_ERR_NOMEM : LMC_ERR_HIP;
+        }
+    }
+    return LMC_OK;
+}
+
+// Switch the ring to slots of slot_bytes.  When the size changes, the producer stream
+// first waits for everything the consumer stream has been given, so no slot of the old
+// division is still being read when the new division is written.
+lmc_status_t ring_reslot(lmc_ctx *c, Ring &r, uint64_t slot_bytes, hipStream_t producer,
+                         hipStream_t consumer) {
+    if (slot_bytes == r.slot_bytes) return LMC_OK;
+    if (r.slot_bytes != 0) {
+        lmc_status_t rc = order_after(c, producer, consumer);
+        if (rc != LMC_OK) return rc;
+    }
+    r.slot_bytes = slot_bytes;
+    r.slots_per_buf = uint32_t(std::max<uint64_t>(1, std::min<uint64_t>(r.buf_bytes / slot_bytes, 32)));
+    const size_t total = r.buf.size() * r.slots_per_buf;
+    while (r.filled.size() < total) {
+        hipEvent_t a, b;
+        lmc_status_t rc = get_event(c, false, &a);
+        if (rc == LMC_OK) rc = get_event(c, false, &b);
+        if (rc != LMC_OK) return rc;
+        r.filled.push_back(a);
+        r.drained.push_back(b);
+    }
+    r.used.assign(total, 0);
+    r.pos = 0;
+    return LMC_OK;
+}
+
+// Next slot in turn: its index (for the events) and its address.
+size_t ring_next(Ring &r, uint8_t **ptr) {
+    const size_t total = r.buf.size() * r.slots_per_buf;
+    const size_t idx = size_t(r.pos++ % total);
+    *ptr = r.buf[idx / r.slots_per_buf] + uint64_t(idx % r.slots_per_buf) * r.slot_bytes;
+    return idx;
+}
+
+// Layer-wise mode: how many chunks' share of `view` one group (one slot, one launch) takes.
+int64_t layer_group_chunks(const lmc_ctx *c, const Ring &r, const lmc::LaunchView &view, int64_t n_chunks) {
+    const int64_t fit = int64_t(r.buf_bytes / view.chunk_stride);
+    return std::max<int64_t>(1, std::min({n_chunks, fit, int64_t(lmc::max_chunks_per_launch(c->kg, view))}));
+}
+
 // A chunk whose store is still on its way to the pool must be loaded after that store:
 // the H2D stream waits for the newest such store (stores complete in order on one
 // stream).  A layer-wise store that has not been submitted completely cannot be waited
@@ -387,18 +454,19 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
     // one group: copies into the next ring buffer on the H2D stream, scatter on the
     // scatter stream; the buffer is released when the scatter has read it
     auto load_group = [&](const lmc::LaunchView &view, uint64_t pool_off, int64_t i0, int64_t k) -> lmc_status_t {
-        const size_t b = size_t(ring.pos++ % ring.buf.size());
+        uint8_t *buf;
+        const size_t b = ring_next(ring, &buf);
         if (ring.used[b]) HIPCHK(c, hipStreamWaitEvent(c->s_h2d, ring.drained[b], 0));
-        lmc_status_t r = copy_group(c, false, ring.buf[b], view.chunk_stride, &pool_slots[size_t(i0)], k,
+        lmc_status_t r = copy_group(c, false, buf, view.chunk_stride, &pool_slots[size_t(i0)], k,
                                     pool_off, view.chunk_stride, c->s_h2d);
         if (r != LMC_OK) return r;
         HIPCHK(c, hipEventRecord(ring.filled[b], c->s_h2d));
         if ((r = force_sync(c, c->s_h2d)) != LMC_OK) return r;
         HIPCHK(c, hipStreamWaitEvent(c->s_scatter, ring.filled[b], 0));
-        r = timed_launch(c, false, view, ptrs, slot_mapping + i0 * CT, uint32_t(k), ring.buf[b], c->s_scatter);
+        r = timed_launch(c, false, view, ptrs, slot_mapping + i0 * CT, uint32_t(k), buf, c->s_scatter);
         if (r != LMC_OK) return r;
         if (c->cfg.flags & LMC_FLAG_POISON_STAGING)
-            HIPCHK(c, lmc::launch_fill(ring.buf[b], 0xA5, uint64_t(k) * view.chunk_stride, c->s_scatter));
+            HIPCHK(c, lmc::launch_fill(buf, 0xA5, uint64_t(k) * view.chunk_stride, c->s_scatter));
         HIPCHK(c, hipEventRecord(ring.drained[b], c->s_scatter));
         ring.used[b] = 1;
         return force_sync(c, c->s_scatter);
@@ -406,6 +474,7 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
 
     if (!op.layerwise) {
         const lmc::LaunchView view = lmc::bulk_view(c->kg);
+        if ((rc = ring_reslot(c, ring, ring.buf_bytes, c->s_h2d, c->s_scatter)) != LMC_OK) return rc;
         // The link is the bottleneck and every scatter but the last hides behind the next
         // copy, so the last group is a single chunk: only its scatter is exposed.
         const int64_t edge = std::min<int64_t>(c->edge_chunks, per);
@@ -423,8 +492,10 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
         for (int32_t l0 = 0; l0 < L; l0 += layers_per_step) {
             const int32_t kk = std::min(layers_per_step, L - l0);
             const lmc::LaunchView view = lmc::layer_view(c->kg, uint32_t(P), uint32_t(l0), uint32_t(kk));
-            const int64_t cap = std::min<int64_t>(int64_t(uint64_t(per) * cb / view.chunk_stride),
-                                                  int64_t(lmc::max_chunks_per_launch(c->kg, view)));
+            const int64_t cap = layer_group_chunks(c, ring, view, n_chunks);
+            if ((rc = ring_reslot(c, ring, (uint64_t(cap) * view.chunk_stride + 255) / 256 * 256, c->s_h2d,
+                                  c->s_scatter)) != LMC_OK)
+                return rc;
             for (int64_t i0 = 0; i0 < n_chunks; i0 += cap)
                 if ((rc = load_group(view, uint64_t(l0) * layer_bytes, i0, std::min(cap, n_chunks - i0))) != LMC_OK)
                     return rc;
@@ -444,33 +515,6 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
     // bulk: the caller's stream continues when everything is in place; layer-wise: the
     // caller orders its streams per layer with lmc_wait_layer
     if (!layerwise) HIPCHK(c, hipStreamWaitEvent(user, c->ops.back().done, 0));
-    return LMC_OK;
-}
-
-lmc_status_t free_ring(Ring &r) {
-    for (uint8_t *p : r.buf)
-        if (p) (void)hipFree(p);
-    r.buf.clear();
-    return LMC_OK;
-}
-
-lmc_status_t make_ring(lmc_ctx *c, Ring &r) {
-    const size_t n = size_t(c->cfg.num_staging);
-    const size_t bytes = size_t(c->cfg.staging_chunks) * size_t(c->chunk_bytes);
-    r.buf.assign(n, nullptr);
-    r.filled.assign(n, nullptr);
-    r.drained.assign(n, nullptr);
-    r.used.assign(n, 0);
-    for (size_t i = 0; i < n; i++) {
-        hipError_t e = hipMalloc(reinterpret_cast<void **>(&r.buf[i]), bytes);
-        if (e != hipSuccess) {
-            c->last_hip_error = int32_t(e);
-            return e == hipErrorOutOfMemory ? LMC_ERR_NOMEM : LMC_ERR_HIP;
-        }
-        lmc_status_t rc = get_event(c, false, &r.filled[i]);
-        if (rc == LMC_OK) rc = get_event(c, false, &r.drained[i]);
-        if (rc != LMC_OK) return rc;
-    }
     return LMC_OK;
 }
 
@@ -636,19 +680,20 @@ static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64
         const size_t cap = (j0 == 0 && edge > 0 && new_chunk.size() > edge) ? edge : per;
         size_t k = 1;
         while (k < cap && j0 + k < new_chunk.size() && new_chunk[j0 + k] == new_chunk[j0] + int64_t(k)) k++;
-        const size_t b = size_t(ring.pos++ % ring.buf.size());
+        uint8_t *buf;
+        const size_t b = ring_next(ring, &buf);
         if (ring.used[b]) HIPCHK(c, hipStreamWaitEvent(c->s_gather, ring.drained[b], 0));
         lmc_status_t rc = timed_launch(c, true, view, ptrs, slot_mapping + new_chunk[j0] * CT, uint32_t(k),
-                                       ring.buf[b], c->s_gather);
+                                       buf, c->s_gather);
         if (rc != LMC_OK) return rc;
         HIPCHK(c, hipEventRecord(ring.filled[b], c->s_gather));
         if ((rc = force_sync(c, c->s_gather)) != LMC_OK) return rc;
         HIPCHK(c, hipStreamWaitEvent(c->s_d2h, ring.filled[b], 0));
-        rc = copy_group(c, true, ring.buf[b], view.chunk_stride, &new_slot[j0], int64_t(k), pool_off,
+        rc = copy_group(c, true, buf, view.chunk_stride, &new_slot[j0], int64_t(k), pool_off,
                         view.chunk_stride, c->s_d2h);
         if (rc != LMC_OK) return rc;
         if (c->cfg.flags & LMC_FLAG_POISON_STAGING)
-            HIPCHK(c, lmc::launch_fill(ring.buf[b], 0xA5, uint64_t(k) * view.chunk_stride, c->s_d2h));
+            HIPCHK(c, lmc::launch_fill(buf, 0xA5, uint64_t(k) * view.chunk_stride, c->s_d2h));
         HIPCHK(c, hipEventRecord(ring.drained[b], c->s_d2h));
         ring.used[b] = 1;
         if ((rc = force_sync(c, c->s_d2h)) != LMC_OK) return rc;
@@ -680,6 +725,7 @@ lmc_status_t lmc_store(lmc_ctx_t *c, void *const *kv_layers, const int64_t *slot
     std::vector<int64_t> new_chunk;
     const bool fits = admit_new_chunks(c, ids, n_chunks, &op, &new_chunk);
     c->stats.chunks_stored += new_chunk.size();
+    if ((rc = ring_reslot(c, c->store_ring, c->store_ring.buf_bytes, c->s_gather, c->s_d2h)) != LMC_OK) return rc;
     rc = store_groups(c, lmc::bulk_view(c->kg), 0, ptrs, slot_mapping, new_chunk, op.slots,
                       c->cfg.staging_chunks, true);
     if (rc != LMC_OK) return rc;
@@ -739,9 +785,10 @@ lmc_status_t lmc_store_layers(lmc_ctx_t *c, uint64_t ticket, int32_t first_layer
     const lmc::LaunchView view = lmc::layer_view(c->kg, uint32_t(geom.num_planes), uint32_t(first_layer),
                                                  uint32_t(n_layers));
     const uint64_t layer_bytes = uint64_t(geom.num_planes) * c->kg.plane_bytes;
-    const int64_t cap = std::min<int64_t>(
-        int64_t(uint64_t(c->cfg.staging_chunks) * uint64_t(c->chunk_bytes) / view.chunk_stride),
-        int64_t(lmc::max_chunks_per_launch(c->kg, view)));
+    const int64_t cap = layer_group_chunks(c, c->store_ring, view, int64_t(op->new_chunk.size()));
+    if ((rc = ring_reslot(c, c->store_ring, (uint64_t(cap) * view.chunk_stride + 255) / 256 * 256, c->s_gather,
+                          c->s_d2h)) != LMC_OK)
+        return rc;
     rc = store_groups(c, view, uint64_t(first_layer) * layer_bytes, ptrs, op->slot_mapping, op->new_chunk,
                       op->slots, cap, false);
     if (rc != LMC_OK) return rc;

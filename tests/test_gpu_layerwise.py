@@ -196,3 +196,48 @@ def test_pending_layerwise_store_rules():
         t3 = c.store(kv.dev, d0, [99], stream)
         assert _status(lambda: c.wait_layer(t3, 0, stream)) in (lmc.LMC_ERR_INVAL, 0)        # not layer-wise (or done)
         c.wait()
+
+
+def test_bulk_and_layerwise_calls_share_the_rings_safely():
+    """Bulk and layer-wise calls divide the same staging memory differently.  Enqueue them
+    back to back without host waits, with released staging overwritten at once: every
+    result must still be exact."""
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    from paper_2510_09665_amd import lmc
+    g = W.geometry("llama3_8b", L=6, NB=2048)
+    rng = np.random.default_rng(31)
+    n = 10
+    blocks = rng.permutation(g.NB)
+    bpc = g.CT // g.BS
+    src = PagedKV(g, blocks[:n * bpc], rng)
+    dsts = [PagedKV(g, blocks[(i + 1) * n * bpc:(i + 2) * n * bpc], fill="sentinel") for i in range(4)]
+    s_slots = W.slots_from_blocks(g, src.blocks, n * g.CT)
+    stream = torch.cuda.current_stream()
+    ids = np.arange(100, 100 + n, dtype=np.uint64)
+    with lmc.Context(g, 2 * n * g.chunk_bytes, staging_chunks=3, flags=lmc.LMC_FLAG_POISON_STAGING) as c:
+        d_s = slots_to_device(s_slots)
+        # store: first half in bulk, second half layer by layer, enqueued back to back
+        t1 = c.store(src.dev, d_s, ids[:5], stream)
+        d_s2 = slots_to_device(s_slots[5 * g.CT:])
+        t2 = c.store_begin(d_s2, ids[5:], stream)
+        for l in range(0, g.L, 2):
+            c.store_layers(t2, l, 2, src.dev, stream)
+        # retrieve four times, alternating the two modes, no host wait anywhere
+        d_l = [slots_to_device(W.slots_from_blocks(g, d.blocks, n * g.CT)) for d in dsts]
+        c.retrieve(ids, d_l[0], dsts[0].dev, stream)
+        c.retrieve_layerwise(ids, d_l[1], dsts[1].dev, 1, stream)
+        c.retrieve(ids, d_l[2], dsts[2].dev, stream)
+        c.retrieve_layerwise(ids, d_l[3], dsts[3].dev, 4, stream)
+        c.wait()
+        torch.cuda.synchronize()
+        chunks = [oracle.gather_chunk(src.gc, src.host, s)
+                  for s in src.compact_slots(s_slots).reshape(n, g.CT)]
+        for i, ch in zip(ids.tolist(), chunks):
+            assert np.array_equal(c.get_host(i), ch)
+        for d in dsts:
+            cs = d.compact_slots(W.slots_from_blocks(g, d.blocks, n * g.CT)).reshape(n, g.CT)
+            for ch, s in zip(chunks, cs):
+                oracle.scatter_chunk(d.gc, ch, s, d.host)
+            assert_layers_equal(d.device_blocks_to_host(), d.host)
+            assert d.untracked_blocks_untouched()
