@@ -20,6 +20,8 @@ Also reported in the same JSON line:
                kernel of the same size as the achievable ceiling
   link         hipMemcpyAsync peak between the pinned pool and the GPU per direction,
                and store / retrieve payload rate as a fraction of it
+  duplex       a store and a retrieve of different requests running at the same time,
+               against the link's measured two-way peak
   layerwise    the same request moved layer by layer (rectangle copies + kernels over
                one or four layers), as a fraction of the link peak, and how soon layer 0
                is usable compared with the bulk retrieve
@@ -98,8 +100,8 @@ def main():
     ap.add_argument("--staging-chunks", type=int, default=16)
     ap.add_argument("--num-staging", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--legs", default="pipeline,link,device,layerwise,cpu",
-                    help="comma list of pipeline (always run), link, device, layerwise, cpu: the "
+    ap.add_argument("--legs", default="pipeline,link,device,duplex,layerwise,cpu",
+                    help="comma list of pipeline (always run), link, device, duplex, layerwise, cpu: the "
                          "extra measurements to make; profiling runs use a subset")
     ap.add_argument("--tune", action="append", default=[], help="key=value for lmc_tune")
     args = ap.parse_args()
@@ -140,7 +142,7 @@ def main():
     d_load = torch.from_numpy(seq["load_slots"]).to(dev)
     stream = torch.cuda.current_stream()
 
-    ctx = lmc.Context(g, max(n_chunks * g.chunk_bytes, 1 << 30), num_staging=args.num_staging,
+    ctx = lmc.Context(g, max(2 * n_chunks * g.chunk_bytes, 1 << 30), num_staging=args.num_staging,
                       staging_chunks=args.staging_chunks, device=0, flags=lmc.LMC_FLAG_TIMING)
     for kv in args.tune:
         k, v = kv.split("=")
@@ -265,6 +267,32 @@ def main():
             "scatter_frac_of_hbm_peak": round(2 * payload_one_way / tsc / 1e9 / HBM_PEAK_GBPS, 4),
         }
         del stagings
+    # full duplex: store one request while another is retrieved (two streams per
+    # direction, nothing shared but the link and HBM)
+    duplex = None
+    if "duplex" in legs:
+        ctx.tune("timing", 0)
+        ids_a = ctx.hash_chunks(seq["tokens"])
+        seq_b = W.sequence(WORKLOAD, g, stream=1)
+        ids_b = ctx.hash_chunks(seq_b["tokens"])
+        d_load_b = torch.from_numpy(seq["load_slots"]).to(dev)
+        ctx.clear(ids_a)
+        ctx.wait(ctx.store(src, d_store, ids_b, stream))       # request B's chunks are in the pool
+
+        def both():
+            ctx.clear(ids_a)
+            t1 = ctx.store(src, d_store, ids_a, stream)
+            t2 = ctx.retrieve(ids_b, d_load_b, dst, stream)
+            ctx.wait(t1)
+            ctx.wait(t2)
+        t_both = timed(both)
+        peak = ctx.measure_link_duplex(512 << 20, reps=3)
+        duplex = {"store_plus_retrieve_gbps": round(2 * payload_one_way / t_both / 1e9, 2),
+                  "link_duplex_peak_gbps": round(peak, 2),
+                  "frac_of_duplex_peak": round(2 * payload_one_way / t_both / 1e9 / peak, 4)}
+        ctx.clear(ids_a)
+        ctx.clear(ids_b)
+
     # layer-wise mode: the same request moved layer by layer, alone and with a consumer /
     # producer that works on each layer as soon as it is there
     layerwise = None
@@ -331,6 +359,8 @@ def main():
         out["device"] = device
     if link:
         out["link"] = link
+    if duplex:
+        out["duplex"] = duplex
     if layerwise:
         out["layerwise"] = layerwise
     if "cpu" in legs:

@@ -291,6 +291,11 @@ lmc_status_t lmc_measure_link(lmc_ctx_t *ctx, uint64_t nbytes, int32_t reps,
                               double *h2d_gbps_out, double *d2h_gbps_out);
 lmc_status_t lmc_copy(lmc_ctx_t *ctx, void *dst_dev, const void *src_dev, uint64_t nbytes,
                       void *stream);
+/* Both directions at once (section 5.1 "Parallel Store/load Operations": the host link is
+ * full duplex): nbytes up and nbytes down at the same time, sum of both directions in
+ * GB/s, best of reps.  Needs 2*nbytes of pool; pool content is preserved.  Blocks. */
+lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *ctx, uint64_t nbytes, int32_t reps,
+                                     double *sum_gbps_out);
 
 /* Run-time knobs for experiments; the defaults are the measured best.  Keys: "nt_load",
  * "nt_store" (0/1: non-temporal hints on the kernels' streaming accesses), "xcd_run"

@@ -1087,6 +1087,55 @@ lmc_status_t lmc_measure_link(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, doubl
     return rc;
 }
 
+lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, double *gbps_out) {
+    if (!c || !gbps_out || reps < 1 || nbytes == 0) return LMC_ERR_INVAL;
+    if (!c->has_device) return LMC_ERR_NODEVICE;
+    if (2 * nbytes > uint64_t(c->n_pool_slots) * uint64_t(c->chunk_bytes)) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    HIPCHK(c, hipDeviceSynchronize());
+    reap(c);
+    uint8_t *up = nullptr, *down = nullptr;
+    if (hipMalloc(reinterpret_cast<void **>(&up), nbytes) != hipSuccess) return LMC_ERR_NOMEM;
+    if (hipMalloc(reinterpret_cast<void **>(&down), nbytes) != hipSuccess) {
+        (void)hipFree(up);
+        return LMC_ERR_NOMEM;
+    }
+    hipEvent_t e0 = nullptr, e1 = nullptr, e2 = nullptr;
+    lmc_status_t rc = get_event(c, true, &e0);
+    if (rc == LMC_OK) rc = get_event(c, true, &e1);
+    if (rc == LMC_OK) rc = get_event(c, true, &e2);
+    double best = 0.0;
+    auto ok = [&](hipError_t e) {
+        if (e != hipSuccess && rc == LMC_OK) {
+            c->last_hip_error = int32_t(e);
+            rc = LMC_ERR_HIP;
+        }
+    };
+    // the second half of the region is uploaded first and downloaded unchanged in every
+    // pass, so the pool ends as it started
+    if (rc == LMC_OK) ok(hipMemcpy(down, c->pool + nbytes, nbytes, hipMemcpyHostToDevice));
+    for (int r = 0; r < reps + 1 && rc == LMC_OK; r++) {
+        ok(hipEventRecord(e0, c->s_h2d));
+        ok(hipStreamWaitEvent(c->s_d2h, e0, 0));           // both directions start together
+        ok(hipMemcpyAsync(up, c->pool, nbytes, hipMemcpyHostToDevice, c->s_h2d));
+        ok(hipMemcpyAsync(c->pool + nbytes, down, nbytes, hipMemcpyDeviceToHost, c->s_d2h));
+        ok(hipEventRecord(e1, c->s_d2h));
+        ok(hipStreamWaitEvent(c->s_h2d, e1, 0));
+        ok(hipEventRecord(e2, c->s_h2d));                  // after both
+        ok(hipEventSynchronize(e2));
+        float ms = 0.f;
+        ok(hipEventElapsedTime(&ms, e0, e2));
+        if (rc == LMC_OK && r > 0 && ms > 0.f) best = std::max(best, 2.0 * double(nbytes) / (double(ms) * 1e6));
+    }
+    for (hipEvent_t e : {e0, e1, e2})
+        if (e) c->free_time_events.push_back(e);
+    (void)hipFree(up);
+    (void)hipFree(down);
+    *gbps_out = best;
+    return rc;
+}
+
 lmc_status_t lmc_copy(lmc_ctx_t *c, void *dst, const void *src, uint64_t nbytes, void *stream) {
     if (!c || !dst || !src || (nbytes % 16) != 0 || (reinterpret_cast<uintptr_t>(dst) % 16) != 0 ||
         (reinterpret_cast<uintptr_t>(src) % 16) != 0)

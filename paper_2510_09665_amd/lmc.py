@@ -27,7 +27,8 @@ EXPORTS = [
     "lmc_lookup", "lmc_store", "lmc_retrieve", "lmc_retrieve_batch", "lmc_retrieve_layerwise",
     "lmc_store_begin", "lmc_store_layers", "lmc_wait_layer", "lmc_wait", "lmc_gather",
     "lmc_scatter", "lmc_put_host", "lmc_get_host", "lmc_find_slot", "lmc_pin", "lmc_unpin",
-    "lmc_clear", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_copy", "lmc_tune",
+    "lmc_clear", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_measure_link_duplex",
+    "lmc_copy", "lmc_tune",
     "lmc_strerror", "lmc_last_hip_error",
 ]
 
@@ -111,6 +112,7 @@ def _lib():
             "lmc_reset_stats": (st, [vp]),
             "lmc_measure_link": (st, [vp, u64, i32, ctypes.POINTER(ctypes.c_double),
                                       ctypes.POINTER(ctypes.c_double)]),
+            "lmc_measure_link_duplex": (st, [vp, u64, i32, ctypes.POINTER(ctypes.c_double)]),
             "lmc_copy": (st, [vp, vp, vp, u64, vp]),
             "lmc_tune": (st, [vp, ctypes.c_char_p, i64]),
             "lmc_strerror": (ctypes.c_char_p, [st]),
@@ -327,6 +329,13 @@ class Context:
         self._check(_lib().lmc_measure_link(self._h, nbytes, reps, ctypes.byref(a), ctypes.byref(b)),
                     "lmc_measure_link")
         return a.value, b.value
+
+    def measure_link_duplex(self, nbytes, reps=3):
+        """sum of both directions, GB/s, with an upload and a download running together"""
+        a = ctypes.c_double()
+        self._check(_lib().lmc_measure_link_duplex(self._h, nbytes, reps, ctypes.byref(a)),
+                    "lmc_measure_link_duplex")
+        return a.value
 
     def copy(self, dst_dev, src_dev, nbytes, stream=None):
         self._check(_lib().lmc_copy(self._h, _dev(dst_dev), _dev(src_dev), nbytes, _stream(stream)),

@@ -320,3 +320,56 @@ def test_partial_skip_store_launches_per_run_of_new_chunks():
         for k in range(8):
             src_slots = other[k] if k in (0, 1, 4) else slots[k]
             assert np.array_equal(c.get_host(ids[k]), oracle.gather_chunk(g, kv.host, src_slots)), k
+
+
+def test_store_and_retrieve_run_concurrently_from_two_threads():
+    """Full duplex (paper section 5.1, "Parallel Store/load Operations"): one thread stores
+    request A while another retrieves request B; afterwards both are exact."""
+    import threading
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    lmc = _lmc()
+    g = W.geometry("llama3_8b", L=8, NB=2048)
+    rng = np.random.default_rng(41)
+    n = 12
+    bpc = g.CT // g.BS
+    blocks = rng.permutation(g.NB)
+    src_a = PagedKV(g, blocks[:n * bpc], rng)
+    src_b = PagedKV(g, blocks[n * bpc:2 * n * bpc], rng)
+    dst_b = PagedKV(g, blocks[2 * n * bpc:3 * n * bpc], fill="sentinel")
+    sa = W.slots_from_blocks(g, src_a.blocks, n * g.CT)
+    sb = W.slots_from_blocks(g, src_b.blocks, n * g.CT)
+    tb = W.slots_from_blocks(g, dst_b.blocks, n * g.CT)
+    ids_a = np.arange(1, n + 1, dtype=np.uint64)
+    ids_b = np.arange(101, n + 101, dtype=np.uint64)
+    with lmc.Context(g, 2 * n * g.chunk_bytes, staging_chunks=2, flags=lmc.LMC_FLAG_POISON_STAGING) as c:
+        d_sa, d_sb, d_tb = slots_to_device(sa), slots_to_device(sb), slots_to_device(tb)
+        torch.cuda.synchronize()
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        c.wait(c.store(src_b.dev, d_sb, ids_b, s1))
+        errors = []
+
+        def run(fn):
+            try:
+                for _ in range(3):
+                    fn()
+            except Exception as e:  # noqa: BLE001
+                errors.append(e)
+
+        def do_store():
+            c.clear(ids_a)
+            c.wait(c.store(src_a.dev, d_sa, ids_a, s1))
+
+        def do_load():
+            c.wait(c.retrieve(ids_b, d_tb, dst_b.dev, s2))
+
+        th = [threading.Thread(target=run, args=(f,)) for f in (do_store, do_load)]
+        [t.start() for t in th]
+        [t.join() for t in th]
+        assert not errors, errors
+        torch.cuda.synchronize()
+        for i, s in zip(ids_a.tolist(), src_a.compact_slots(sa).reshape(n, g.CT)):
+            assert np.array_equal(c.get_host(i), oracle.gather_chunk(src_a.gc, src_a.host, s))
+        for s, t in zip(src_b.compact_slots(sb).reshape(n, g.CT), dst_b.compact_slots(tb).reshape(n, g.CT)):
+            oracle.scatter_chunk(dst_b.gc, oracle.gather_chunk(src_b.gc, src_b.host, s), t, dst_b.host)
+        assert_layers_equal(dst_b.device_blocks_to_host(), dst_b.host)
