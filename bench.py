@@ -22,6 +22,7 @@ Also reported in the same JSON line:
                and store / retrieve payload rate as a fraction of it
   duplex       a store and a retrieve of different requests running at the same time,
                against the link's measured two-way peak
+  direct       the variant without staging: the kernels read / write the pinned pool
   layerwise    the same request moved layer by layer (rectangle copies + kernels over
                one or four layers), as a fraction of the link peak, and how soon layer 0
                is usable compared with the bulk retrieve
@@ -100,8 +101,8 @@ def main():
     ap.add_argument("--staging-chunks", type=int, default=16)
     ap.add_argument("--num-staging", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--legs", default="pipeline,link,device,duplex,layerwise,cpu",
-                    help="comma list of pipeline (always run), link, device, duplex, layerwise, cpu: the "
+    ap.add_argument("--legs", default="pipeline,link,device,duplex,direct,layerwise,cpu",
+                    help="comma list of pipeline (always run), link, device, duplex, direct, layerwise, cpu: the "
                          "extra measurements to make; profiling runs use a subset")
     ap.add_argument("--tune", action="append", default=[], help="key=value for lmc_tune")
     args = ap.parse_args()
@@ -293,6 +294,24 @@ def main():
         ctx.clear(ids_a)
         ctx.clear(ids_b)
 
+    # direct mode: no staging, the kernels move the bytes over the link themselves
+    direct = None
+    if "direct" in legs:
+        dctx = lmc.Context(g, max(n_chunks * g.chunk_bytes, 1 << 30), device=0, flags=lmc.LMC_FLAG_DIRECT)
+        dids = dctx.hash_chunks(seq["tokens"])
+
+        def d_store_only():
+            dctx.clear(dids)
+            dctx.wait(dctx.store(src, d_store, dids, stream))
+        td_s = timed(d_store_only)
+        td_l = timed(lambda: dctx.wait(dctx.retrieve(dids, d_load, dst, stream)))
+        h2d, d2h = dctx.measure_link(512 << 20, reps=3)
+        direct = {"store_gbps": round(payload_one_way / td_s / 1e9, 2),
+                  "retrieve_gbps": round(payload_one_way / td_l / 1e9, 2),
+                  "store_frac_of_d2h_peak": round(payload_one_way / td_s / 1e9 / d2h, 4),
+                  "retrieve_frac_of_h2d_peak": round(payload_one_way / td_l / 1e9 / h2d, 4)}
+        dctx.destroy()
+
     # layer-wise mode: the same request moved layer by layer, alone and with a consumer /
     # producer that works on each layer as soon as it is there
     layerwise = None
@@ -361,6 +380,8 @@ def main():
         out["link"] = link
     if duplex:
         out["duplex"] = duplex
+    if direct:
+        out["direct"] = direct
     if layerwise:
         out["layerwise"] = layerwise
     if "cpu" in legs:

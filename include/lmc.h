@@ -78,6 +78,10 @@ enum {
 #define LMC_FLAG_POISON_STAGING 4u /* overwrite a staging buffer with 0xA5 as soon as the
                                       pipeline releases it: a reuse that came too early
                                       then shows as corrupt data.  For tests. */
+#define LMC_FLAG_DIRECT 16u        /* no staging buffer and no copy engine: the gather kernel
+                                      writes, and the scatter kernel reads, the pinned pool
+                                      over the host link.  Same results; the kernels then
+                                      occupy compute units for the length of the transfer. */
 #define LMC_FLAG_TIMING 8u         /* give every gather / scatter launch a start and a stop
                                       HIP event (kernel begin / end on its own stream);
                                       durations appear in lmc_stats_t. */

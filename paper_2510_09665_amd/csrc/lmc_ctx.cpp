@@ -70,6 +70,7 @@ struct lmc_ctx {
     int64_t chunk_bytes = 0;
     int64_t n_pool_slots = 0;
     uint8_t *pool = nullptr;
+    uint8_t *pool_dev = nullptr;   // the pool's address as the GPU sees it (LMC_FLAG_DIRECT)
     bool has_device = false;
     lmc::ChunkIndex index;
     std::mutex mu;
@@ -273,7 +274,7 @@ lmc_status_t timed_launch(lmc_ctx *c, bool gather, const lmc::LaunchView &view,
         if (rc != LMC_OK) return rc;
     }
     const lmc::LaunchShape &s = c->shape;
-    const uint64_t moved = uint64_t(n_chunks) * view.chunk_stride;
+    const uint64_t moved = uint64_t(n_chunks) * view.by_n_lp.d * c->kg.plane_bytes;
     if (gather) {
         HIPCHK(c, lmc::launch_gather(c->kg, view, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1));
         c->stats.gather_launches++;
@@ -398,7 +399,7 @@ int64_t layer_group_chunks(const lmc_ctx *c, const Ring &r, const lmc::LaunchVie
 // the H2D stream waits for the newest such store (stores complete in order on one
 // stream).  A layer-wise store that has not been submitted completely cannot be waited
 // for on the device: LMC_ERR_BUSY.
-lmc_status_t after_stores(lmc_ctx *c, const std::vector<int64_t> &pool_slots) {
+lmc_status_t after_stores(lmc_ctx *c, const std::vector<int64_t> &pool_slots, hipStream_t waiter) {
     uint64_t newest = 0;
     for (int64_t s : pool_slots) {
         const uint64_t t = c->index.meta(s).ready_ticket;
@@ -410,7 +411,7 @@ lmc_status_t after_stores(lmc_ctx *c, const std::vector<int64_t> &pool_slots) {
     }
     if (newest != 0) {
         const Op *o = find_op(c, newest);
-        if (o != nullptr && o->done != nullptr) HIPCHK(c, hipStreamWaitEvent(c->s_h2d, o->done, 0));
+        if (o != nullptr && o->done != nullptr) HIPCHK(c, hipStreamWaitEvent(waiter, o->done, 0));
     }
     return LMC_OK;
 }
@@ -442,7 +443,8 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
     rc = validate_slots(c, slot_mapping, n_chunks * CT, c->s_scatter);
     if (rc != LMC_OK) return rc;
 
-    if ((rc = after_stores(c, pool_slots)) != LMC_OK) return rc;
+    const bool direct = (c->cfg.flags & LMC_FLAG_DIRECT) != 0;
+    if ((rc = after_stores(c, pool_slots, direct ? c->s_scatter : c->s_h2d)) != LMC_OK) return rc;
     Op op;
     op.ticket = c->next_ticket++;
     op.layerwise = layers_per_step > 0;
@@ -451,6 +453,23 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
     Ring &ring = c->load_ring;
     const uint64_t cb = uint64_t(c->chunk_bytes);
     const int64_t per = c->cfg.staging_chunks;
+    // LMC_FLAG_DIRECT: no staging, no copy: the scatter kernel reads the pinned pool over
+    // the link; one launch per run of consecutive pool slots (and per layer step)
+    auto load_direct = [&](lmc::LaunchView view, uint64_t pool_off) -> lmc_status_t {
+        view.chunk_stride = cb;  // chunks lie one pool slot apart
+        const int64_t max_k = int64_t(lmc::max_chunks_per_launch(c->kg, view));
+        for (int64_t i0 = 0; i0 < n_chunks;) {
+            int64_t k = 1;
+            while (k < max_k && i0 + k < n_chunks && pool_slots[size_t(i0 + k)] == pool_slots[size_t(i0)] + k) k++;
+            lmc_status_t r = timed_launch(c, false, view, ptrs, slot_mapping + i0 * CT, uint32_t(k),
+                                          c->pool_dev + uint64_t(pool_slots[size_t(i0)]) * cb + pool_off, c->s_scatter);
+            if (r != LMC_OK) return r;
+            c->stats.bytes_h2d += uint64_t(k) * view.by_n_lp.d * c->kg.plane_bytes;
+            if ((r = force_sync(c, c->s_scatter)) != LMC_OK) return r;
+            i0 += k;
+        }
+        return LMC_OK;
+    };
     // one group: copies into the next ring buffer on the H2D stream, scatter on the
     // scatter stream; the buffer is released when the scatter has read it
     auto load_group = [&](const lmc::LaunchView &view, uint64_t pool_off, int64_t i0, int64_t k) -> lmc_status_t {
@@ -472,7 +491,9 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
         return force_sync(c, c->s_scatter);
     };
 
-    if (!op.layerwise) {
+    if (direct && !op.layerwise) {
+        if ((rc = load_direct(lmc::bulk_view(c->kg), 0)) != LMC_OK) return rc;
+    } else if (!op.layerwise) {
         const lmc::LaunchView view = lmc::bulk_view(c->kg);
         if ((rc = ring_reslot(c, ring, ring.buf_bytes, c->s_h2d, c->s_scatter)) != LMC_OK) return rc;
         // The link is the bottleneck and every scatter but the last hides behind the next
@@ -492,13 +513,17 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
         for (int32_t l0 = 0; l0 < L; l0 += layers_per_step) {
             const int32_t kk = std::min(layers_per_step, L - l0);
             const lmc::LaunchView view = lmc::layer_view(c->kg, uint32_t(P), uint32_t(l0), uint32_t(kk));
-            const int64_t cap = layer_group_chunks(c, ring, view, n_chunks);
-            if ((rc = ring_reslot(c, ring, (uint64_t(cap) * view.chunk_stride + 255) / 256 * 256, c->s_h2d,
-                                  c->s_scatter)) != LMC_OK)
-                return rc;
-            for (int64_t i0 = 0; i0 < n_chunks; i0 += cap)
-                if ((rc = load_group(view, uint64_t(l0) * layer_bytes, i0, std::min(cap, n_chunks - i0))) != LMC_OK)
+            if (direct) {
+                if ((rc = load_direct(view, uint64_t(l0) * layer_bytes)) != LMC_OK) return rc;
+            } else {
+                const int64_t cap = layer_group_chunks(c, ring, view, n_chunks);
+                if ((rc = ring_reslot(c, ring, (uint64_t(cap) * view.chunk_stride + 255) / 256 * 256, c->s_h2d,
+                                      c->s_scatter)) != LMC_OK)
                     return rc;
+                for (int64_t i0 = 0; i0 < n_chunks; i0 += cap)
+                    if ((rc = load_group(view, uint64_t(l0) * layer_bytes, i0, std::min(cap, n_chunks - i0))) != LMC_OK)
+                        return rc;
+            }
             hipEvent_t e;
             if ((rc = get_event(c, false, &e)) != LMC_OK) return rc;
             HIPCHK(c, hipEventRecord(e, c->s_scatter));
@@ -587,6 +612,8 @@ lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out) {
             c->last_hip_error = int32_t(e);
             return fail(LMC_ERR_NOMEM);
         }
+        if (hipHostGetDevicePointer(reinterpret_cast<void **>(&c->pool_dev), c->pool, 0) != hipSuccess)
+            return fail(LMC_ERR_HIP);
         e = hipHostMalloc(reinterpret_cast<void **>(&c->bad_flag_host), 64, hipHostMallocMapped);
         if (e != hipSuccess) {
             c->bad_flag_host = nullptr;
@@ -671,6 +698,27 @@ static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64
                                  bool edge_group) {
     Ring &ring = c->store_ring;
     const int64_t CT = c->cfg.geom.chunk_tokens;
+    if (c->cfg.flags & LMC_FLAG_DIRECT) {
+        // no staging, no copy: the gather kernel writes the pinned pool over the link; one
+        // launch per run of chunks that are consecutive both in the slot mapping and in the pool
+        lmc::LaunchView v = view;
+        v.chunk_stride = uint64_t(c->chunk_bytes);
+        const size_t max_k = size_t(lmc::max_chunks_per_launch(c->kg, v));
+        for (size_t j0 = 0; j0 < new_chunk.size();) {
+            size_t k = 1;
+            while (k < max_k && j0 + k < new_chunk.size() && new_chunk[j0 + k] == new_chunk[j0] + int64_t(k) &&
+                   new_slot[j0 + k] == new_slot[j0] + int64_t(k))
+                k++;
+            lmc_status_t rc = timed_launch(c, true, v, ptrs, slot_mapping + new_chunk[j0] * CT, uint32_t(k),
+                                           c->pool_dev + uint64_t(new_slot[j0]) * v.chunk_stride + pool_off,
+                                           c->s_gather);
+            if (rc != LMC_OK) return rc;
+            c->stats.bytes_d2h += uint64_t(k) * v.by_n_lp.d * c->kg.plane_bytes;
+            if ((rc = force_sync(c, c->s_gather)) != LMC_OK) return rc;
+            j0 += k;
+        }
+        return LMC_OK;
+    }
     const size_t per = size_t(cap_chunks);
     for (size_t j0 = 0; j0 < new_chunk.size();) {
         // one launch covers chunks that are consecutive in the caller's slot mapping.
@@ -729,7 +777,8 @@ lmc_status_t lmc_store(lmc_ctx_t *c, void *const *kv_layers, const int64_t *slot
     rc = store_groups(c, lmc::bulk_view(c->kg), 0, ptrs, slot_mapping, new_chunk, op.slots,
                       c->cfg.staging_chunks, true);
     if (rc != LMC_OK) return rc;
-    rc = finish_op(c, std::move(op), c->s_d2h, !new_chunk.empty(), ticket_out);
+    rc = finish_op(c, std::move(op), (c->cfg.flags & LMC_FLAG_DIRECT) ? c->s_gather : c->s_d2h,
+                   !new_chunk.empty(), ticket_out);
     if (rc != LMC_OK) return rc;
     return fits ? LMC_OK : LMC_ERR_NOMEM;
 }
@@ -786,7 +835,7 @@ lmc_status_t lmc_store_layers(lmc_ctx_t *c, uint64_t ticket, int32_t first_layer
                                                  uint32_t(n_layers));
     const uint64_t layer_bytes = uint64_t(geom.num_planes) * c->kg.plane_bytes;
     const int64_t cap = layer_group_chunks(c, c->store_ring, view, int64_t(op->new_chunk.size()));
-    if ((rc = ring_reslot(c, c->store_ring, (uint64_t(cap) * view.chunk_stride + 255) / 256 * 256, c->s_gather,
+    if (!(c->cfg.flags & LMC_FLAG_DIRECT) && (rc = ring_reslot(c, c->store_ring, (uint64_t(cap) * view.chunk_stride + 255) / 256 * 256, c->s_gather,
                           c->s_d2h)) != LMC_OK)
         return rc;
     rc = store_groups(c, view, uint64_t(first_layer) * layer_bytes, ptrs, op->slot_mapping, op->new_chunk,
@@ -794,13 +843,14 @@ lmc_status_t lmc_store_layers(lmc_ctx_t *c, uint64_t ticket, int32_t first_layer
     if (rc != LMC_OK) return rc;
     hipEvent_t e;
     if ((rc = get_event(c, false, &e)) != LMC_OK) return rc;
-    HIPCHK(c, hipEventRecord(e, c->s_d2h));
+    hipStream_t last = (c->cfg.flags & LMC_FLAG_DIRECT) ? c->s_gather : c->s_d2h;
+    HIPCHK(c, hipEventRecord(e, last));
     op->owned_events.push_back(e);
     for (int32_t l = first_layer; l < first_layer + n_layers; l++) op->layer_done[size_t(l)] = e;
     op->next_layer = first_layer + n_layers;
     if (op->next_layer == geom.num_layers) {
         if ((rc = get_event(c, false, &op->done)) != LMC_OK) return rc;
-        HIPCHK(c, hipEventRecord(op->done, c->s_d2h));
+        HIPCHK(c, hipEventRecord(op->done, last));
         op->pending = false;
     }
     return LMC_OK;

@@ -19,6 +19,7 @@ LMC_ERR_HIP, LMC_ERR_BUSY, LMC_ERR_NODEVICE = -5, -6, -7
 LMC_MAX_LAYERS = 160
 LMC_DEVICE_NONE = -1
 LMC_FLAG_VALIDATE_SLOTS, LMC_FLAG_FORCE_SYNC, LMC_FLAG_POISON_STAGING, LMC_FLAG_TIMING = 1, 2, 4, 8
+LMC_FLAG_DIRECT = 16
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblmc.so")
 

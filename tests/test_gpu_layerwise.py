@@ -19,6 +19,8 @@ CASES = {
     "mla_fp8_k3": ("mla_fp8", {}, 8192, 1, 3, 0),
     "hnd_k2": ("llama3_8b", dict(L=6, NB=512, layout="HND"), 8 * 256, 2, 2, 0),
     "all_layers_in_one_step": ("tiny", {}, 256, 1, 99, 0),
+    "direct_llama_k1": ("llama3_8b", dict(L=8, NB=1024), 10 * 256, 1, 1, "direct"),
+    "direct_mla_k3": ("mla_bf16", dict(L=7), 4 * 256, 1, 3, "direct"),
 }
 
 
@@ -31,7 +33,7 @@ def _setup(case):
     rng = W.rng_for(name, stream=3)
     src = PagedKV(g, seq["store_blocks"], rng)
     dst = PagedKV(g, seq["load_blocks"], fill="sentinel")
-    f = lmc.LMC_FLAG_POISON_STAGING if flags == "poison" else 0
+    f = {"poison": lmc.LMC_FLAG_POISON_STAGING, "direct": lmc.LMC_FLAG_DIRECT}.get(flags, 0)
     n_chunks = n_tok // g.CT
     ctx = lmc.Context(g, n_chunks * g.chunk_bytes, staging_chunks=staging, flags=f | lmc.LMC_FLAG_TIMING)
     return lmc, g, seq, src, dst, ctx, k, n_chunks
@@ -68,7 +70,7 @@ def test_layerwise_retrieve_matches_oracle(case):
         assert st["scatter_launches"] >= steps
 
 
-@pytest.mark.parametrize("case", ["llama8b_full_k1", "mla_fp8_k3"])
+@pytest.mark.parametrize("case", ["llama8b_full_k1", "mla_fp8_k3", "direct_llama_k1"])
 def test_each_layer_is_complete_when_its_wait_returns(case):
     """A consumer stream waits for layer l, then reads layer l's pages at once (while the
     later layers are still loading).  What it read must already be the final content."""
@@ -112,7 +114,8 @@ def _status(fn):
         return e.status
 
 
-@pytest.mark.parametrize("case", ["tiny_k1", "llama8b_k5_ragged", "many_groups_per_layer", "mla_fp8_k3", "hnd_k2"])
+@pytest.mark.parametrize("case", ["tiny_k1", "llama8b_k5_ragged", "many_groups_per_layer", "mla_fp8_k3", "hnd_k2",
+                                  "direct_llama_k1", "direct_mla_k3"])
 def test_layerwise_store_matches_oracle(case):
     """The 'engine' writes layer l's KV on its stream and submits the layer at once; the
     pool must end up holding exactly the oracle's chunks."""

@@ -92,15 +92,22 @@ def test_config5_mla_fp8_full():
     _run_sequence("mla_fp8", staging_chunks=3)      # 32 chunks in groups of 3: ragged last group
 
 
-@pytest.mark.parametrize("flags", ["poison", "force_sync", "validate"])
+@pytest.mark.parametrize("flags", ["poison", "force_sync", "validate", "direct"])
 def test_pipeline_modes_give_identical_results(flags):
     lmc = _lmc()
     f = {"poison": lmc.LMC_FLAG_POISON_STAGING, "force_sync": lmc.LMC_FLAG_FORCE_SYNC,
-         "validate": lmc.LMC_FLAG_VALIDATE_SLOTS}[flags]
+         "validate": lmc.LMC_FLAG_VALIDATE_SLOTS, "direct": lmc.LMC_FLAG_DIRECT}[flags]
     # 24 chunks through a ring of 2 single-chunk buffers: every buffer is reused 12 times
     g = W.geometry("llama3_8b", L=4, NB=1024)
     _run_sequence("llama3_8b", g, flags=f, n_tokens=24 * 256)
     _run_sequence("llama3_8b", g, flags=f, n_tokens=24 * 256, num_staging=3, staging_chunks=5)
+
+
+def test_direct_mode_full_size_config2_and_mla():
+    """LMC_FLAG_DIRECT: the kernels read and write the pinned pool themselves."""
+    lmc = _lmc()
+    _run_sequence("llama3_8b", flags=lmc.LMC_FLAG_DIRECT, staging_chunks=1)
+    _run_sequence("mla_fp8", flags=lmc.LMC_FLAG_DIRECT, staging_chunks=1)
 
 
 def test_hnd_layout_through_the_pipeline():
