@@ -147,6 +147,7 @@ lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out);
 lmc_status_t lmc_destroy(lmc_ctx_t *ctx);
 
 int64_t lmc_chunk_bytes(const lmc_ctx_t *ctx); /* chunk_tokens*layers*planes*heads*dim*elem */
+int32_t lmc_chunk_tokens(const lmc_ctx_t *ctx);
 int64_t lmc_pool_slots(const lmc_ctx_t *ctx);
 
 /* Token processor (section 4): chained 64-bit ids of the full chunks of a token
@@ -156,6 +157,9 @@ int64_t lmc_pool_slots(const lmc_ctx_t *ctx);
  * n_chunks_out: HOST, receives that count. */
 lmc_status_t lmc_hash_chunks(const lmc_ctx_t *ctx, const int32_t *tokens, int64_t n_tokens,
                              uint64_t *ids_out, int64_t *n_chunks_out);
+/* The same chain continued: prev_id is the id of the chunk just before tokens[0]. */
+lmc_status_t lmc_hash_chunks_from(const lmc_ctx_t *ctx, uint64_t prev_id, const int32_t *tokens,
+                                  int64_t n_tokens, uint64_t *ids_out, int64_t *n_chunks_out);
 
 /* Prefix match (section 4 "Retrieve"): n_hit_out receives the number of leading ids
  * that are all present.  A later isolated hit does not count.  HOST pointers. */
@@ -268,6 +272,34 @@ lmc_status_t lmc_put_host(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n,
                           const void *host_src);
 lmc_status_t lmc_get_host(lmc_ctx_t *ctx, uint64_t chunk_id, void *host_dst);
 lmc_status_t lmc_find_slot(lmc_ctx_t *ctx, uint64_t chunk_id, int64_t *slot_out);
+
+/* Delayed decode storing (section 5.1 "Delayed Decode KV Cache Storing"): tokens
+ * generated during decoding are not offloaded one at a time; they are held back until a
+ * whole chunk exists, which is then stored in one batched operation.  An lmc_seq_t is
+ * that accumulator for one sequence; it is a policy layer over lmc_store and is not
+ * thread-safe by itself (one sequence, one caller).
+ * lmc_seq_open: prompt_tokens / prompt_slots (HOST, n_prompt entries) describe what the
+ *   sequence holds already.  The prompt's full chunks only advance the id chain (storing
+ *   them is the prefill's lmc_store); its tail shorter than a chunk starts the pending
+ *   chunk.  Allocates a few chunk_tokens-sized slot buffers (pinned and device).
+ * lmc_seq_append: n more tokens with their slots (HOST).  Every chunk that becomes
+ *   complete gets its chained id, its slot mapping is uploaded on `stream`, and it is
+ *   handed to lmc_store (ordered after `stream`; a chunk already present is skipped).
+ *   n_chunks_offered_out (may be NULL): chunks completed by this call;
+ *   last_ticket_out (may be NULL): ticket of the last store, 0 if none.  kv_layers as in
+ *   lmc_store.  LMC_ERR_NOMEM: the pool was full for at least one chunk; the chain moves
+ *   on regardless.  The caller's slots arrays are copied and need not stay alive.
+ * lmc_seq_pending_tokens: tokens held back so far (always < chunk_tokens).
+ * lmc_seq_close: waits for the sequence's stores and frees it; pending tokens are
+ *   dropped (only full chunks are ever stored). */
+typedef struct lmc_seq lmc_seq_t;
+lmc_status_t lmc_seq_open(lmc_ctx_t *ctx, const int32_t *prompt_tokens, const int64_t *prompt_slots,
+                          int64_t n_prompt, lmc_seq_t **seq_out);
+lmc_status_t lmc_seq_append(lmc_seq_t *seq, const int32_t *tokens, const int64_t *slots, int64_t n,
+                            void *const *kv_layers, void *stream, int64_t *n_chunks_offered_out,
+                            uint64_t *last_ticket_out);
+lmc_status_t lmc_seq_pending_tokens(const lmc_seq_t *seq, int64_t *n_out);
+lmc_status_t lmc_seq_close(lmc_seq_t *seq);
 
 /* Local forms of the controller verbs of section 7, Table 3.  HOST pointers.
  * pin: every id must be present (else LMC_ERR_MISS, nothing pinned); adds one pin each.

@@ -640,21 +640,28 @@ lmc_status_t lmc_destroy(lmc_ctx_t *c) {
 }
 
 int64_t lmc_chunk_bytes(const lmc_ctx_t *c) { return c ? c->chunk_bytes : 0; }
+int32_t lmc_chunk_tokens(const lmc_ctx_t *c) { return c ? c->cfg.geom.chunk_tokens : 0; }
 int64_t lmc_pool_slots(const lmc_ctx_t *c) { return c ? c->n_pool_slots : 0; }
 
-lmc_status_t lmc_hash_chunks(const lmc_ctx_t *c, const int32_t *tokens, int64_t n_tokens,
-                             uint64_t *ids_out, int64_t *n_chunks_out) {
+lmc_status_t lmc_hash_chunks_from(const lmc_ctx_t *c, uint64_t prev_id, const int32_t *tokens,
+                                  int64_t n_tokens, uint64_t *ids_out, int64_t *n_chunks_out) {
     if (!c || n_tokens < 0 || (n_tokens > 0 && !tokens) || !n_chunks_out) return LMC_ERR_INVAL;
     const int32_t CT = c->cfg.geom.chunk_tokens;
     const int64_t n = n_tokens / CT;
     if (n > 0 && !ids_out) return LMC_ERR_INVAL;
-    uint64_t prev = c->cfg.hash_seed;
+    uint64_t prev = prev_id;
     for (int64_t i = 0; i < n; i++) {
         prev = lmc::chunk_id(prev, tokens + i * CT, CT);
         ids_out[i] = prev;
     }
     *n_chunks_out = n;
     return LMC_OK;
+}
+
+lmc_status_t lmc_hash_chunks(const lmc_ctx_t *c, const int32_t *tokens, int64_t n_tokens,
+                             uint64_t *ids_out, int64_t *n_chunks_out) {
+    if (!c) return LMC_ERR_INVAL;
+    return lmc_hash_chunks_from(c, c->cfg.hash_seed, tokens, n_tokens, ids_out, n_chunks_out);
 }
 
 lmc_status_t lmc_lookup(lmc_ctx_t *c, const uint64_t *ids, int64_t n, int64_t *n_hit_out) {

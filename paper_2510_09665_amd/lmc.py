@@ -24,7 +24,9 @@ LMC_FLAG_DIRECT = 16
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblmc.so")
 
 EXPORTS = [
-    "lmc_create", "lmc_destroy", "lmc_chunk_bytes", "lmc_pool_slots", "lmc_hash_chunks",
+    "lmc_create", "lmc_destroy", "lmc_chunk_bytes", "lmc_chunk_tokens", "lmc_pool_slots",
+    "lmc_hash_chunks", "lmc_hash_chunks_from", "lmc_seq_open", "lmc_seq_append",
+    "lmc_seq_pending_tokens", "lmc_seq_close",
     "lmc_lookup", "lmc_store", "lmc_retrieve", "lmc_retrieve_batch", "lmc_retrieve_layerwise",
     "lmc_store_begin", "lmc_store_layers", "lmc_wait_layer", "lmc_wait", "lmc_gather",
     "lmc_scatter", "lmc_put_host", "lmc_get_host", "lmc_find_slot", "lmc_pin", "lmc_unpin",
@@ -90,7 +92,13 @@ def _lib():
             "lmc_create": (st, [ctypes.POINTER(lmc_config_t), ctypes.POINTER(vp)]),
             "lmc_destroy": (st, [vp]),
             "lmc_chunk_bytes": (i64, [vp]),
+            "lmc_chunk_tokens": (i32, [vp]),
             "lmc_pool_slots": (i64, [vp]),
+            "lmc_hash_chunks_from": (st, [vp, u64, vp, i64, vp, ctypes.POINTER(i64)]),
+            "lmc_seq_open": (st, [vp, vp, vp, i64, ctypes.POINTER(vp)]),
+            "lmc_seq_append": (st, [vp, vp, vp, i64, vp, vp, ctypes.POINTER(i64), ctypes.POINTER(u64)]),
+            "lmc_seq_pending_tokens": (st, [vp, ctypes.POINTER(i64)]),
+            "lmc_seq_close": (st, [vp]),
             "lmc_hash_chunks": (st, [vp, vp, i64, vp, ctypes.POINTER(i64)]),
             "lmc_lookup": (st, [vp, vp, i64, ctypes.POINTER(i64)]),
             "lmc_store": (st, [vp, vp, vp, vp, i64, vp, ctypes.POINTER(u64)]),
@@ -211,6 +219,18 @@ class Context:
         self._check(_lib().lmc_hash_chunks(self._h, tp, tok.size, ctypes.c_void_p(out.ctypes.data),
                                            ctypes.byref(n)), "lmc_hash_chunks")
         return out[:n.value]
+
+    def hash_chunks_from(self, prev_id, tokens):
+        tok, tp = _host(tokens, np.int32)
+        out = np.empty(tok.size // self.chunk_tokens, dtype=np.uint64)
+        n = ctypes.c_int64()
+        self._check(_lib().lmc_hash_chunks_from(self._h, int(prev_id), tp, tok.size,
+                                                ctypes.c_void_p(out.ctypes.data), ctypes.byref(n)),
+                    "lmc_hash_chunks_from")
+        return out[:n.value]
+
+    def seq_open(self, prompt_tokens, prompt_slots):
+        return Sequence(self, prompt_tokens, prompt_slots)
 
     def lookup(self, chunk_ids):
         ids, ip = _host(chunk_ids, np.uint64)
@@ -344,6 +364,49 @@ class Context:
 
     def tune(self, key, value):
         self._check(_lib().lmc_tune(self._h, key.encode(), int(value)), "lmc_tune")
+
+
+class Sequence:
+    """One lmc_seq_t: the delayed-decode-storing accumulator of one sequence."""
+
+    def __init__(self, ctx, prompt_tokens, prompt_slots):
+        self._ctx = ctx
+        self._h = None
+        tok, tp = _host(prompt_tokens, np.int32)
+        sl, sp = _host(prompt_slots, np.int64)
+        if tok.size != sl.size:
+            raise ValueError("one slot per token")
+        h = ctypes.c_void_p()
+        ctx._check(_lib().lmc_seq_open(ctx._h, tp, sp, tok.size, ctypes.byref(h)), "lmc_seq_open")
+        self._h = h
+
+    def append(self, tokens, slots, kv_layers, stream=None):
+        """Returns (chunks completed by this call, ticket of the last store or 0)."""
+        tok, tp = _host(tokens, np.int32)
+        sl, sp = _host(slots, np.int64)
+        if tok.size != sl.size:
+            raise ValueError("one slot per token")
+        n, t = ctypes.c_int64(), ctypes.c_uint64()
+        rc = _lib().lmc_seq_append(self._h, tp, sp, tok.size, self._ctx._layers(kv_layers),
+                                   _stream(stream), ctypes.byref(n), ctypes.byref(t))
+        self._ctx._check(rc, "lmc_seq_append", t.value)
+        return n.value, t.value
+
+    def pending_tokens(self):
+        n = ctypes.c_int64()
+        self._ctx._check(_lib().lmc_seq_pending_tokens(self._h, ctypes.byref(n)), "lmc_seq_pending_tokens")
+        return n.value
+
+    def close(self):
+        if self._h is not None:
+            _lib().lmc_seq_close(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def strerror(status):

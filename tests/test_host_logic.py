@@ -51,6 +51,19 @@ def test_hash_chunks_matches_oracle():
         assert np.array_equal(c.hash_chunks(toks), oracle.hash_chunks(toks, 16, 0))
 
 
+def test_hash_chain_can_be_continued():
+    g = W.geometry("tiny")
+    rng = np.random.default_rng(8)
+    toks = W.tokens_for(rng, 256 * 7 + 30)
+    with _ctx(g, 1, hash_seed=5) as c:
+        whole = c.hash_chunks(toks)
+        for cut in (1, 3, 6):
+            rest = c.hash_chunks_from(whole[cut - 1], toks[256 * cut:])
+            assert np.array_equal(rest, whole[cut:])
+        assert np.array_equal(c.hash_chunks_from(5, toks), whole)
+        assert np.array_equal(whole, oracle.hash_chunks(toks, 256, 5))
+
+
 def test_sizes_and_bad_configs():
     for name in W.CONFIGS:
         g = W.geometry(name)
