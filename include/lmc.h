@@ -148,6 +148,7 @@ lmc_status_t lmc_destroy(lmc_ctx_t *ctx);
 
 int64_t lmc_chunk_bytes(const lmc_ctx_t *ctx); /* chunk_tokens*layers*planes*heads*dim*elem */
 int32_t lmc_chunk_tokens(const lmc_ctx_t *ctx);
+int32_t lmc_block_size(const lmc_ctx_t *ctx);
 int64_t lmc_pool_slots(const lmc_ctx_t *ctx);
 
 /* Token processor (section 4): chained 64-bit ids of the full chunks of a token
@@ -252,6 +253,10 @@ lmc_status_t lmc_wait_layer(lmc_ctx_t *ctx, uint64_t ticket, int32_t layer, void
  * is the ticket named (or ticket is 0); an older one is left out of the wait. */
 lmc_status_t lmc_wait(lmc_ctx_t *ctx, uint64_t ticket);
 
+/* Has the work of `ticket` finished?  LMC_OK: yes; LMC_ERR_BUSY: not yet (or a layer-wise
+ * store still lacks layers).  Never blocks, reports no slot errors. */
+lmc_status_t lmc_test(lmc_ctx_t *ctx, uint64_t ticket);
+
 /* The two kernels alone, for unit parity and for measuring them against HBM
  * bandwidth: pages -> n_chunks contiguous chunks at staging_dev (DEVICE,
  * n_chunks*chunk_bytes, 16-byte aligned) and back.  Enqueued on `stream`
@@ -300,6 +305,40 @@ lmc_status_t lmc_seq_append(lmc_seq_t *seq, const int32_t *tokens, const int64_t
                             uint64_t *last_ticket_out);
 lmc_status_t lmc_seq_pending_tokens(const lmc_seq_t *seq, int64_t *n_out);
 lmc_status_t lmc_seq_close(lmc_seq_t *seq);
+
+/* Dynamic offloading (section 5.3): the engine's free pages form a queue and only a
+ * window of them is duplicated to CPU memory.  Three pointers walk the queue: start (head
+ * of the free region), current (pages before it are offloaded), end (pages before it are
+ * scheduled).  A page here is one block over all layers, stored as one chunk, so the
+ * context must have chunk_tokens == block_size (else LMC_ERR_INVAL).  One window, one
+ * caller at a time.
+ * lmc_window_create: window_pages >= 1 is the target of end - start; max_batch_pages
+ *   bounds how many pages one lmc_store call duplicates.
+ * lmc_window_release: the engine frees n blocks (HOST arrays): they join the tail with the
+ *   ids under which their KV is cached; the end pointer follows until the window is full.
+ * lmc_window_offload: start duplicating the scheduled pages that have not been started
+ *   yet (lmc_store in batches, ordered after `stream`); n_issued_out may be NULL.  Pages
+ *   that find the pool full leave the window without a copy.
+ * lmc_window_acquire: a query wants n free pages.  LMC_OK: blocks_out[0..n) are the n
+ *   head blocks and the end pointer has moved forward by n.  LMC_ERR_BUSY: the request
+ *   stalls, nothing is taken: not all n pages are duplicated yet (a request larger than
+ *   the window pulls the end pointer to start + n; call lmc_window_offload and try
+ *   again).  With block != 0 the call first waits for the duplications in flight.
+ *   LMC_ERR_NOMEM: fewer than n free pages exist.
+ * lmc_window_get: pointer positions (absolute counts of pages that ever entered the free
+ *   region; any may be NULL) and the section's state number: 1 initialization, 2 in
+ *   progress, 4 steady (state 3, query arrival, is the move made by a granted acquire). */
+typedef struct lmc_window lmc_window_t;
+lmc_status_t lmc_window_create(lmc_ctx_t *ctx, int64_t window_pages, int64_t max_batch_pages,
+                               lmc_window_t **window_out);
+lmc_status_t lmc_window_destroy(lmc_window_t *w);
+lmc_status_t lmc_window_release(lmc_window_t *w, const int64_t *blocks, const uint64_t *chunk_ids,
+                                int64_t n);
+lmc_status_t lmc_window_offload(lmc_window_t *w, void *const *kv_layers, void *stream,
+                                int64_t *n_issued_out);
+lmc_status_t lmc_window_acquire(lmc_window_t *w, int64_t n, int64_t *blocks_out, int32_t block);
+lmc_status_t lmc_window_get(lmc_window_t *w, int64_t *start, int64_t *current, int64_t *end,
+                            int64_t *tail, int32_t *state);
 
 /* Local forms of the controller verbs of section 7, Table 3.  HOST pointers.
  * pin: every id must be present (else LMC_ERR_MISS, nothing pinned); adds one pin each.

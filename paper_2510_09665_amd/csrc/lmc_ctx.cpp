@@ -641,6 +641,7 @@ lmc_status_t lmc_destroy(lmc_ctx_t *c) {
 
 int64_t lmc_chunk_bytes(const lmc_ctx_t *c) { return c ? c->chunk_bytes : 0; }
 int32_t lmc_chunk_tokens(const lmc_ctx_t *c) { return c ? c->cfg.geom.chunk_tokens : 0; }
+int32_t lmc_block_size(const lmc_ctx_t *c) { return c ? c->cfg.geom.block_size : 0; }
 int64_t lmc_pool_slots(const lmc_ctx_t *c) { return c ? c->n_pool_slots : 0; }
 
 lmc_status_t lmc_hash_chunks_from(const lmc_ctx_t *c, uint64_t prev_id, const int32_t *tokens,
@@ -949,6 +950,16 @@ lmc_status_t lmc_wait(lmc_ctx_t *c, uint64_t ticket) {
         return LMC_ERR_BADSLOT;
     }
     return LMC_OK;
+}
+
+lmc_status_t lmc_test(lmc_ctx_t *c, uint64_t ticket) {
+    if (!c || ticket == 0) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    if (ticket >= c->next_ticket) return LMC_ERR_INVAL;
+    if (!c->has_device) return LMC_OK;
+    DeviceScope dev(c);
+    reap(c);
+    return find_op(c, ticket) == nullptr ? LMC_OK : LMC_ERR_BUSY;
 }
 
 static lmc_status_t device_only(lmc_ctx_t *c, bool gather, void *const *kv_layers,

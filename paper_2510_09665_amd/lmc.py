@@ -26,7 +26,9 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblmc.so")
 EXPORTS = [
     "lmc_create", "lmc_destroy", "lmc_chunk_bytes", "lmc_chunk_tokens", "lmc_pool_slots",
     "lmc_hash_chunks", "lmc_hash_chunks_from", "lmc_seq_open", "lmc_seq_append",
-    "lmc_seq_pending_tokens", "lmc_seq_close",
+    "lmc_seq_pending_tokens", "lmc_seq_close", "lmc_block_size", "lmc_test", "lmc_window_create",
+    "lmc_window_destroy", "lmc_window_release", "lmc_window_offload", "lmc_window_acquire",
+    "lmc_window_get",
     "lmc_lookup", "lmc_store", "lmc_retrieve", "lmc_retrieve_batch", "lmc_retrieve_layerwise",
     "lmc_store_begin", "lmc_store_layers", "lmc_wait_layer", "lmc_wait", "lmc_gather",
     "lmc_scatter", "lmc_put_host", "lmc_get_host", "lmc_find_slot", "lmc_pin", "lmc_unpin",
@@ -99,6 +101,14 @@ def _lib():
             "lmc_seq_append": (st, [vp, vp, vp, i64, vp, vp, ctypes.POINTER(i64), ctypes.POINTER(u64)]),
             "lmc_seq_pending_tokens": (st, [vp, ctypes.POINTER(i64)]),
             "lmc_seq_close": (st, [vp]),
+            "lmc_block_size": (i32, [vp]),
+            "lmc_test": (st, [vp, u64]),
+            "lmc_window_create": (st, [vp, i64, i64, ctypes.POINTER(vp)]),
+            "lmc_window_destroy": (st, [vp]),
+            "lmc_window_release": (st, [vp, vp, vp, i64]),
+            "lmc_window_offload": (st, [vp, vp, vp, ctypes.POINTER(i64)]),
+            "lmc_window_acquire": (st, [vp, i64, vp, i32]),
+            "lmc_window_get": (st, [vp] + [ctypes.POINTER(i64)] * 4 + [ctypes.POINTER(i32)]),
             "lmc_hash_chunks": (st, [vp, vp, i64, vp, ctypes.POINTER(i64)]),
             "lmc_lookup": (st, [vp, vp, i64, ctypes.POINTER(i64)]),
             "lmc_store": (st, [vp, vp, vp, vp, i64, vp, ctypes.POINTER(u64)]),
@@ -293,6 +303,17 @@ class Context:
     def wait_layer(self, ticket, layer, stream=None):
         self._check(_lib().lmc_wait_layer(self._h, ticket, layer, _stream(stream)), "lmc_wait_layer")
 
+    def test(self, ticket):
+        """True if the ticket's work has finished (never blocks)."""
+        rc = _lib().lmc_test(self._h, ticket)
+        if rc == LMC_ERR_BUSY:
+            return False
+        self._check(rc, "lmc_test")
+        return True
+
+    def window_create(self, window_pages, max_batch_pages=64):
+        return Window(self, window_pages, max_batch_pages)
+
     def wait(self, ticket=0):
         self._check(_lib().lmc_wait(self._h, ticket), "lmc_wait")
 
@@ -405,6 +426,57 @@ class Sequence:
     def __del__(self):
         try:
             self.close()
+        except Exception:
+            pass
+
+
+class Window:
+    """One lmc_window_t: the three-pointer window of dynamic offloading."""
+
+    def __init__(self, ctx, window_pages, max_batch_pages):
+        self._ctx, self._h = ctx, None
+        h = ctypes.c_void_p()
+        ctx._check(_lib().lmc_window_create(ctx._h, window_pages, max_batch_pages, ctypes.byref(h)),
+                   "lmc_window_create")
+        self._h = h
+
+    def release(self, blocks, chunk_ids):
+        b, bp = _host(blocks, np.int64)
+        i, ip = _host(chunk_ids, np.uint64)
+        if b.size != i.size:
+            raise ValueError("one id per block")
+        self._ctx._check(_lib().lmc_window_release(self._h, bp, ip, b.size), "lmc_window_release")
+
+    def offload(self, kv_layers, stream=None):
+        n = ctypes.c_int64()
+        self._ctx._check(_lib().lmc_window_offload(self._h, self._ctx._layers(kv_layers), _stream(stream),
+                                                   ctypes.byref(n)), "lmc_window_offload")
+        return n.value
+
+    def acquire(self, n, block=False):
+        """The n head blocks, or None when the request stalls."""
+        out = np.empty(n, dtype=np.int64)
+        rc = _lib().lmc_window_acquire(self._h, n, ctypes.c_void_p(out.ctypes.data), 1 if block else 0)
+        if rc == LMC_ERR_BUSY:
+            return None
+        self._ctx._check(rc, "lmc_window_acquire")
+        return out
+
+    def get(self):
+        v = [ctypes.c_int64() for _ in range(4)]
+        st = ctypes.c_int32()
+        self._ctx._check(_lib().lmc_window_get(self._h, *[ctypes.byref(x) for x in v], ctypes.byref(st)),
+                         "lmc_window_get")
+        return dict(start=v[0].value, current=v[1].value, end=v[2].value, tail=v[3].value, state=st.value)
+
+    def destroy(self):
+        if self._h is not None:
+            _lib().lmc_window_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
         except Exception:
             pass
 
