@@ -44,7 +44,6 @@ struct Op {
     uint64_t ticket = 0;
     hipEvent_t done = nullptr;       // null: nothing enqueued (yet) for this ticket
     std::vector<int64_t> slots;      // pool slots whose in-flight count this op holds
-    bool is_store = false;
     // layer-wise operations (paper section 5.2)
     bool layerwise = false;
     bool pending = false;                 // a store whose layers have not all been submitted
@@ -577,6 +576,9 @@ lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out) {
     if (rc == LMC_OK) {
         c->n_pool_slots = int64_t(cfg->host_pool_bytes / uint64_t(c->chunk_bytes));
         if (c->n_pool_slots < 1) rc = LMC_ERR_INVAL;
+        // one launch must be able to cover a whole staging buffer
+        if (int64_t(cfg->staging_chunks) > int64_t(lmc::max_chunks_per_launch(c->kg, lmc::bulk_view(c->kg))))
+            rc = LMC_ERR_INVAL;
     }
     if (rc != LMC_OK) {
         delete c;
@@ -777,7 +779,6 @@ lmc_status_t lmc_store(lmc_ctx_t *c, void *const *kv_layers, const int64_t *slot
 
     Op op;
     op.ticket = c->next_ticket++;
-    op.is_store = true;
     std::vector<int64_t> new_chunk;
     const bool fits = admit_new_chunks(c, ids, n_chunks, &op, &new_chunk);
     c->stats.chunks_stored += new_chunk.size();
@@ -805,7 +806,6 @@ lmc_status_t lmc_store_begin(lmc_ctx_t *c, const int64_t *slot_mapping, const ui
     if ((rc = validate_slots(c, slot_mapping, n_chunks * CT, c->s_gather)) != LMC_OK) return rc;
     Op op;
     op.ticket = c->next_ticket++;
-    op.is_store = true;
     op.layerwise = true;
     const bool fits = admit_new_chunks(c, ids, n_chunks, &op, &op.new_chunk);
     c->stats.chunks_stored += op.new_chunk.size();

@@ -380,3 +380,25 @@ def test_store_and_retrieve_run_concurrently_from_two_threads():
         for s, t in zip(src_b.compact_slots(sb).reshape(n, g.CT), dst_b.compact_slots(tb).reshape(n, g.CT)):
             oracle.scatter_chunk(dst_b.gc, oracle.gather_chunk(src_b.gc, src_b.host, s), t, dst_b.host)
         assert_layers_equal(dst_b.device_blocks_to_host(), dst_b.host)
+
+
+def test_allocation_failures_are_clean_errors():
+    """A pool or a staging ring that cannot be allocated gives LMC_ERR_NOMEM and leaves
+    nothing behind: a normal context can be created right after."""
+    import torch
+    lmc = _lmc()
+    g = W.geometry("llama3_8b")
+    with lmc.Context(g, 2 * g.chunk_bytes):                       # the runtime's own stream resources exist now
+        pass
+    torch.cuda.synchronize()
+    free_before = torch.cuda.mem_get_info()[0]
+    with pytest.raises(lmc.LMCError) as e:
+        lmc.Context(g, 1 << 50)                                   # a petabyte of pinned memory
+    assert e.value.status == lmc.LMC_ERR_NOMEM
+    with pytest.raises(lmc.LMCError) as e:
+        lmc.Context(g, 2 * g.chunk_bytes, staging_chunks=200000)  # 6 TiB of staging per buffer
+    assert e.value.status == lmc.LMC_ERR_NOMEM
+    torch.cuda.synchronize()
+    assert torch.cuda.mem_get_info()[0] >= free_before - (64 << 20)
+    with lmc.Context(g, 2 * g.chunk_bytes) as c:
+        assert c.pool_slots() == 2
