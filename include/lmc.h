@@ -140,8 +140,8 @@ typedef struct {
  * pin/unpin/clear, stats); every call that would move data to or from a GPU returns
  * LMC_ERR_NODEVICE.  There is no CPU implementation of the data path.
  * Errors: LMC_ERR_INVAL (a geometry field out of the ranges given at lmc_kv_geom_t,
- * num_staging < 2, staging_chunks < 1, pool smaller than one chunk), LMC_ERR_NOMEM,
- * LMC_ERR_HIP. */
+ * num_staging < 2, staging_chunks < 1 or more than one launch can cover, pool smaller
+ * than one chunk), LMC_ERR_NOMEM (pool or staging cannot be allocated), LMC_ERR_HIP. */
 lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out);
 /* Waits for outstanding work, then frees everything the context owns. */
 lmc_status_t lmc_destroy(lmc_ctx_t *ctx);

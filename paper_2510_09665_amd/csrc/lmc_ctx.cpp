@@ -309,10 +309,19 @@ lmc_status_t copy_group(lmc_ctx *c, bool to_host, uint8_t *staging, uint64_t str
         if (m == 1 || (width == cb && stride == cb)) {
             if (to_host) HIPCHK(c, hipMemcpyAsync(host, dev, size_t(m * width), kind, stream));
             else HIPCHK(c, hipMemcpyAsync(dev, host, size_t(m * width), kind, stream));
-        } else if (to_host) {
-            HIPCHK(c, hipMemcpy2DAsync(host, cb, dev, stride, width, size_t(m), kind, stream));
         } else {
-            HIPCHK(c, hipMemcpy2DAsync(dev, stride, host, cb, width, size_t(m), kind, stream));
+            hipError_t e = to_host ? hipMemcpy2DAsync(host, cb, dev, stride, width, size_t(m), kind, stream)
+                                   : hipMemcpy2DAsync(dev, stride, host, cb, width, size_t(m), kind, stream);
+            if (e == hipErrorInvalidPitchValue || e == hipErrorInvalidValue) {
+                // a pitch the runtime does not take: one plain copy per chunk instead
+                (void)hipGetLastError();
+                for (int64_t i = 0; i < m; i++) {
+                    if (to_host) HIPCHK(c, hipMemcpyAsync(host + uint64_t(i) * cb, dev + uint64_t(i) * stride, size_t(width), kind, stream));
+                    else HIPCHK(c, hipMemcpyAsync(dev + uint64_t(i) * stride, host + uint64_t(i) * cb, size_t(width), kind, stream));
+                }
+            } else {
+                HIPCHK(c, e);
+            }
         }
         if (to_host) c->stats.bytes_d2h += uint64_t(m) * width;
         else c->stats.bytes_h2d += uint64_t(m) * width;
