@@ -74,6 +74,7 @@ struct lmc_ctx {
     lmc::ChunkIndex index;
     std::mutex mu;
     hipStream_t s_gather = nullptr, s_d2h = nullptr, s_h2d = nullptr, s_scatter = nullptr;
+    hipStream_t s_h2d2 = nullptr;  // second copy stream: layer-wise steps alternate between the two
     Ring store_ring, load_ring;
     int32_t *bad_flag_host = nullptr, *bad_flag_dev = nullptr;
     std::deque<Op> ops;
@@ -367,10 +368,11 @@ lmc_status_t make_ring(lmc_ctx *c, Ring &r) {
 // first waits for everything the consumer stream has been given, so no slot of the old
 // division is still being read when the new division is written.
 lmc_status_t ring_reslot(lmc_ctx *c, Ring &r, uint64_t slot_bytes, hipStream_t producer,
-                         hipStream_t consumer) {
+                         hipStream_t consumer, hipStream_t producer2 = nullptr) {
     if (slot_bytes == r.slot_bytes) return LMC_OK;
     if (r.slot_bytes != 0) {
         lmc_status_t rc = order_after(c, producer, consumer);
+        if (rc == LMC_OK && producer2 != nullptr) rc = order_after(c, producer2, consumer);
         if (rc != LMC_OK) return rc;
     }
     r.slot_bytes = slot_bytes;
@@ -453,6 +455,7 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
 
     const bool direct = (c->cfg.flags & LMC_FLAG_DIRECT) != 0;
     if ((rc = after_stores(c, pool_slots, direct ? c->s_scatter : c->s_h2d)) != LMC_OK) return rc;
+    if (!direct && layers_per_step > 0 && (rc = after_stores(c, pool_slots, c->s_h2d2)) != LMC_OK) return rc;
     Op op;
     op.ticket = c->next_ticket++;
     op.layerwise = layers_per_step > 0;
@@ -480,15 +483,16 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
     };
     // one group: copies into the next ring buffer on the H2D stream, scatter on the
     // scatter stream; the buffer is released when the scatter has read it
-    auto load_group = [&](const lmc::LaunchView &view, uint64_t pool_off, int64_t i0, int64_t k) -> lmc_status_t {
+    auto load_group = [&](const lmc::LaunchView &view, uint64_t pool_off, int64_t i0, int64_t k,
+                          hipStream_t copy_stream) -> lmc_status_t {
         uint8_t *buf;
         const size_t b = ring_next(ring, &buf);
-        if (ring.used[b]) HIPCHK(c, hipStreamWaitEvent(c->s_h2d, ring.drained[b], 0));
+        if (ring.used[b]) HIPCHK(c, hipStreamWaitEvent(copy_stream, ring.drained[b], 0));
         lmc_status_t r = copy_group(c, false, buf, view.chunk_stride, &pool_slots[size_t(i0)], k,
-                                    pool_off, view.chunk_stride, c->s_h2d);
+                                    pool_off, view.chunk_stride, copy_stream);
         if (r != LMC_OK) return r;
-        HIPCHK(c, hipEventRecord(ring.filled[b], c->s_h2d));
-        if ((r = force_sync(c, c->s_h2d)) != LMC_OK) return r;
+        HIPCHK(c, hipEventRecord(ring.filled[b], copy_stream));
+        if ((r = force_sync(c, copy_stream)) != LMC_OK) return r;
         HIPCHK(c, hipStreamWaitEvent(c->s_scatter, ring.filled[b], 0));
         r = timed_launch(c, false, view, ptrs, slot_mapping + i0 * CT, uint32_t(k), buf, c->s_scatter);
         if (r != LMC_OK) return r;
@@ -510,7 +514,7 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
         const int64_t body = (edge > 0 && n_chunks > edge) ? n_chunks - edge : n_chunks;
         for (int64_t i0 = 0, k = 0; i0 < n_chunks; i0 += k) {
             k = i0 < body ? std::min(per, body - i0) : n_chunks - i0;
-            if ((rc = load_group(view, 0, i0, k)) != LMC_OK) return rc;
+            if ((rc = load_group(view, 0, i0, k, c->s_h2d)) != LMC_OK) return rc;
         }
     } else {
         // All chunks' share of a few layers at a time: one rectangle copy per run of pool
@@ -526,10 +530,14 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
             } else {
                 const int64_t cap = layer_group_chunks(c, ring, view, n_chunks);
                 if ((rc = ring_reslot(c, ring, (uint64_t(cap) * view.chunk_stride + 255) / 256 * 256, c->s_h2d,
-                                      c->s_scatter)) != LMC_OK)
+                                      c->s_scatter, c->s_h2d2)) != LMC_OK)
                     return rc;
+                // Steps alternate between two copy streams: on one stream the runtime puts
+                // an event marker between consecutive copies, which costs the link about
+                // 20 us per step; with two streams the next step's copy is already running.
+                hipStream_t cs = ((l0 / layers_per_step) & 1) ? c->s_h2d2 : c->s_h2d;
                 for (int64_t i0 = 0; i0 < n_chunks; i0 += cap)
-                    if ((rc = load_group(view, uint64_t(l0) * layer_bytes, i0, std::min(cap, n_chunks - i0))) != LMC_OK)
+                    if ((rc = load_group(view, uint64_t(l0) * layer_bytes, i0, std::min(cap, n_chunks - i0), cs)) != LMC_OK)
                         return rc;
             }
             hipEvent_t e;
@@ -558,7 +566,7 @@ void destroy_ctx(lmc_ctx *c) {
         free_ring(c->store_ring);
         free_ring(c->load_ring);
         for (hipEvent_t e : c->all_events) (void)hipEventDestroy(e);
-        for (hipStream_t s : {c->s_gather, c->s_d2h, c->s_h2d, c->s_scatter})
+        for (hipStream_t s : {c->s_gather, c->s_d2h, c->s_h2d, c->s_scatter, c->s_h2d2})
             if (s) (void)hipStreamDestroy(s);
         if (c->bad_flag_host) (void)hipHostFree(c->bad_flag_host);
         if (c->pool) (void)hipHostFree(c->pool);
@@ -633,7 +641,7 @@ lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out) {
         *c->bad_flag_host = 0;
         if (hipHostGetDevicePointer(reinterpret_cast<void **>(&c->bad_flag_dev), c->bad_flag_host, 0) != hipSuccess)
             return fail(LMC_ERR_HIP);
-        for (hipStream_t *s : {&c->s_gather, &c->s_d2h, &c->s_h2d, &c->s_scatter})
+        for (hipStream_t *s : {&c->s_gather, &c->s_d2h, &c->s_h2d, &c->s_scatter, &c->s_h2d2})
             if (hipStreamCreateWithFlags(s, hipStreamNonBlocking) != hipSuccess) return fail(LMC_ERR_HIP);
         if ((rc = make_ring(c, c->store_ring)) != LMC_OK) return fail(rc);
         if ((rc = make_ring(c, c->load_ring)) != LMC_OK) return fail(rc);
