@@ -376,7 +376,10 @@ lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *ctx, uint64_t nbytes, int32_t re
  * "nt_store" (0/1: non-temporal hints on the kernels' streaming accesses), "xcd_run"
  * (consecutive tiles handed to one XCD, 0 = hardware round-robin), "edge_chunks" (size
  * of the group at the exposed end of a pipeline, 0 = none), "timing" (0/1: switches
- * LMC_FLAG_TIMING).  Unknown key or out-of-range value: LMC_ERR_INVAL. */
+ * LMC_FLAG_TIMING), "direct_store_below" / "direct_retrieve_below" (bytes, defaults 4 MiB /
+ * 2 MiB: an lmc_store with at most that many new bytes, or an lmc_retrieve /
+ * lmc_retrieve_batch of at most that many bytes, goes the LMC_FLAG_DIRECT way because
+ * a transfer that small is bound by launch latencies, not by the link; 0 = never).  Unknown key or out-of-range value: LMC_ERR_INVAL. */
 lmc_status_t lmc_tune(lmc_ctx_t *ctx, const char *key, int64_t value);
 
 const char *lmc_strerror(lmc_status_t status);

@@ -66,6 +66,11 @@ struct lmc_ctx {
     lmc::KernelGeom kg{};
     lmc::LaunchShape shape{};
     int64_t edge_chunks = 1;  // size of the group at the exposed end of a pipeline; 0 = no special group
+    // Bulk calls that move at most this many bytes skip staging and the copy engine (the
+    // kernel itself crosses the link): below a few MiB the copy's launch and the extra
+    // event hand-over cost more than the kernel's lower link efficiency.  0 = never.
+    int64_t direct_store_below = int64_t(4) << 20;
+    int64_t direct_retrieve_below = int64_t(2) << 20;
     int64_t chunk_bytes = 0;
     int64_t n_pool_slots = 0;
     uint8_t *pool = nullptr;
@@ -406,21 +411,22 @@ int64_t layer_group_chunks(const lmc_ctx *c, const Ring &r, const lmc::LaunchVie
 }
 
 // A chunk whose store is still on its way to the pool must be loaded after that store:
-// the H2D stream waits for the newest such store (stores complete in order on one
-// stream).  A layer-wise store that has not been submitted completely cannot be waited
-// for on the device: LMC_ERR_BUSY.
+// the loading stream waits for every such store (stores end on different streams, the
+// D2H stream or, without staging, the gather stream, so the newest alone says nothing
+// about the others).  A layer-wise store that has not been submitted completely cannot
+// be waited for on the device: LMC_ERR_BUSY.
 lmc_status_t after_stores(lmc_ctx *c, const std::vector<int64_t> &pool_slots, hipStream_t waiter) {
-    uint64_t newest = 0;
+    std::vector<uint64_t> tickets;
     for (int64_t s : pool_slots) {
         const uint64_t t = c->index.meta(s).ready_ticket;
-        if (t == 0) continue;
+        if (t == 0 || (!tickets.empty() && tickets.back() == t)) continue;
         const Op *o = find_op(c, t);
         if (o == nullptr) continue;  // finished
         if (o->pending) return LMC_ERR_BUSY;
-        newest = std::max(newest, t);
+        if (std::find(tickets.begin(), tickets.end(), t) == tickets.end()) tickets.push_back(t);
     }
-    if (newest != 0) {
-        const Op *o = find_op(c, newest);
+    for (uint64_t t : tickets) {
+        const Op *o = find_op(c, t);
         if (o != nullptr && o->done != nullptr) HIPCHK(c, hipStreamWaitEvent(waiter, o->done, 0));
     }
     return LMC_OK;
@@ -453,7 +459,8 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
     rc = validate_slots(c, slot_mapping, n_chunks * CT, c->s_scatter);
     if (rc != LMC_OK) return rc;
 
-    const bool direct = (c->cfg.flags & LMC_FLAG_DIRECT) != 0;
+    const bool direct = (c->cfg.flags & LMC_FLAG_DIRECT) != 0 ||
+                        (layers_per_step == 0 && n_chunks * c->chunk_bytes <= c->direct_retrieve_below);
     if ((rc = after_stores(c, pool_slots, direct ? c->s_scatter : c->s_h2d)) != LMC_OK) return rc;
     if (!direct && layers_per_step > 0 && (rc = after_stores(c, pool_slots, c->s_h2d2)) != LMC_OK) return rc;
     Op op;
@@ -464,8 +471,9 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
     Ring &ring = c->load_ring;
     const uint64_t cb = uint64_t(c->chunk_bytes);
     const int64_t per = c->cfg.staging_chunks;
-    // LMC_FLAG_DIRECT: no staging, no copy: the scatter kernel reads the pinned pool over
-    // the link; one launch per run of consecutive pool slots (and per layer step)
+    // without staging (LMC_FLAG_DIRECT, or a small bulk call): no copy, the scatter kernel
+    // reads the pinned pool over the link; one launch per run of consecutive pool slots
+    // (and per layer step)
     auto load_direct = [&](lmc::LaunchView view, uint64_t pool_off) -> lmc_status_t {
         view.chunk_stride = cb;  // chunks lie one pool slot apart
         const int64_t max_k = int64_t(lmc::max_chunks_per_launch(c->kg, view));
@@ -722,10 +730,10 @@ static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64
                                  const lmc::LayerPtrs &ptrs, const int64_t *slot_mapping,
                                  const std::vector<int64_t> &new_chunk,
                                  const std::vector<int64_t> &new_slot, int64_t cap_chunks,
-                                 bool edge_group) {
+                                 bool edge_group, bool direct) {
     Ring &ring = c->store_ring;
     const int64_t CT = c->cfg.geom.chunk_tokens;
-    if (c->cfg.flags & LMC_FLAG_DIRECT) {
+    if (direct) {
         // no staging, no copy: the gather kernel writes the pinned pool over the link; one
         // launch per run of chunks that are consecutive both in the slot mapping and in the pool
         lmc::LaunchView v = view;
@@ -799,12 +807,15 @@ lmc_status_t lmc_store(lmc_ctx_t *c, void *const *kv_layers, const int64_t *slot
     std::vector<int64_t> new_chunk;
     const bool fits = admit_new_chunks(c, ids, n_chunks, &op, &new_chunk);
     c->stats.chunks_stored += new_chunk.size();
-    if ((rc = ring_reslot(c, c->store_ring, c->store_ring.buf_bytes, c->s_gather, c->s_d2h)) != LMC_OK) return rc;
+    const bool direct = (c->cfg.flags & LMC_FLAG_DIRECT) != 0 ||
+                        int64_t(new_chunk.size()) * c->chunk_bytes <= c->direct_store_below;
+    if (!direct &&
+        (rc = ring_reslot(c, c->store_ring, c->store_ring.buf_bytes, c->s_gather, c->s_d2h)) != LMC_OK)
+        return rc;
     rc = store_groups(c, lmc::bulk_view(c->kg), 0, ptrs, slot_mapping, new_chunk, op.slots,
-                      c->cfg.staging_chunks, true);
+                      c->cfg.staging_chunks, true, direct);
     if (rc != LMC_OK) return rc;
-    rc = finish_op(c, std::move(op), (c->cfg.flags & LMC_FLAG_DIRECT) ? c->s_gather : c->s_d2h,
-                   !new_chunk.empty(), ticket_out);
+    rc = finish_op(c, std::move(op), direct ? c->s_gather : c->s_d2h, !new_chunk.empty(), ticket_out);
     if (rc != LMC_OK) return rc;
     return fits ? LMC_OK : LMC_ERR_NOMEM;
 }
@@ -864,7 +875,7 @@ lmc_status_t lmc_store_layers(lmc_ctx_t *c, uint64_t ticket, int32_t first_layer
                           c->s_d2h)) != LMC_OK)
         return rc;
     rc = store_groups(c, view, uint64_t(first_layer) * layer_bytes, ptrs, op->slot_mapping, op->new_chunk,
-                      op->slots, cap, false);
+                      op->slots, cap, false, (c->cfg.flags & LMC_FLAG_DIRECT) != 0);
     if (rc != LMC_OK) return rc;
     hipEvent_t e;
     if ((rc = get_event(c, false, &e)) != LMC_OK) return rc;
@@ -1240,6 +1251,10 @@ lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
         c->cfg.flags = value ? (c->cfg.flags | LMC_FLAG_TIMING) : (c->cfg.flags & ~LMC_FLAG_TIMING);
     } else if (k == "edge_chunks") {
         c->edge_chunks = value;
+    } else if (k == "direct_store_below") {
+        c->direct_store_below = value;
+    } else if (k == "direct_retrieve_below") {
+        c->direct_retrieve_below = value;
     } else if (k == "xcd_run") {
         if (value > (1 << 20)) return LMC_ERR_INVAL;
         c->shape.xcd_run = uint32_t(value);

@@ -33,6 +33,8 @@ class KVGeometry:
     CT: int = 256
     layout: str = "NHD"          # "NHD": [P][NB][BS][H][D]   "HND": [P][NB][H][BS][D]
     block_pad: int = 0           # extra bytes after every block (exercises padded strides)
+    order: str = "PN"            # "PN": planes outermost, as above; "NP": blocks outermost,
+                                 # [NB][P][...]: the K and V page of a block are neighbours
     plane_stride: int = field(init=False)
     block_stride: int = field(init=False)
     token_stride: int = field(init=False)
@@ -46,11 +48,17 @@ class KVGeometry:
             token, head = run, self.BS * run
         else:
             raise ValueError(self.layout)
-        block = self.BS * self.H * run + self.block_pad
+        page = self.BS * self.H * run + self.block_pad
+        if self.order == "PN":
+            plane, block = self.NB * page, page
+        elif self.order == "NP":
+            plane, block = page, self.P * page
+        else:
+            raise ValueError(self.order)
         object.__setattr__(self, "head_stride", head)
         object.__setattr__(self, "token_stride", token)
         object.__setattr__(self, "block_stride", block)
-        object.__setattr__(self, "plane_stride", self.NB * block)
+        object.__setattr__(self, "plane_stride", plane)
 
     @property
     def R(self):
@@ -58,8 +66,13 @@ class KVGeometry:
         return self.H * self.D * self.e
 
     @property
+    def page_bytes(self):
+        """bytes from one page (a block's share of one plane) to the next, padding included"""
+        return self.BS * self.R + self.block_pad
+
+    @property
     def layer_bytes(self):
-        return self.P * self.plane_stride
+        return self.P * self.NB * self.page_bytes
 
     @property
     def chunk_bytes(self):
@@ -80,6 +93,23 @@ CONFIGS = {
     "mla_bf16":    dict(id=5, geom=dict(L=61, P=1, H=1, D=576, e=2, BS=64, NB=1024), tokens=8192),
     "mla_fp8":     dict(id=5, geom=dict(L=61, P=1, H=1, D=576, e=1, BS=64, NB=1024), tokens=8192),
 }
+
+
+def page_view(geom, layer):
+    """A layer's bytes (numpy array or torch tensor) seen as [P][NB][page_bytes]."""
+    if geom.order == "PN":
+        return layer.reshape(geom.P, geom.NB, geom.page_bytes)
+    v = layer.reshape(geom.NB, geom.P, geom.page_bytes)
+    return v.transpose(1, 0) if hasattr(v, "is_contiguous") else v.transpose(1, 0, 2)
+
+
+def pages_to_layer(geom, pages):
+    """Inverse of page_view: [P][NB][page_bytes] (array or tensor) to the layer's flat bytes."""
+    if geom.order == "NP":
+        pages = pages.transpose(1, 0) if hasattr(pages, "is_contiguous") else pages.transpose(1, 0, 2)
+    if hasattr(pages, "is_contiguous"):
+        return pages.contiguous().view(-1)
+    return np.ascontiguousarray(pages).reshape(-1)
 
 
 def geometry(name, **overrides):

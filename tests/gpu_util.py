@@ -23,7 +23,6 @@ class PagedKV:
     device is block i of the compact geometry `gc`."""
 
     def __init__(self, geom, blocks, rng=None, device="cuda", fill="payload"):
-        assert geom.plane_stride == geom.NB * geom.block_stride
         self.g = geom
         self.blocks = np.asarray(blocks, dtype=np.int64)
         assert np.unique(self.blocks).size == self.blocks.size
@@ -36,8 +35,7 @@ class PagedKV:
             d = torch.full((geom.layer_bytes,), sentinel_byte(l), dtype=torch.uint8, device=device)
             if fill == "payload":
                 h = W.payload_bytes(rng, geom, self.gc.layer_bytes)
-                d.view(geom.P, geom.NB, geom.block_stride)[:, tb] = \
-                    torch.from_numpy(h).to(device).view(geom.P, self.gc.NB, geom.block_stride)
+                W.page_view(geom, d)[:, tb] = W.page_view(self.gc, torch.from_numpy(h).to(device))
             else:
                 h = np.full(self.gc.layer_bytes, sentinel_byte(l), dtype=np.uint8)
             self.dev.append(d)
@@ -59,8 +57,7 @@ class PagedKV:
         """The tracked blocks as they are on the device now, in compact layout."""
         tb = torch.from_numpy(self.blocks).to(self.dev[0].device)
         g = self.g
-        return [d.view(g.P, g.NB, g.block_stride)[:, tb].contiguous().view(-1).cpu().numpy()
-                for d in self.dev]
+        return [W.pages_to_layer(self.gc, W.page_view(g, d)[:, tb]).cpu().numpy() for d in self.dev]
 
     def untracked_blocks_untouched(self):
         """True if every block outside the tracked set still holds only the sentinel."""
@@ -68,7 +65,7 @@ class PagedKV:
         keep = torch.ones(g.NB, dtype=torch.bool, device=self.dev[0].device)
         keep[torch.from_numpy(self.blocks).to(keep.device)] = False
         for l, d in enumerate(self.dev):
-            v = d.view(g.P, g.NB, g.block_stride)[:, keep]
+            v = W.page_view(g, d)[:, keep]
             if not bool((v == sentinel_byte(l)).all()):
                 return False
         return True

@@ -13,7 +13,8 @@ pytestmark = pytest.mark.gpu
 # shapes chosen to cross every kernel path: 16-byte vectors with contiguous rows,
 # per-head runs (HND), padded blocks, rows that are not a multiple of a wavefront
 # (MLA: 72 and 36 vectors), narrow vectors (8/4/2/1 bytes), a block size that is not a
-# power of two, planes whose size is not a multiple of a 256-vector tile, P=1 and P=2.
+# power of two, planes whose size is not a multiple of a 256-vector tile, P=1 and P=2,
+# pages ordered blocks-outermost (the K and V page of a block adjacent in memory).
 SHAPES = {
     "tiny_cfg1": dict(L=2, P=2, H=4, D=64, e=2, BS=16, NB=64, CT=256),
     "hnd": dict(L=5, P=2, H=8, D=64, e=2, BS=16, NB=40, CT=64, layout="HND"),
@@ -26,6 +27,9 @@ SHAPES = {
     "vec1_pad": dict(L=2, P=1, H=2, D=5, e=1, BS=3, NB=70, CT=24, block_pad=1),
     "bs_not_pow2": dict(L=17, P=2, H=2, D=32, e=2, BS=12, NB=30, CT=48),
     "many_lp": dict(L=37, P=2, H=1, D=64, e=2, BS=16, NB=32, CT=128),
+    "blocks_outer": dict(L=4, P=2, H=4, D=64, e=2, BS=16, NB=48, CT=256, order="NP"),
+    "blocks_outer_hnd_pad": dict(L=3, P=2, H=3, D=12, e=2, BS=4, NB=64, CT=32, order="NP", layout="HND",
+                                 block_pad=8),
 }
 
 

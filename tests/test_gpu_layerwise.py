@@ -18,6 +18,7 @@ CASES = {
     "many_groups_per_layer": ("llama3_8b", dict(L=4, NB=1024), 24 * 256, 1, 1, "poison"),
     "mla_fp8_k3": ("mla_fp8", {}, 8192, 1, 3, 0),
     "hnd_k2": ("llama3_8b", dict(L=6, NB=512, layout="HND"), 8 * 256, 2, 2, 0),
+    "blocks_outer_k2": ("llama3_8b", dict(L=6, NB=512, order="NP"), 8 * 256, 2, 2, "poison"),
     "all_layers_in_one_step": ("tiny", {}, 256, 1, 99, 0),
     "direct_llama_k1": ("llama3_8b", dict(L=8, NB=1024), 10 * 256, 1, 1, "direct"),
     "direct_mla_k3": ("mla_bf16", dict(L=7), 4 * 256, 1, 3, "direct"),
@@ -90,7 +91,7 @@ def test_each_layer_is_complete_when_its_wait_returns(case):
         for l in range(g.L):
             c.wait_layer(t, l, consumer)
             with torch.cuda.stream(consumer):
-                snaps.append(dst.dev[l].view(g.P, g.NB, g.block_stride)[:, lb].clone())
+                snaps.append(W.page_view(g, dst.dev[l])[:, lb].clone())
         consumer.synchronize()
         c.wait(t)
         c.wait_layer(t, g.L - 1, consumer)          # a finished ticket: nothing to wait for
@@ -99,7 +100,7 @@ def test_each_layer_is_complete_when_its_wait_returns(case):
         for ch, s in zip(chunks, cs):
             oracle.scatter_chunk(dst.gc, ch, s, dst.host)
         for l in range(g.L):
-            assert np.array_equal(snaps[l].view(-1).cpu().numpy(), dst.host[l]), "layer %d" % l
+            assert np.array_equal(W.pages_to_layer(dst.gc, snaps[l]).cpu().numpy(), dst.host[l]), "layer %d" % l
         with pytest.raises(lmc.LMCError) as e:
             c.wait_layer(t, g.L, consumer)
         assert e.value.status == lmc.LMC_ERR_INVAL
@@ -134,8 +135,7 @@ def test_layerwise_store_matches_oracle(case):
         for l0 in range(0, g.L, k):
             kk = min(k, g.L - l0)
             for l in range(l0, l0 + kk):                          # forward pass produces the layer
-                live.dev[l].view(g.P, g.NB, g.block_stride)[:, tb] = \
-                    src.dev[l].view(g.P, g.NB, g.block_stride)[:, tb]
+                W.page_view(g, live.dev[l])[:, tb] = W.page_view(g, src.dev[l])[:, tb]
             # layers are still missing: the ticket cannot be waited for yet
             assert _status(lambda: c.wait(t)) == lmc.LMC_ERR_BUSY
             c.store_layers(t, l0, kk, live.dev, stream)

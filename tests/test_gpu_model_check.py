@@ -19,8 +19,12 @@ def _status(fn):
         return e.status
 
 
-@pytest.mark.parametrize("seed,flags", [(1, "poison"), (2, "direct"), (3, "none")])
-def test_random_operation_sequences(seed, flags):
+@pytest.mark.parametrize("seed,flags,small_direct", [(1, "poison", 0), (2, "direct", None), (3, "none", 0),
+                                                     (4, "none", 2), (5, "poison", 2)])
+def test_random_operation_sequences(seed, flags, small_direct):
+    # small_direct: bulk calls of at most that many chunks skip staging (the library's
+    # size rule, which at this geometry's 12 KiB chunks would otherwise catch every call);
+    # 0 = every call staged, 2 = calls of 1-2 chunks direct and of 3-4 chunks staged
     import torch
     from gpu_util import PagedKV, assert_layers_equal, slots_to_device
     from paper_2510_09665_amd import lmc
@@ -34,6 +38,9 @@ def test_random_operation_sequences(seed, flags):
     ora = oracle.OracleStore(g, n_slots)
     keep = []                                                # device slot mappings stay alive
     with lmc.Context(g, n_slots * g.chunk_bytes, staging_chunks=2, flags=f) as c:
+        if small_direct is not None:
+            c.tune("direct_store_below", small_direct * g.chunk_bytes)
+            c.tune("direct_retrieve_below", small_direct * g.chunk_bytes)
         for step in range(150):
             op = rng.choice(["store", "store_lw", "retrieve", "retrieve_lw", "batch", "lookup", "clear",
                              "pin", "unpin"])

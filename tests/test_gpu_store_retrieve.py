@@ -16,7 +16,7 @@ def _lmc():
 
 
 def _run_sequence(name, geom=None, flags=0, num_staging=2, staging_chunks=1, n_tokens=None,
-                  pool_chunks=None):
+                  pool_chunks=None, tune=()):
     """Store a whole request, retrieve it into fresh blocks, compare pool and pages."""
     import torch
     from gpu_util import PagedKV, assert_layers_equal, slots_to_device
@@ -31,6 +31,8 @@ def _run_sequence(name, geom=None, flags=0, num_staging=2, staging_chunks=1, n_t
     stream = torch.cuda.current_stream()
     with lmc.Context(g, pool_chunks * g.chunk_bytes, num_staging=num_staging,
                      staging_chunks=staging_chunks, flags=flags | lmc.LMC_FLAG_TIMING) as c:
+        for key, value in tune:
+            c.tune(key, value)
         ids = c.hash_chunks(seq["tokens"])
         assert np.array_equal(ids, oracle.hash_chunks(seq["tokens"], g.CT, 0))
         assert c.lookup(ids) == 0
@@ -69,7 +71,60 @@ def _run_sequence(name, geom=None, flags=0, num_staging=2, staging_chunks=1, n_t
 
 
 def test_config1_tiny():
-    _run_sequence("tiny")
+    # half a MiB: by the library's size rule both directions skip staging ...
+    st = _run_sequence("tiny")
+    assert st["gather_launches"] == 1 and st["scatter_launches"] == 1
+    # ... and with the rule switched off the same bytes come through the staging ring
+    _run_sequence("tiny", tune=(("direct_store_below", 0), ("direct_retrieve_below", 0)))
+
+
+def test_small_direct_and_large_staged_calls_interleaved_without_waiting():
+    """Calls below the size threshold skip staging, larger ones use it; they end on
+    different streams.  A retrieve enqueued right behind both kinds of store must see
+    both complete, and a small retrieve must be ordered behind a large store."""
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    lmc = _lmc()
+    g = W.geometry("llama3_8b", L=2, NB=1024)                # 2 MiB chunks
+    rng = np.random.default_rng(11)
+    n_big, n_small = 12, 1
+    n = n_big + n_small
+    blocks = rng.permutation(g.NB)
+    bpc = g.CT // g.BS
+    sb, lb = blocks[:n * bpc], blocks[n * bpc:2 * n * bpc]
+    src = PagedKV(g, sb, rng)
+    toks = W.tokens_for(rng, n * g.CT)
+    s_slots = W.slots_from_blocks(g, sb, n * g.CT)
+    l_slots = W.slots_from_blocks(g, lb, n * g.CT)
+    stream = torch.cuda.current_stream()
+    for rep in range(3):
+        dst = PagedKV(g, lb, fill="sentinel")
+        with lmc.Context(g, n * g.chunk_bytes, staging_chunks=2, flags=lmc.LMC_FLAG_POISON_STAGING) as c:
+            ids = c.hash_chunks(toks)
+            d_s, d_l = slots_to_device(s_slots), slots_to_device(l_slots)
+            cut = n_big * g.CT
+            # 24 MiB through staging (gather stream, then D2H stream) ...
+            c.store(src.dev, d_s[:cut], ids[:n_big], stream)
+            # ... and 2 MiB written by the gather kernel itself, which finishes first
+            c.store(src.dev, d_s[cut:], ids[n_big:], stream)
+            st = c.get_stats()
+            assert st["gather_launches"] == 1 + 6 + 1 and st["bytes_d2h"] == n * g.chunk_bytes
+            if rep == 0:
+                t = c.retrieve(ids, d_l, dst.dev, stream)            # staged; needs both stores
+            elif rep == 1:
+                c.retrieve(ids[n_big:], d_l[cut:], dst.dev, stream)  # direct; behind the direct store
+                t = c.retrieve(ids[:n_big], d_l[:cut], dst.dev, stream)
+            else:
+                c.retrieve(ids[:1], d_l[:g.CT], dst.dev, stream)     # direct; behind the staged store
+                t = c.retrieve(ids[1:], d_l[g.CT:], dst.dev, stream)
+            c.wait(t)
+            c.wait()
+            torch.cuda.synchronize()
+            chunks = oracle.gather(src.gc, src.host, src.compact_slots(s_slots))
+            oracle.scatter(dst.gc, chunks, dst.compact_slots(l_slots), dst.host)
+            for k, i in enumerate(ids.tolist()):
+                assert np.array_equal(c.get_host(i), chunks[k]), "pool chunk %d" % k
+            assert_layers_equal(dst.device_blocks_to_host(), dst.host, "rep %d" % rep)
 
 
 def test_config2_llama3_8b_full():
@@ -115,6 +170,14 @@ def test_hnd_layout_through_the_pipeline():
     _run_sequence("llama3_8b", g, n_tokens=8 * 256, staging_chunks=3)
 
 
+def test_blocks_outermost_page_order_through_the_pipeline():
+    # [NB][P][BS][H][D]: the K and the V page of a block are neighbours (64 KiB apart per block)
+    g = W.geometry("llama3_8b", L=6, NB=512, order="NP")
+    assert g.plane_stride == 32768 and g.block_stride == 65536
+    _run_sequence("llama3_8b", g, n_tokens=8 * 256, staging_chunks=3)
+    _run_sequence("llama3_8b", g, n_tokens=8 * 256, staging_chunks=1, flags=_lmc().LMC_FLAG_DIRECT)
+
+
 def test_config3_llama3_70b_full_size_sampled_oracle():
     """Full size on the device (40 GiB of pages, 128 chunks = 10 GiB through the pinned
     pool).  The oracle checks sampled chunks byte for byte; the whole result is checked
@@ -140,9 +203,9 @@ def test_config3_llama3_70b_full_size_sampled_oracle():
     gen.manual_seed(W.SEED_BASE + 3)
     others = torch.from_numpy(np.setdiff1d(seq["store_blocks"], sb)).cuda()
     for d in src.dev:
-        v = d.view(g.P, g.NB, g.block_stride)
-        r = (torch.rand((g.P, others.numel(), g.block_stride // 2), device="cuda", generator=gen) * 2 - 1)
-        v[:, others] = r.to(torch.bfloat16).view(torch.uint8).view(g.P, others.numel(), g.block_stride)
+        v = W.page_view(g, d)
+        r = (torch.rand((g.P, others.numel(), g.page_bytes // 2), device="cuda", generator=gen) * 2 - 1)
+        v[:, others] = r.to(torch.bfloat16).view(torch.uint8).view(g.P, others.numel(), g.page_bytes)
     stream = torch.cuda.current_stream()
     with lmc.Context(g, n_chunks * g.chunk_bytes, staging_chunks=2) as c:
         ids = c.hash_chunks(seq["tokens"])
@@ -165,8 +228,8 @@ def test_config3_llama3_70b_full_size_sampled_oracle():
     keep = torch.ones(g.NB, dtype=torch.bool, device="cuda")
     keep[l_all] = False
     for l in range(g.L):
-        sv = src.dev[l].view(g.P, g.NB, g.block_stride)
-        dv = dst.dev[l].view(g.P, g.NB, g.block_stride)
+        sv = W.page_view(g, src.dev[l])
+        dv = W.page_view(g, dst.dev[l])
         assert torch.equal(dv[:, l_all], sv[:, s_all]), "layer %d round trip" % l
         assert bool((dv[:, keep] == sentinel_byte(l)).all()), "layer %d untouched blocks" % l
 
@@ -301,7 +364,8 @@ def test_store_semantics_against_oracle_store():
     ora.close()
 
 
-def test_partial_skip_store_launches_per_run_of_new_chunks():
+@pytest.mark.parametrize("staged", [True, False])
+def test_partial_skip_store_launches_per_run_of_new_chunks(staged):
     """Chunks 0,1 and 4 are present; 2,3 and 5,6,7 are new: launches never span a gap, and
     gather from the right parts of the slot mapping."""
     import torch
@@ -314,6 +378,8 @@ def test_partial_skip_store_launches_per_run_of_new_chunks():
     slots = rng.permutation(g.n_slots)[:8 * g.CT].reshape(8, g.CT)
     other = rng.permutation(g.n_slots)[:8 * g.CT].reshape(8, g.CT)
     with lmc.Context(g, 8 * g.chunk_bytes, staging_chunks=4) as c:
+        if staged:
+            c.tune("direct_store_below", 0)    # 2.5 MiB of new chunks would otherwise skip staging
         ids = c.hash_chunks(toks)
         d_other, d_slots = slots_to_device(other[[0, 1, 4]]), slots_to_device(slots)
         c.store(kv.dev, d_other, ids[[0, 1, 4]], torch.cuda.current_stream())
@@ -323,7 +389,9 @@ def test_partial_skip_store_launches_per_run_of_new_chunks():
         c.wait()
         st = c.get_stats()
         assert st["chunks_stored"] == 5 and st["chunks_skipped_dup"] == 3
-        assert st["gather_launches"] == 3          # [2] (single-chunk head), [3], [5, 6, 7]
+        # staged: [2] (single-chunk head), [3], [5, 6, 7]; direct: [2, 3], [5, 6, 7] (the new
+        # chunks took pool slots 3..7 in order, so each run is also one run of the pool)
+        assert st["gather_launches"] == (3 if staged else 2)
         for k in range(8):
             src_slots = other[k] if k in (0, 1, 4) else slots[k]
             assert np.array_equal(c.get_host(ids[k]), oracle.gather_chunk(g, kv.host, src_slots)), k

@@ -15,6 +15,8 @@ SHAPES = [
     dict(L=3, P=2, H=2, D=8, e=2, BS=4, NB=24, CT=32, block_pad=48),
     dict(L=2, P=1, H=1, D=36, e=1, BS=8, NB=16, CT=32),                     # MLA-like, fp8
     dict(L=2, P=2, H=3, D=5, e=1, BS=4, NB=20, CT=16, layout="HND", block_pad=7),
+    dict(L=2, P=2, H=2, D=8, e=2, BS=4, NB=24, CT=32, order="NP"),           # K and V page of a block adjacent
+    dict(L=2, P=2, H=2, D=6, e=1, BS=4, NB=20, CT=16, order="NP", layout="HND", block_pad=5),
 ]
 
 
@@ -67,14 +69,18 @@ def test_identity_mapping_is_plain_copy():
 
 
 def _as_nd(g, layer):
-    """numpy view [P][NB][BS][H][run] of an unpadded layer, any layout."""
+    """numpy view [P][NB][BS][H][run] of an unpadded layer, any layout and page order."""
     run = g.D * g.e
+    if g.order == "NP":
+        inner = (g.BS, g.H, run) if g.layout == "NHD" else (g.H, g.BS, run)
+        v = layer.reshape((g.NB, g.P) + inner).transpose(1, 0, 2, 3, 4)
+        return v if g.layout == "NHD" else v.transpose(0, 1, 3, 2, 4)
     if g.layout == "NHD":
         return layer.reshape(g.P, g.NB, g.BS, g.H, run)
     return layer.reshape(g.P, g.NB, g.H, g.BS, run).transpose(0, 1, 3, 2, 4)
 
 
-@pytest.mark.parametrize("kw", [SHAPES[0], SHAPES[1], SHAPES[3]])
+@pytest.mark.parametrize("kw", [SHAPES[0], SHAPES[1], SHAPES[3], SHAPES[5]])
 def test_gather_equals_numpy_take(kw):
     g = W.KVGeometry(**kw)
     rng = np.random.default_rng(2)
@@ -86,7 +92,7 @@ def test_gather_equals_numpy_take(kw):
         assert np.array_equal(chunk[l], np.take(nd, slot, axis=1))
 
 
-@pytest.mark.parametrize("kw", [SHAPES[0], SHAPES[1], SHAPES[3]])
+@pytest.mark.parametrize("kw", [SHAPES[0], SHAPES[1], SHAPES[3], SHAPES[5]])
 def test_scatter_equals_numpy_indexed_assignment(kw):
     g = W.KVGeometry(**kw)
     rng = np.random.default_rng(3)
