@@ -215,8 +215,10 @@ FastDiv make_fastdiv(uint32_t d) {
 }
 
 uint32_t max_chunks_per_launch(const KernelGeom &g, const LaunchView &v) {
-    // the workgroup index is 32-bit and must stay below 2^31 for the fast division
-    return uint32_t(0x7FFFFFFFu / (uint64_t(v.by_n_lp.d) * g.by_tiles_per_plane.d));
+    // the workgroup index must stay below 2^31 for the fast division, and a launch's
+    // thread count (workgroups x 256) below 2^32, the stricter of the two: 2^24 - 1
+    // workgroups, 64 GiB at 4 KiB tiles
+    return uint32_t(0x00FFFFFFu / (uint64_t(v.by_n_lp.d) * g.by_tiles_per_plane.d));
 }
 
 LaunchView bulk_view(const KernelGeom &g) {

@@ -19,6 +19,7 @@ CASES = {
     "mla_fp8_k3": ("mla_fp8", {}, 8192, 1, 3, 0),
     "hnd_k2": ("llama3_8b", dict(L=6, NB=512, layout="HND"), 8 * 256, 2, 2, 0),
     "blocks_outer_k2": ("llama3_8b", dict(L=6, NB=512, order="NP"), 8 * 256, 2, 2, "poison"),
+    "max_layers_k7_ragged": ("tiny", dict(L=160, NB=128), 512, 1, 7, 0),    # 160 layers = 22 steps of 7 + one of 6
     "all_layers_in_one_step": ("tiny", {}, 256, 1, 99, 0),
     "direct_llama_k1": ("llama3_8b", dict(L=8, NB=1024), 10 * 256, 1, 1, "direct"),
     "direct_mla_k3": ("mla_bf16", dict(L=7), 4 * 256, 1, 3, "direct"),

@@ -464,8 +464,11 @@ def test_allocation_failures_are_clean_errors():
         lmc.Context(g, 1 << 50)                                   # a petabyte of pinned memory
     assert e.value.status == lmc.LMC_ERR_NOMEM
     with pytest.raises(lmc.LMCError) as e:
-        lmc.Context(g, 2 * g.chunk_bytes, staging_chunks=200000)  # 6 TiB of staging per buffer
+        lmc.Context(g, 2 * g.chunk_bytes, staging_chunks=2000, num_staging=8)   # 16 buffers of 62.5 GiB
     assert e.value.status == lmc.LMC_ERR_NOMEM
+    with pytest.raises(lmc.LMCError) as e:
+        lmc.Context(g, 2 * g.chunk_bytes, staging_chunks=200000)  # more than one launch can cover
+    assert e.value.status == lmc.LMC_ERR_INVAL
     torch.cuda.synchronize()
     assert torch.cuda.mem_get_info()[0] >= free_before - (64 << 20)
     with lmc.Context(g, 2 * g.chunk_bytes) as c:
