@@ -134,7 +134,7 @@ typedef struct {
 } lmc_stats_t;
 
 /* Create a context: allocates the pinned host pool, 2*num_staging device staging
- * buffers of staging_chunks chunks each (one ring per direction), five HIP streams
+ * buffers of staging_chunks chunks each (one ring per direction), six HIP streams
  * and the index.  With device == LMC_DEVICE_NONE nothing touches HIP: the pool is
  * ordinary host memory and only the host-side calls work (hashing, lookup, put/get,
  * pin/unpin/clear, stats); every call that would move data to or from a GPU returns

@@ -79,7 +79,10 @@ struct lmc_ctx {
     lmc::ChunkIndex index;
     std::mutex mu;
     hipStream_t s_gather = nullptr, s_d2h = nullptr, s_h2d = nullptr, s_scatter = nullptr;
-    hipStream_t s_h2d2 = nullptr;  // second copy stream: layer-wise steps alternate between the two
+    // second copy streams: where consecutive transfers cannot be merged into one (layer
+    // steps, scattered pool slots) they alternate between the two streams of their
+    // direction, because back-to-back copies on one stream leave the link idle in between
+    hipStream_t s_h2d2 = nullptr, s_d2h2 = nullptr;
     Ring store_ring, load_ring;
     int32_t *bad_flag_host = nullptr, *bad_flag_dev = nullptr;
     std::deque<Op> ops;
@@ -301,15 +304,23 @@ lmc_status_t force_sync(lmc_ctx *c, hipStream_t s) {
 // Copies `width` bytes per chunk between staging (chunks `stride` bytes apart) and the
 // pool (offset `pool_off` inside each slot), one transfer per run of consecutive pool
 // slots: a plain copy when the extents are back to back on both sides (whole chunks),
-// else a rectangle copy whose rows are the chunks (layer-wise mode).
+// else a rectangle copy whose rows are the chunks (layer-wise mode).  With a second
+// stream the runs go to the two streams in turn; *used_second says whether any did.
 lmc_status_t copy_group(lmc_ctx *c, bool to_host, uint8_t *staging, uint64_t stride,
                         const int64_t *pool_slots, int64_t k, uint64_t pool_off, uint64_t width,
-                        hipStream_t stream) {
+                        hipStream_t first, hipStream_t second = nullptr, bool *used_second = nullptr) {
     const uint64_t cb = uint64_t(c->chunk_bytes);
     const hipMemcpyKind kind = to_host ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice;
-    for (int64_t j = 0; j < k;) {
+    if (used_second) *used_second = false;
+    int64_t run = 0;
+    for (int64_t j = 0; j < k; run++) {
         int64_t m = 1;
         while (j + m < k && pool_slots[j + m] == pool_slots[j] + m) m++;
+        hipStream_t stream = first;
+        if (second != nullptr && (run & 1)) {
+            stream = second;
+            if (used_second) *used_second = true;
+        }
         uint8_t *host = c->pool + uint64_t(pool_slots[j]) * cb + pool_off;
         uint8_t *dev = staging + uint64_t(j) * stride;
         if (m == 1 || (width == cb && stride == cb)) {
@@ -334,6 +345,13 @@ lmc_status_t copy_group(lmc_ctx *c, bool to_host, uint8_t *staging, uint64_t str
         j += m;
     }
     return LMC_OK;
+}
+
+// True if the pool slots are not one run of consecutive numbers (more than one transfer).
+bool several_runs(const int64_t *pool_slots, int64_t k) {
+    for (int64_t j = 1; j < k; j++)
+        if (pool_slots[j] != pool_slots[j - 1] + 1) return true;
+    return false;
 }
 
 lmc_status_t finish_op(lmc_ctx *c, Op &&op, hipStream_t last_stream, bool enqueued,
@@ -462,7 +480,7 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
     const bool direct = (c->cfg.flags & LMC_FLAG_DIRECT) != 0 ||
                         (layers_per_step == 0 && n_chunks * c->chunk_bytes <= c->direct_retrieve_below);
     if ((rc = after_stores(c, pool_slots, direct ? c->s_scatter : c->s_h2d)) != LMC_OK) return rc;
-    if (!direct && layers_per_step > 0 && (rc = after_stores(c, pool_slots, c->s_h2d2)) != LMC_OK) return rc;
+    if (!direct && (rc = after_stores(c, pool_slots, c->s_h2d2)) != LMC_OK) return rc;
     Op op;
     op.ticket = c->next_ticket++;
     op.layerwise = layers_per_step > 0;
@@ -492,13 +510,20 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
     // one group: copies into the next ring buffer on the H2D stream, scatter on the
     // scatter stream; the buffer is released when the scatter has read it
     auto load_group = [&](const lmc::LaunchView &view, uint64_t pool_off, int64_t i0, int64_t k,
-                          hipStream_t copy_stream) -> lmc_status_t {
+                          hipStream_t copy_stream, hipStream_t second) -> lmc_status_t {
         uint8_t *buf;
         const size_t b = ring_next(ring, &buf);
-        if (ring.used[b]) HIPCHK(c, hipStreamWaitEvent(copy_stream, ring.drained[b], 0));
+        if (!several_runs(&pool_slots[size_t(i0)], k)) second = nullptr;
+        if (ring.used[b]) {
+            HIPCHK(c, hipStreamWaitEvent(copy_stream, ring.drained[b], 0));
+            if (second) HIPCHK(c, hipStreamWaitEvent(second, ring.drained[b], 0));
+        }
+        bool used_second = false;
         lmc_status_t r = copy_group(c, false, buf, view.chunk_stride, &pool_slots[size_t(i0)], k,
-                                    pool_off, view.chunk_stride, copy_stream);
+                                    pool_off, view.chunk_stride, copy_stream, second, &used_second);
         if (r != LMC_OK) return r;
+        // the buffer is full when the copies of both streams are in
+        if (used_second && (r = order_after(c, copy_stream, second)) != LMC_OK) return r;
         HIPCHK(c, hipEventRecord(ring.filled[b], copy_stream));
         if ((r = force_sync(c, copy_stream)) != LMC_OK) return r;
         HIPCHK(c, hipStreamWaitEvent(c->s_scatter, ring.filled[b], 0));
@@ -515,14 +540,14 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
         if ((rc = load_direct(lmc::bulk_view(c->kg), 0)) != LMC_OK) return rc;
     } else if (!op.layerwise) {
         const lmc::LaunchView view = lmc::bulk_view(c->kg);
-        if ((rc = ring_reslot(c, ring, ring.buf_bytes, c->s_h2d, c->s_scatter)) != LMC_OK) return rc;
+        if ((rc = ring_reslot(c, ring, ring.buf_bytes, c->s_h2d, c->s_scatter, c->s_h2d2)) != LMC_OK) return rc;
         // The link is the bottleneck and every scatter but the last hides behind the next
         // copy, so the last group is a single chunk: only its scatter is exposed.
         const int64_t edge = std::min<int64_t>(c->edge_chunks, per);
         const int64_t body = (edge > 0 && n_chunks > edge) ? n_chunks - edge : n_chunks;
         for (int64_t i0 = 0, k = 0; i0 < n_chunks; i0 += k) {
             k = i0 < body ? std::min(per, body - i0) : n_chunks - i0;
-            if ((rc = load_group(view, 0, i0, k, c->s_h2d)) != LMC_OK) return rc;
+            if ((rc = load_group(view, 0, i0, k, c->s_h2d, c->s_h2d2)) != LMC_OK) return rc;
         }
     } else {
         // All chunks' share of a few layers at a time: one rectangle copy per run of pool
@@ -545,7 +570,7 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
                 // 20 us per step; with two streams the next step's copy is already running.
                 hipStream_t cs = ((l0 / layers_per_step) & 1) ? c->s_h2d2 : c->s_h2d;
                 for (int64_t i0 = 0; i0 < n_chunks; i0 += cap)
-                    if ((rc = load_group(view, uint64_t(l0) * layer_bytes, i0, std::min(cap, n_chunks - i0), cs)) != LMC_OK)
+                    if ((rc = load_group(view, uint64_t(l0) * layer_bytes, i0, std::min(cap, n_chunks - i0), cs, nullptr)) != LMC_OK)
                         return rc;
             }
             hipEvent_t e;
@@ -574,7 +599,7 @@ void destroy_ctx(lmc_ctx *c) {
         free_ring(c->store_ring);
         free_ring(c->load_ring);
         for (hipEvent_t e : c->all_events) (void)hipEventDestroy(e);
-        for (hipStream_t s : {c->s_gather, c->s_d2h, c->s_h2d, c->s_scatter, c->s_h2d2})
+        for (hipStream_t s : {c->s_gather, c->s_d2h, c->s_h2d, c->s_scatter, c->s_h2d2, c->s_d2h2})
             if (s) (void)hipStreamDestroy(s);
         if (c->bad_flag_host) (void)hipHostFree(c->bad_flag_host);
         if (c->pool) (void)hipHostFree(c->pool);
@@ -649,7 +674,7 @@ lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out) {
         *c->bad_flag_host = 0;
         if (hipHostGetDevicePointer(reinterpret_cast<void **>(&c->bad_flag_dev), c->bad_flag_host, 0) != hipSuccess)
             return fail(LMC_ERR_HIP);
-        for (hipStream_t *s : {&c->s_gather, &c->s_d2h, &c->s_h2d, &c->s_scatter, &c->s_h2d2})
+        for (hipStream_t *s : {&c->s_gather, &c->s_d2h, &c->s_h2d, &c->s_scatter, &c->s_h2d2, &c->s_d2h2})
             if (hipStreamCreateWithFlags(s, hipStreamNonBlocking) != hipSuccess) return fail(LMC_ERR_HIP);
         if ((rc = make_ring(c, c->store_ring)) != LMC_OK) return fail(rc);
         if ((rc = make_ring(c, c->load_ring)) != LMC_OK) return fail(rc);
@@ -772,9 +797,14 @@ static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64
         HIPCHK(c, hipEventRecord(ring.filled[b], c->s_gather));
         if ((rc = force_sync(c, c->s_gather)) != LMC_OK) return rc;
         HIPCHK(c, hipStreamWaitEvent(c->s_d2h, ring.filled[b], 0));
+        hipStream_t second = several_runs(&new_slot[j0], int64_t(k)) ? c->s_d2h2 : nullptr;
+        if (second) HIPCHK(c, hipStreamWaitEvent(second, ring.filled[b], 0));
+        bool used_second = false;
         rc = copy_group(c, true, buf, view.chunk_stride, &new_slot[j0], int64_t(k), pool_off,
-                        view.chunk_stride, c->s_d2h);
+                        view.chunk_stride, c->s_d2h, second, &used_second);
         if (rc != LMC_OK) return rc;
+        // the D2H stream stands for the whole group: it ends after the second stream's copies
+        if (used_second && (rc = order_after(c, c->s_d2h, second)) != LMC_OK) return rc;
         if (c->cfg.flags & LMC_FLAG_POISON_STAGING)
             HIPCHK(c, lmc::launch_fill(buf, 0xA5, uint64_t(k) * view.chunk_stride, c->s_d2h));
         HIPCHK(c, hipEventRecord(ring.drained[b], c->s_d2h));

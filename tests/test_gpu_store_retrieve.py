@@ -178,6 +178,52 @@ def test_blocks_outermost_page_order_through_the_pipeline():
     _run_sequence("llama3_8b", g, n_tokens=8 * 256, staging_chunks=1, flags=_lmc().LMC_FLAG_DIRECT)
 
 
+def test_fragmented_pool_copies_alternate_between_two_streams():
+    """Every other pool slot is taken, so no two new chunks are neighbours in the pool:
+    each group needs one copy per chunk, and those go to two copy streams in turn.  Pool
+    image and pages must equal the oracle's, whose store went through the same history."""
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    lmc = _lmc()
+    name = "llama3_8b"
+    g = W.geometry(name, L=4, NB=1024)                       # 4 MiB chunks
+    n = 13
+    seq = W.sequence(name, g, n_tokens=n * g.CT)
+    rng = W.rng_for(name, stream=7)
+    src = PagedKV(g, seq["store_blocks"], rng)
+    dst = PagedKV(g, seq["load_blocks"], fill="sentinel")
+    stream = torch.cuda.current_stream()
+    n_pool = 2 * n + 2
+    ora = oracle.OracleStore(src.gc, n_pool)
+    filler_ids = np.arange(1, 2 * n + 1, dtype=np.uint64) + np.uint64(1 << 40)
+    filler_slots = np.tile(src.compact_slots(seq["store_slots"][:g.CT]), 2 * n)
+    with lmc.Context(g, n_pool * g.chunk_bytes, staging_chunks=5, num_staging=2,
+                     flags=lmc.LMC_FLAG_POISON_STAGING) as c:
+        # history: 2n filler chunks, then every second one removed, in both stores
+        d_fill = slots_to_device(np.tile(seq["store_slots"][:g.CT], 2 * n))
+        c.wait(c.store(src.dev, d_fill, filler_ids, stream))
+        assert ora.store(src.host, filler_slots, filler_ids) == (0, 2 * n)
+        c.clear(filler_ids[1::2])
+        assert ora.clear(filler_ids[1::2]) == 0
+        ids = c.hash_chunks(seq["tokens"])
+        d_store, d_load = slots_to_device(seq["store_slots"]), slots_to_device(seq["load_slots"])
+        t = c.store(src.dev, d_store, ids, stream)
+        t2 = c.retrieve(ids, d_load, dst.dev, stream)          # behind the store, on the device
+        c.wait(t)
+        c.wait(t2)
+        torch.cuda.synchronize()
+        assert ora.store(src.host, src.compact_slots(seq["store_slots"]), ids) == (0, n)
+        got_slots = [c.find_slot(i) for i in ids.tolist()]
+        assert got_slots == [ora.find(i) for i in ids.tolist()]
+        assert got_slots == list(range(1, 2 * n, 2))           # no two are neighbours
+        for i in ids.tolist() + filler_ids[0::2].tolist():
+            assert np.array_equal(c.get_host(i), ora.slot_bytes(ora.find(i))), "pool chunk"
+        assert ora.retrieve(ids, dst.compact_slots(seq["load_slots"]), dst.host) == 0
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host, "retrieve from a fragmented pool")
+        assert dst.untracked_blocks_untouched()
+    ora.close()
+
+
 def test_config3_llama3_70b_full_size_sampled_oracle():
     """Full size on the device (40 GiB of pages, 128 chunks = 10 GiB through the pinned
     pool).  The oracle checks sampled chunks byte for byte; the whole result is checked
