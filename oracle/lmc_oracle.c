@@ -30,12 +30,17 @@
  *   hash  : FNV-1a 64 over LE64(previous hash) followed by the chunk's CT tokens as
  *           LE32, chained from a seed; only full chunks are hashed
  *   pool  : fixed-size slots of one chunk each, lowest free slot first
+ *   evict : off by default (a full pool refuses new chunks); when switched on, least
+ *           recently used with the tail of a request going before its head (see the
+ *           comment at orc_store_set_evict)
  *
  * Parity pins (tests/test_oracle_*.py): coordinate stamping closed form, identity
  * mapping == memcpy, store/retrieve round trip, untouched-byte sentinel, brute force
  * over every injective mapping on a tiny shape, numpy take / indexed assignment as a
  * library third opinion, published FNV-1a vectors, the prefix property of the chain,
- * and a model check of the store against a dict of bytes.  The paper prints no
+ * a model check of the store against a dict of bytes, and for eviction the textbook
+ * LRU cache (ordered dict) in the one-chunk-per-call case, a hand-worked sequence and
+ * invariants on random sequences.  The paper prints no
  * values for this path, so parity against printed values is unpinned; the pins
  * above fix the definitions taken.
  */
@@ -176,6 +181,15 @@ typedef struct {
     uint8_t *used;      /* per slot: 0 free, 1 holds a chunk */
     uint64_t *key;      /* per slot: the chunk's hash when used */
     int32_t *pins;      /* per slot: pin count */
+    /* optional eviction (off unless orc_store_set_evict): recency of use per slot.
+     * Every store or retrieve call takes the next call number; a chunk it uses gets
+     * (that number, its position in the call's chunk list). */
+    int evict;
+    uint64_t calls;      /* number of the latest store / retrieve call */
+    uint64_t *use_call;  /* per slot: number of the last call that used the chunk */
+    int64_t *use_pos;    /* per slot: first position of the chunk in that call */
+    uint64_t *evicted;   /* hashes evicted since the log was last drained */
+    int64_t n_evicted, cap_evicted;
 } orc_store_t;
 
 orc_store_t *orc_store_new(const orc_geom_t *g, int64_t n_slots)
@@ -189,13 +203,16 @@ orc_store_t *orc_store_new(const orc_geom_t *g, int64_t n_slots)
     s->used = (uint8_t *)calloc((size_t)n_slots, 1);
     s->key = (uint64_t *)calloc((size_t)n_slots, sizeof(uint64_t));
     s->pins = (int32_t *)calloc((size_t)n_slots, sizeof(int32_t));
+    s->use_call = (uint64_t *)calloc((size_t)n_slots, sizeof(uint64_t));
+    s->use_pos = (int64_t *)calloc((size_t)n_slots, sizeof(int64_t));
     return s;
 }
 
 void orc_store_free(orc_store_t *s)
 {
     if (!s) return;
-    free(s->pool); free(s->used); free(s->key); free(s->pins); free(s);
+    free(s->pool); free(s->used); free(s->key); free(s->pins);
+    free(s->use_call); free(s->use_pos); free(s->evicted); free(s);
 }
 
 /* slot holding hash h, or -1 */
@@ -226,51 +243,135 @@ int64_t orc_lookup(const orc_store_t *s, const uint64_t *hashes, int64_t n)
     return k;
 }
 
+/* ---- eviction (the paper says that instances store and evict, sections 4.2 and 7,
+ * but names no policy; the reading taken here is least recently used, refined for
+ * prefix caches) ----
+ *
+ * Recency: a chunk used by call number c at position i of the call's chunk list is
+ * "(c, i)".  Chunk A is older than chunk B if A's call is earlier, or, within one call,
+ * if A's position is LATER: the tail of a request goes before its head, because a
+ * lookup counts only the leading run of present chunks, so a request that lost its
+ * tail still hits on what remains while one that lost its head hits on nothing.
+ * The victim is the oldest chunk that is not pinned and was not used by the call that
+ * needs the room (a call never evicts what it is itself storing or has just found). */
+void orc_store_set_evict(orc_store_t *s, int on) { s->evict = on; }
+
+/* writes up to cap evicted hashes, oldest eviction first, and forgets them */
+int64_t orc_store_drain_evicted(orc_store_t *s, uint64_t *out, int64_t cap)
+{
+    int64_t n = s->n_evicted < cap ? s->n_evicted : cap;
+    for (int64_t i = 0; i < n; i++) out[i] = s->evicted[i];
+    for (int64_t i = n; i < s->n_evicted; i++) s->evicted[i - n] = s->evicted[i];
+    s->n_evicted -= n;
+    return n;
+}
+
+static int64_t pick_victim(const orc_store_t *s)
+{
+    int64_t v = -1;
+    for (int64_t f = 0; f < s->n_slots; f++) {
+        if (!s->used[f] || s->pins[f] > 0 || s->use_call[f] == s->calls) continue;
+        if (v < 0 || s->use_call[f] < s->use_call[v] ||
+            (s->use_call[f] == s->use_call[v] && s->use_pos[f] > s->use_pos[v]))
+            v = f;
+    }
+    return v;
+}
+
+static void evict_slot(orc_store_t *s, int64_t v)
+{
+    if (s->n_evicted == s->cap_evicted) {
+        s->cap_evicted = s->cap_evicted ? 2 * s->cap_evicted : 64;
+        s->evicted = (uint64_t *)realloc(s->evicted, (size_t)s->cap_evicted * sizeof(uint64_t));
+    }
+    s->evicted[s->n_evicted++] = s->key[v];
+    s->used[v] = 0;
+}
+
+/* the chunks of the current call that are present get this call's number ... */
+static void mark_call(orc_store_t *s, const uint64_t *hashes, int64_t n)
+{
+    for (int64_t i = 0; i < n; i++) {
+        int64_t f = orc_store_find(s, hashes[i]);
+        if (f >= 0) s->use_call[f] = s->calls;
+    }
+}
+
+/* ... and, when the call ends, their first position in it */
+static void mark_positions(orc_store_t *s, const uint64_t *hashes, int64_t n)
+{
+    for (int64_t i = n - 1; i >= 0; i--) {
+        int64_t f = orc_store_find(s, hashes[i]);
+        if (f >= 0) s->use_pos[f] = i;
+    }
+}
+
 /* Store chunks in order.  A chunk already present is left as it is (only new tokens
  * are stored, section 4 "Store").  A new chunk takes the lowest free slot.  With no
- * free slot the call stops with ORC_NOMEM and everything stored before stays.
- * n_new_out counts chunks actually written. */
+ * free slot, and with eviction on, the oldest evictable chunk gives up its slot; if
+ * there is none, or eviction is off, the call stops with ORC_NOMEM and everything
+ * stored before stays.  n_new_out counts chunks actually written. */
 int orc_store(orc_store_t *s, const uint8_t *const *layers, const int64_t *slot_mapping,
               const uint64_t *hashes, int64_t n_chunks, int64_t *n_new_out)
 {
     int64_t n_new = 0;
+    int rc = ORC_OK;
     if (n_new_out) *n_new_out = 0;
     if (orc_check_slots(&s->g, slot_mapping, n_chunks * s->g.CT) != ORC_OK) return ORC_BADSLOT;
+    s->calls++;
+    mark_call(s, hashes, n_chunks);   /* what the call finds present is safe from it */
     for (int64_t i = 0; i < n_chunks; i++) {
         if (orc_store_find(s, hashes[i]) >= 0) continue;
         int64_t f = 0;
         while (f < s->n_slots && s->used[f]) f++;
+        if (f == s->n_slots && s->evict) {
+            f = pick_victim(s);
+            if (f >= 0) evict_slot(s, f); else f = s->n_slots;
+        }
         if (f == s->n_slots) {
-            if (n_new_out) *n_new_out = n_new;
-            return ORC_NOMEM;
+            rc = ORC_NOMEM;
+            break;
         }
         orc_gather_chunk(&s->g, layers, slot_mapping + i * s->g.CT, s->pool + f * s->chunk_bytes);
         s->used[f] = 1;
         s->key[f] = hashes[i];
         s->pins[f] = 0;
+        s->use_call[f] = s->calls;
         n_new++;
     }
+    mark_positions(s, hashes, n_chunks);
     if (n_new_out) *n_new_out = n_new;
-    return ORC_OK;
+    return rc;
 }
 
-/* All chunks must be present, else ORC_MISS and no page byte changes. */
-int orc_retrieve(const orc_store_t *s, const uint64_t *hashes, int64_t n_chunks,
+static void scatter_all(const orc_store_t *s, const uint64_t *hashes, int64_t n_chunks,
+                        const int64_t *slot_mapping, uint8_t *const *layers)
+{
+    for (int64_t i = 0; i < n_chunks; i++) {
+        int64_t f = orc_store_find(s, hashes[i]);
+        orc_scatter_chunk(&s->g, s->pool + f * s->chunk_bytes, slot_mapping + i * s->g.CT, layers);
+    }
+}
+
+/* All chunks must be present, else ORC_MISS and no page byte changes (and no chunk
+ * counts as used). */
+int orc_retrieve(orc_store_t *s, const uint64_t *hashes, int64_t n_chunks,
                  const int64_t *slot_mapping, uint8_t *const *layers)
 {
     if (orc_check_slots(&s->g, slot_mapping, n_chunks * s->g.CT) != ORC_OK) return ORC_BADSLOT;
     for (int64_t i = 0; i < n_chunks; i++)
         if (orc_store_find(s, hashes[i]) < 0) return ORC_MISS;
-    for (int64_t i = 0; i < n_chunks; i++) {
-        int64_t f = orc_store_find(s, hashes[i]);
-        orc_scatter_chunk(&s->g, s->pool + f * s->chunk_bytes, slot_mapping + i * s->g.CT, layers);
-    }
+    scatter_all(s, hashes, n_chunks, slot_mapping, layers);
+    s->calls++;
+    mark_call(s, hashes, n_chunks);
+    mark_positions(s, hashes, n_chunks);
     return ORC_OK;
 }
 
 /* Many requests at once: request r owns chunks [off[r], off[r+1]) of hashes and of the
- * slot mapping.  One missing chunk anywhere means nothing is written. */
-int orc_retrieve_batch(const orc_store_t *s, int64_t n_req, const int64_t *req_chunk_offsets,
+ * slot mapping.  One missing chunk anywhere means nothing is written.  For recency the
+ * batch is one call and a chunk's position is its place in the concatenated list. */
+int orc_retrieve_batch(orc_store_t *s, int64_t n_req, const int64_t *req_chunk_offsets,
                        const uint64_t *hashes, const int64_t *slot_mapping,
                        uint8_t *const *layers)
 {
@@ -280,9 +381,11 @@ int orc_retrieve_batch(const orc_store_t *s, int64_t n_req, const int64_t *req_c
         if (orc_store_find(s, hashes[i]) < 0) return ORC_MISS;
     for (int64_t r = 0; r < n_req; r++) {
         int64_t a = req_chunk_offsets[r], b = req_chunk_offsets[r + 1];
-        int rc = orc_retrieve(s, hashes + a, b - a, slot_mapping + a * s->g.CT, layers);
-        if (rc != ORC_OK) return rc;
+        scatter_all(s, hashes + a, b - a, slot_mapping + a * s->g.CT, layers);
     }
+    s->calls++;
+    mark_call(s, hashes, total);
+    mark_positions(s, hashes, total);
     return ORC_OK;
 }
 

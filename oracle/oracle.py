@@ -53,6 +53,8 @@ def _L():
             "orc_hash_chunks": (i64, [u64, i32, vp, i64, vp]),
             "orc_store_new": (vp, [gp, i64]),
             "orc_store_free": (None, [vp]),
+            "orc_store_set_evict": (None, [vp, ctypes.c_int]),
+            "orc_store_drain_evicted": (i64, [vp, vp, i64]),
             "orc_store_find": (i64, [vp, u64]),
             "orc_store_slot_ptr": (vp, [vp, i64]),
             "orc_store_used": (i64, [vp]),
@@ -151,7 +153,7 @@ def hash_chunks(tokens, CT=256, seed=0):
 class OracleStore:
     """The CPU-memory chunk store (pool + index) of lmc_oracle.c."""
 
-    def __init__(self, g, n_slots):
+    def __init__(self, g, n_slots, evict=False):
         self.g = g
         self._cg = _geom(g)
         self.n_slots = n_slots
@@ -159,6 +161,18 @@ class OracleStore:
         self._h = ctypes.c_void_p(_L().orc_store_new(ctypes.byref(self._cg), n_slots))
         if not self._h:
             raise MemoryError
+        if evict:
+            _L().orc_store_set_evict(self._h, 1)
+
+    def drain_evicted(self):
+        """Hashes evicted since the last call, oldest eviction first."""
+        out = np.empty(max(self.n_slots, 1) * 64, dtype=np.uint64)
+        parts = []
+        while True:
+            n = int(_L().orc_store_drain_evicted(self._h, _ptr(out), out.size))
+            parts.append(out[:n].copy())
+            if n < out.size:
+                return np.concatenate(parts)
 
     def close(self):
         if self._h:
