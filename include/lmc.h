@@ -82,6 +82,16 @@ enum {
                                       writes, and the scatter kernel reads, the pinned pool
                                       over the host link.  Same results; the kernels then
                                       occupy compute units for the length of the transfer. */
+#define LMC_FLAG_EVICT_LRU 32u     /* a new chunk that finds the pool full takes the slot of
+                                      the least recently used chunk that is not pinned, has
+                                      no transfer in flight and is not used by the same
+                                      call; within one call's chunks the later position is
+                                      the older one (a request loses its tail first, and
+                                      what is left still hits as a prefix).  Uses are
+                                      lmc_store (new and present chunks), lmc_put_host and
+                                      the retrieve calls; lookup, pin, unpin are not.  The
+                                      paper names no policy (sections 4.2, 7); without the
+                                      flag a full pool gives LMC_ERR_NOMEM. */
 #define LMC_FLAG_TIMING 8u         /* give every gather / scatter launch a start and a stop
                                       HIP event (kernel begin / end on its own stream);
                                       durations appear in lmc_stats_t. */
@@ -126,6 +136,7 @@ typedef struct {
     uint64_t chunks_retrieved;
     uint64_t retrieve_misses;     /* calls refused with LMC_ERR_MISS */
     uint64_t alloc_failures;      /* calls that hit LMC_ERR_NOMEM */
+    uint64_t chunks_evicted;      /* LMC_FLAG_EVICT_LRU: chunks that gave up their slot */
     uint64_t bytes_gathered, bytes_scattered; /* chunk payload through the kernels */
     uint64_t bytes_d2h, bytes_h2d;            /* chunk payload over the host link */
     uint64_t gather_launches, scatter_launches;
@@ -350,6 +361,12 @@ lmc_status_t lmc_window_get(lmc_window_t *w, int64_t *start, int64_t *current, i
 lmc_status_t lmc_pin(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n);
 lmc_status_t lmc_unpin(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n);
 lmc_status_t lmc_clear(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n);
+
+/* LMC_FLAG_EVICT_LRU: the ids evicted since the last call, oldest eviction first, so
+ * that a layer above can report them (batched_evict of section 7, Table 3).  Writes at
+ * most cap ids to ids_out (HOST) and forgets those; *n_out = how many were written.
+ * The log keeps the latest 2^20 evictions. */
+lmc_status_t lmc_drain_evicted(lmc_ctx_t *ctx, uint64_t *ids_out, int64_t cap, int64_t *n_out);
 
 lmc_status_t lmc_get_stats(lmc_ctx_t *ctx, lmc_stats_t *out);
 lmc_status_t lmc_reset_stats(lmc_ctx_t *ctx);

@@ -69,6 +69,8 @@ struct lmc_ctx {
     // Bulk calls that move at most this many bytes skip staging and the copy engine (the
     // kernel itself crosses the link): below a few MiB the copy's launch and the extra
     // event hand-over cost more than the kernel's lower link efficiency.  0 = never.
+    uint64_t use_calls = 0;         // number of the latest call that used chunks (recency of use)
+    std::vector<uint64_t> evicted;  // LMC_FLAG_EVICT_LRU: ids evicted and not yet drained
     int64_t direct_store_below = int64_t(4) << 20;
     int64_t direct_retrieve_below = int64_t(2) << 20;
     int64_t chunk_bytes = 0;
@@ -95,11 +97,15 @@ struct lmc_ctx {
 
 namespace {
 
+// A failed HIP call is reported through the library's own status and
+// lmc_last_hip_error(); the runtime's per-thread "last error" is cleared so that it does
+// not surface in the caller's next, unrelated HIP call.
 #define HIPCHK(ctx, expr)                                  \
     do {                                                   \
         hipError_t e_ = (expr);                            \
         if (e_ != hipSuccess) {                            \
             (ctx)->last_hip_error = int32_t(e_);           \
+            (void)hipGetLastError();                       \
             return LMC_ERR_HIP;                            \
         }                                                  \
     } while (0)
@@ -381,6 +387,7 @@ lmc_status_t make_ring(lmc_ctx *c, Ring &r) {
         hipError_t e = hipMalloc(reinterpret_cast<void **>(&r.buf[i]), r.buf_bytes);
         if (e != hipSuccess) {
             c->last_hip_error = int32_t(e);
+            (void)hipGetLastError();  // the runtime keeps a failure as its "last error": take it back
             return e == hipErrorOutOfMemory ? LMC_ERR_NOMEM : LMC_ERR_HIP;
         }
     }
@@ -426,6 +433,26 @@ size_t ring_next(Ring &r, uint8_t **ptr) {
 int64_t layer_group_chunks(const lmc_ctx *c, const Ring &r, const lmc::LaunchView &view, int64_t n_chunks) {
     const int64_t fit = int64_t(r.buf_bytes / view.chunk_stride);
     return std::max<int64_t>(1, std::min({n_chunks, fit, int64_t(lmc::max_chunks_per_launch(c->kg, view))}));
+}
+
+// Recency of use.  A call that uses chunks takes the next call number and stamps the
+// chunks it finds present (they are then safe from the call's own evictions) ...
+void begin_use(lmc_ctx *c, const uint64_t *ids, int64_t n) {
+    c->use_calls++;
+    for (int64_t i = 0; i < n; i++) {
+        const int64_t s = c->index.find(ids[i]);
+        if (s >= 0) c->index.meta(s).use_call = c->use_calls;
+    }
+}
+
+// ... and when it ends its chunks become the newest, the first of the call the newest of
+// all: within a call the later position is the older one, so a request loses its tail
+// before its head and what is left still hits as a prefix.
+void end_use(lmc_ctx *c, const uint64_t *ids, int64_t n) {
+    for (int64_t i = n - 1; i >= 0; i--) {
+        const int64_t s = c->index.find(ids[i]);
+        if (s >= 0) c->index.touch(s);
+    }
 }
 
 // A chunk whose store is still on its way to the pool must be loaded after that store:
@@ -481,6 +508,8 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
                         (layers_per_step == 0 && n_chunks * c->chunk_bytes <= c->direct_retrieve_below);
     if ((rc = after_stores(c, pool_slots, direct ? c->s_scatter : c->s_h2d)) != LMC_OK) return rc;
     if (!direct && (rc = after_stores(c, pool_slots, c->s_h2d2)) != LMC_OK) return rc;
+    begin_use(c, ids, n_chunks);   // a retrieve that is served is a use of its chunks
+    end_use(c, ids, n_chunks);
     Op op;
     op.ticket = c->next_ticket++;
     op.layerwise = layers_per_step > 0;
@@ -650,6 +679,7 @@ lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out) {
         hipError_t e = hipGetDeviceCount(&n_dev);
         if (e != hipSuccess || cfg->device >= n_dev) {
             c->last_hip_error = int32_t(e);
+            (void)hipGetLastError();  // the runtime keeps a failure as its "last error": take it back
             delete c;
             return e != hipSuccess ? LMC_ERR_HIP : LMC_ERR_INVAL;
         }
@@ -662,6 +692,7 @@ lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out) {
         if (e != hipSuccess) {
             c->pool = nullptr;
             c->last_hip_error = int32_t(e);
+            (void)hipGetLastError();  // the runtime keeps a failure as its "last error": take it back
             return fail(LMC_ERR_NOMEM);
         }
         if (hipHostGetDevicePointer(reinterpret_cast<void **>(&c->pool_dev), c->pool, 0) != hipSuccess)
@@ -726,19 +757,42 @@ lmc_status_t lmc_lookup(lmc_ctx_t *c, const uint64_t *ids, int64_t n, int64_t *n
     return LMC_OK;
 }
 
-// Token processor of a store: which chunks are new, and where they go (lowest free
-// slot).  Stops at the first chunk that finds the pool full.
+// A slot for a new chunk: the lowest free one; with LMC_FLAG_EVICT_LRU and a full pool
+// the least recently used chunk that may go gives up its slot.  -1: no room.
+static int64_t take_slot(lmc_ctx *c, uint64_t id) {
+    int64_t s = c->index.insert(id);
+    if (s < 0 && (c->cfg.flags & LMC_FLAG_EVICT_LRU)) {
+        const int64_t v = c->index.victim(c->use_calls);
+        if (v >= 0) {
+            const uint64_t gone = c->index.meta(v).id;
+            c->index.erase(gone);
+            c->stats.chunks_evicted++;
+            if (c->evicted.size() >= (size_t(1) << 20))
+                c->evicted.erase(c->evicted.begin(), c->evicted.begin() + (size_t(1) << 19));
+            c->evicted.push_back(gone);
+            s = c->index.insert(id);
+        }
+    }
+    if (s < 0) c->stats.alloc_failures++;
+    else c->index.meta(s).use_call = c->use_calls;
+    return s;
+}
+
+// Token processor of a store: which chunks are new, and where they go.  Stops at the
+// first chunk that finds no room.
 static bool admit_new_chunks(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks, Op *op,
                              std::vector<int64_t> *new_chunk) {
+    bool fits = true;
+    begin_use(c, ids, n_chunks);
     for (int64_t i = 0; i < n_chunks; i++) {
         if (c->index.find(ids[i]) >= 0) {
             c->stats.chunks_skipped_dup++;
             continue;
         }
-        const int64_t s = c->index.insert(ids[i]);
+        const int64_t s = take_slot(c, ids[i]);
         if (s < 0) {
-            c->stats.alloc_failures++;
-            return false;
+            fits = false;
+            break;
         }
         lmc::SlotMeta &m = c->index.meta(s);
         m.inflight = 1;
@@ -746,7 +800,8 @@ static bool admit_new_chunks(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks, 
         new_chunk->push_back(i);
         op->slots.push_back(s);
     }
-    return true;
+    end_use(c, ids, n_chunks);
+    return fits;
 }
 
 // Gather + D2H of the new chunks' part described by `view` (all layers, or a few),
@@ -999,6 +1054,7 @@ lmc_status_t lmc_wait(lmc_ctx_t *c, uint64_t ticket) {
         lock.lock();
         if (e != hipSuccess) {
             c->last_hip_error = int32_t(e);
+            (void)hipGetLastError();  // the runtime keeps a failure as its "last error": take it back
             return LMC_ERR_HIP;
         }
     }
@@ -1064,19 +1120,32 @@ lmc_status_t lmc_put_host(lmc_ctx_t *c, const uint64_t *ids, int64_t n, const vo
     DeviceScope dev(c);
     if (c->has_device) reap(c);
     const uint8_t *src = static_cast<const uint8_t *>(host_src);
+    lmc_status_t rc = LMC_OK;
+    begin_use(c, ids, n);
     for (int64_t i = 0; i < n; i++) {
         if (c->index.find(ids[i]) >= 0) {
             c->stats.chunks_skipped_dup++;
             continue;
         }
-        const int64_t s = c->index.insert(ids[i]);
+        const int64_t s = take_slot(c, ids[i]);
         if (s < 0) {
-            c->stats.alloc_failures++;
-            return LMC_ERR_NOMEM;
+            rc = LMC_ERR_NOMEM;
+            break;
         }
         std::memcpy(c->pool + s * c->chunk_bytes, src + i * c->chunk_bytes, size_t(c->chunk_bytes));
         c->stats.chunks_stored++;
     }
+    end_use(c, ids, n);
+    return rc;
+}
+
+lmc_status_t lmc_drain_evicted(lmc_ctx_t *c, uint64_t *ids_out, int64_t cap, int64_t *n_out) {
+    if (!c || cap < 0 || !n_out || (cap > 0 && !ids_out)) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    const size_t n = std::min(c->evicted.size(), size_t(cap));
+    std::copy(c->evicted.begin(), c->evicted.begin() + n, ids_out);
+    c->evicted.erase(c->evicted.begin(), c->evicted.begin() + n);
+    *n_out = int64_t(n);
     return LMC_OK;
 }
 
@@ -1179,6 +1248,7 @@ lmc_status_t lmc_measure_link(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, doubl
     hipError_t e = hipMalloc(reinterpret_cast<void **>(&devbuf), nbytes);
     if (e != hipSuccess) {
         c->last_hip_error = int32_t(e);
+        (void)hipGetLastError();  // the runtime keeps a failure as its "last error": take it back
         return LMC_ERR_NOMEM;
     }
     hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -1199,6 +1269,7 @@ lmc_status_t lmc_measure_link(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, doubl
             for (hipError_t x : {a, b, d, f, g})
                 if (x != hipSuccess) {
                     c->last_hip_error = int32_t(x);
+                    (void)hipGetLastError();  // the runtime keeps a failure as its "last error": take it back
                     rc = LMC_ERR_HIP;
                 }
             if (rc != LMC_OK) break;
@@ -1235,6 +1306,7 @@ lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *c, uint64_t nbytes, int32_t reps
     auto ok = [&](hipError_t e) {
         if (e != hipSuccess && rc == LMC_OK) {
             c->last_hip_error = int32_t(e);
+            (void)hipGetLastError();  // the runtime keeps a failure as its "last error": take it back
             rc = LMC_ERR_HIP;
         }
     };

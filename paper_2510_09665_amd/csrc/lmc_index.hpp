@@ -1,8 +1,9 @@
 // Host-side bookkeeping of the chunk pool: which fixed-size slot of the pinned pool
 // holds which chunk id (the storage manager's "CPU memory addresses of the stored KV
 // cache", paper section 4), a lowest-free-first slot allocator, pin counts
-// (section 7, Table 3) and in-flight counts (the reference counter of section 5.3
-// "Zero-Copy Operations": a slot is not released while a transfer still uses it).
+// (section 7, Table 3), in-flight counts (the reference counter of section 5.3
+// "Zero-Copy Operations": a slot is not released while a transfer still uses it) and
+// the order of last use that optional eviction goes by.
 // Plain C++, no HIP: usable in an index-only context.
 #pragma once
 
@@ -91,6 +92,8 @@ struct SlotMeta {
     int32_t pins = 0;
     int32_t inflight = 0;      // enqueued transfers that read or write this slot
     uint64_t ready_ticket = 0; // the store whose D2H fills this slot (0 = already filled)
+    uint64_t use_call = 0;     // number of the last store / retrieve call that used the chunk
+    int64_t older = -1, newer = -1;  // neighbours in the order of last use
     bool used = false;
 };
 
@@ -105,6 +108,7 @@ public:
         mask_ = cap - 1;
         free_.reset(n_slots);
         used_ = 0;
+        oldest_ = newest_ = -1;
     }
     int64_t n_slots() const { return int64_t(meta_.size()); }
     int64_t used() const { return used_; }
@@ -129,6 +133,7 @@ public:
         while (table_[i] >= 0) i = (i + 1) & mask_;
         table_[i] = s;
         used_++;
+        link_newest(s);
         return s;
     }
     void erase(uint64_t id) {
@@ -150,18 +155,51 @@ public:
             }
         }
         table_[hole] = -1;
+        unlink(slot);
         meta_[size_t(slot)].used = false;
         free_.release(slot);
         used_--;
     }
 
+    // The chunk in `slot` has just been used: it becomes the newest.
+    void touch(int64_t slot) {
+        if (newest_ == slot) return;
+        unlink(slot);
+        link_newest(slot);
+    }
+    // The least recently used chunk that may go: not pinned, no transfer in flight, not
+    // used by call number `call` (a call never evicts what it uses itself); -1 if none.
+    int64_t victim(uint64_t call) const {
+        for (int64_t s = oldest_; s >= 0; s = meta_[size_t(s)].newer) {
+            const SlotMeta &m = meta_[size_t(s)];
+            if (m.pins == 0 && m.inflight == 0 && m.use_call != call) return s;
+        }
+        return -1;
+    }
+    int64_t oldest() const { return oldest_; }
+
 private:
+    void link_newest(int64_t s) {
+        SlotMeta &m = meta_[size_t(s)];
+        m.older = newest_;
+        m.newer = -1;
+        if (newest_ >= 0) meta_[size_t(newest_)].newer = s;
+        newest_ = s;
+        if (oldest_ < 0) oldest_ = s;
+    }
+    void unlink(int64_t s) {
+        SlotMeta &m = meta_[size_t(s)];
+        if (m.older >= 0) meta_[size_t(m.older)].newer = m.newer; else oldest_ = m.newer;
+        if (m.newer >= 0) meta_[size_t(m.newer)].older = m.older; else newest_ = m.older;
+        m.older = m.newer = -1;
+    }
     size_t home(uint64_t id) const { return size_t((id * 0x9E3779B97F4A7C15ull) >> 17) & mask_; }
     std::vector<SlotMeta> meta_;
     std::vector<int64_t> table_;
     size_t mask_ = 0;
     FreeSlots free_;
     int64_t used_ = 0;
+    int64_t oldest_ = -1, newest_ = -1;  // ends of the order of last use
 };
 
 }  // namespace lmc

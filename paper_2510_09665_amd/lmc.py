@@ -20,6 +20,7 @@ LMC_MAX_LAYERS = 160
 LMC_DEVICE_NONE = -1
 LMC_FLAG_VALIDATE_SLOTS, LMC_FLAG_FORCE_SYNC, LMC_FLAG_POISON_STAGING, LMC_FLAG_TIMING = 1, 2, 4, 8
 LMC_FLAG_DIRECT = 16
+LMC_FLAG_EVICT_LRU = 32
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblmc.so")
 
@@ -32,7 +33,7 @@ EXPORTS = [
     "lmc_lookup", "lmc_store", "lmc_retrieve", "lmc_retrieve_batch", "lmc_retrieve_layerwise",
     "lmc_store_begin", "lmc_store_layers", "lmc_wait_layer", "lmc_wait", "lmc_gather",
     "lmc_scatter", "lmc_put_host", "lmc_get_host", "lmc_find_slot", "lmc_pin", "lmc_unpin",
-    "lmc_clear", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_measure_link_duplex",
+    "lmc_clear", "lmc_drain_evicted", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_measure_link_duplex",
     "lmc_copy", "lmc_tune",
     "lmc_strerror", "lmc_last_hip_error",
 ]
@@ -56,7 +57,7 @@ class lmc_config_t(ctypes.Structure):
 class lmc_stats_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint64) for n in
                 ("pool_slots_total", "pool_slots_used", "chunks_stored", "chunks_skipped_dup",
-                 "chunks_retrieved", "retrieve_misses", "alloc_failures", "bytes_gathered",
+                 "chunks_retrieved", "retrieve_misses", "alloc_failures", "chunks_evicted", "bytes_gathered",
                  "bytes_scattered", "bytes_d2h", "bytes_h2d", "gather_launches",
                  "scatter_launches", "timed_gather_launches", "timed_scatter_launches")] + \
                [("gather_ms", ctypes.c_double), ("scatter_ms", ctypes.c_double)]
@@ -127,6 +128,7 @@ def _lib():
             "lmc_pin": (st, [vp, vp, i64]),
             "lmc_unpin": (st, [vp, vp, i64]),
             "lmc_clear": (st, [vp, vp, i64]),
+            "lmc_drain_evicted": (st, [vp, vp, i64, vp]),
             "lmc_get_stats": (st, [vp, ctypes.POINTER(lmc_stats_t)]),
             "lmc_reset_stats": (st, [vp]),
             "lmc_measure_link": (st, [vp, u64, i32, ctypes.POINTER(ctypes.c_double),
@@ -353,6 +355,18 @@ class Context:
     def unpin(self, chunk_ids):
         ids, ip = _host(chunk_ids, np.uint64)
         self._check(_lib().lmc_unpin(self._h, ip, ids.size), "lmc_unpin")
+
+    def drain_evicted(self):
+        """Ids evicted since the last call (LMC_FLAG_EVICT_LRU), oldest eviction first."""
+        out = np.empty(4096, dtype=np.uint64)
+        parts = []
+        while True:
+            n = ctypes.c_int64(0)
+            self._check(_lib().lmc_drain_evicted(self._h, out.ctypes.data, out.size, ctypes.byref(n)),
+                        "lmc_drain_evicted")
+            parts.append(out[:n.value].copy())
+            if n.value < out.size:
+                return np.concatenate(parts)
 
     def clear(self, chunk_ids):
         ids, ip = _host(chunk_ids, np.uint64)

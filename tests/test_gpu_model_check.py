@@ -20,7 +20,8 @@ def _status(fn):
 
 
 @pytest.mark.parametrize("seed,flags,small_direct", [(1, "poison", 0), (2, "direct", None), (3, "none", 0),
-                                                     (4, "none", 2), (5, "poison", 2)])
+                                                     (4, "none", 2), (5, "poison", 2),
+                                                     (6, "evict", 0), (7, "evict", 2)])
 def test_random_operation_sequences(seed, flags, small_direct):
     # small_direct: bulk calls of at most that many chunks skip staging (the library's
     # size rule, which at this geometry's 12 KiB chunks would otherwise catch every call);
@@ -33,9 +34,10 @@ def test_random_operation_sequences(seed, flags, small_direct):
     kv = PagedKV(g, np.arange(g.NB), rng)                    # source pages, all tracked
     dst = PagedKV(g, np.arange(g.NB), fill="sentinel")       # destination pages
     n_slots = 6
-    f = {"poison": lmc.LMC_FLAG_POISON_STAGING, "direct": lmc.LMC_FLAG_DIRECT, "none": 0}[flags]
+    f = {"poison": lmc.LMC_FLAG_POISON_STAGING, "direct": lmc.LMC_FLAG_DIRECT, "none": 0,
+         "evict": lmc.LMC_FLAG_EVICT_LRU | lmc.LMC_FLAG_POISON_STAGING}[flags]
     stream = torch.cuda.current_stream()
-    ora = oracle.OracleStore(g, n_slots)
+    ora = oracle.OracleStore(g, n_slots, evict=flags == "evict")
     keep = []                                                # device slot mappings stay alive
     with lmc.Context(g, n_slots * g.chunk_bytes, staging_chunks=2, flags=f) as c:
         if small_direct is not None:
@@ -98,6 +100,9 @@ def test_random_operation_sequences(seed, flags, small_direct):
                 assert _status(lambda: c.pin(ids)) == ora.pin(ids), step
             else:
                 assert _status(lambda: c.unpin(ids)) == ora.unpin(ids), step
+            # with eviction on: the same victims in the same order (every call above was
+            # waited for, so the library has nothing in flight that it would have to spare)
+            assert c.drain_evicted().tolist() == ora.drain_evicted().tolist(), (step, op)
             for i in range(10):
                 s = ora.find(i)
                 if s < 0:
@@ -109,4 +114,5 @@ def test_random_operation_sequences(seed, flags, small_direct):
                 keep = keep[-4:]
         st = c.get_stats()
         assert st["pool_slots_used"] == ora.used()
+        assert (st["chunks_evicted"] > 5) == (flags == "evict")
     ora.close()

@@ -224,6 +224,50 @@ def test_fragmented_pool_copies_alternate_between_two_streams():
     ora.close()
 
 
+def test_eviction_spares_chunks_with_a_transfer_in_flight():
+    """LMC_FLAG_EVICT_LRU: request A (32 chunks, 512 MiB: some 9 ms on the link) is being
+    retrieved when a store of 10 new chunks needs room in a full pool.  Only request B's
+    8 chunks may go, tail first; A's slots are read by the retrieve and must stay, so the
+    ninth new chunk finds no room.  The retrieve still delivers A's bytes."""
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    lmc = _lmc()
+    name = "llama3_8b"
+    g = W.geometry(name, L=16, NB=2048)                      # 16 MiB chunks
+    nA, nB, nC = 32, 8, 10
+    seq = W.sequence(name, g, n_tokens=(nA + nB + nC) * g.CT)
+    rng = W.rng_for(name, stream=9)
+    src = PagedKV(g, seq["store_blocks"], rng)
+    dst = PagedKV(g, seq["load_blocks"][:nA * g.CT // g.BS], fill="sentinel")
+    stream = torch.cuda.current_stream()
+    CT = g.CT
+    with lmc.Context(g, (nA + nB) * g.chunk_bytes, staging_chunks=4, flags=lmc.LMC_FLAG_EVICT_LRU) as c:
+        ids = c.hash_chunks(seq["tokens"])
+        idA, idB, idC = ids[:nA], ids[nA:nA + nB], ids[nA + nB:]
+        d_store = slots_to_device(seq["store_slots"])
+        d_load = slots_to_device(seq["load_slots"][:nA * CT])
+        c.wait(c.store(src.dev, d_store[:nA * CT], idA, stream))
+        c.wait(c.store(src.dev, d_store[nA * CT:(nA + nB) * CT], idB, stream))
+        assert c.get_stats()["pool_slots_used"] == nA + nB
+        t = c.retrieve(idA, d_load, dst.dev, stream)
+        with pytest.raises(lmc.LMCError) as e:
+            c.store(src.dev, d_store[(nA + nB) * CT:], idC, stream)
+        if c.test(t):
+            pytest.skip("the retrieve had finished before the store was admitted")
+        assert e.value.status == lmc.LMC_ERR_NOMEM
+        assert c.drain_evicted().tolist() == idB[::-1].tolist()       # B's tail first
+        assert c.lookup(idA) == nA and c.lookup(idC) == nB and c.lookup(idB) == 0
+        c.wait()
+        torch.cuda.synchronize()
+        chunks = oracle.gather(src.gc, src.host, src.compact_slots(seq["store_slots"]))
+        oracle.scatter(dst.gc, chunks[:nA], dst.compact_slots(seq["load_slots"][:nA * CT]), dst.host)
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host, "retrieve that was in flight")
+        for k in list(range(nA)) + list(range(nA + nB, nA + 2 * nB)):
+            assert np.array_equal(c.get_host(ids[k]), chunks[k]), k
+        st = c.get_stats()
+        assert st["chunks_evicted"] == nB and st["pool_slots_used"] == nA + nB
+
+
 def test_config3_llama3_70b_full_size_sampled_oracle():
     """Full size on the device (40 GiB of pages, 128 chunks = 10 GiB through the pinned
     pool).  The oracle checks sampled chunks byte for byte; the whole result is checked
@@ -515,6 +559,8 @@ def test_allocation_failures_are_clean_errors():
     with pytest.raises(lmc.LMCError) as e:
         lmc.Context(g, 2 * g.chunk_bytes, staging_chunks=200000)  # more than one launch can cover
     assert e.value.status == lmc.LMC_ERR_INVAL
+    # the failures stay inside the library: the caller's next HIP work sees no stale error
+    assert float((torch.full((1024,), 2.0, device="cuda") * 2).sum()) == 4096.0
     torch.cuda.synchronize()
     assert torch.cuda.mem_get_info()[0] >= free_before - (64 << 20)
     with lmc.Context(g, 2 * g.chunk_bytes) as c:

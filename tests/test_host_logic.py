@@ -28,7 +28,7 @@ def test_struct_sizes_match_the_header_layout():
     import ctypes
     assert ctypes.sizeof(lmc.lmc_kv_geom_t) == 8 * 4 + 4 * 8
     assert ctypes.sizeof(lmc.lmc_config_t) == 64 + 8 + 4 * 4 + 8
-    assert ctypes.sizeof(lmc.lmc_stats_t) == 17 * 8
+    assert ctypes.sizeof(lmc.lmc_stats_t) == 18 * 8
 
 
 def _ctx(g, n_slots, **kw):
@@ -114,23 +114,29 @@ def _status(fn):
         return e.status
 
 
-def test_index_and_pool_model_check_against_oracle_store():
+@pytest.mark.parametrize("evict", [False, True])
+def test_index_and_pool_model_check_against_oracle_store(evict):
     """Random put / lookup / get / pin / unpin / clear sequences: statuses, slot numbers
-    (lowest free first) and pool bytes must equal the oracle's chunk store."""
+    (lowest free first), pool bytes and, with eviction on, the evicted ids in order must
+    equal the oracle's chunk store."""
     g = W.KVGeometry(L=2, P=2, H=2, D=4, e=2, BS=4, NB=32, CT=16)
     rng = np.random.default_rng(99)
     layers = W.random_layers(rng, g)
     n_slots = 6
-    ora = oracle.OracleStore(g, n_slots)
-    with _ctx(g, n_slots) as c:
+    ora = oracle.OracleStore(g, n_slots, evict=evict)
+    n_evicted = 0
+    with _ctx(g, n_slots, flags=lmc.LMC_FLAG_EVICT_LRU if evict else 0) as c:
         for step in range(600):
-            op = rng.choice(["put", "lookup", "pin", "unpin", "clear", "get"])
+            op = rng.choice(["put", "put", "lookup", "pin", "unpin", "clear", "get"])
             ids = rng.integers(0, 12, rng.integers(1, 5)).astype(np.uint64)
             if op == "put":
                 slots = rng.permutation(g.n_slots)[:ids.size * g.CT].reshape(ids.size, g.CT)
                 chunks = oracle.gather(g, layers, slots)          # the bytes both sides receive
                 want_rc, _ = ora.store(layers, slots, ids)
                 assert _status(lambda: c.put_host(ids, chunks)) == want_rc, step
+                gone = ora.drain_evicted()
+                assert c.drain_evicted().tolist() == gone.tolist(), step
+                n_evicted += gone.size
             elif op == "lookup":
                 assert c.lookup(ids) == ora.lookup(ids)
             elif op == "pin":
@@ -153,6 +159,8 @@ def test_index_and_pool_model_check_against_oracle_store():
                 assert got == want, (step, i)
             st = c.get_stats()
             assert st["pool_slots_used"] == ora.used() and st["pool_slots_total"] == n_slots
+            assert st["chunks_evicted"] == n_evicted
+    assert (n_evicted > 100) == evict
 
 
 def test_index_survives_many_inserts_and_erases():
