@@ -1,9 +1,12 @@
 // Host-only driver for csrc/lmc_index.hpp, built with -fsanitize=address,undefined by
 // tests/test_host_sanitizers.py: random insert / find / erase sequences on ChunkIndex
-// against std::map, lowest-free-first against a std::set, and the chained chunk id
-// against a byte-wise reference.  Prints "ok" and exits 0 when everything agrees.
+// against std::map, lowest-free-first against a std::set, the order of last use and
+// the choice of a victim against a std::list, and the chained chunk id against a
+// byte-wise reference.  Prints "ok" and exits 0 when everything agrees.
 #include <cstdio>
+#include <algorithm>
 #include <cstdlib>
+#include <list>
 #include <map>
 #include <random>
 #include <set>
@@ -58,6 +61,55 @@ int main() {
             CHECK(idx.used() == int64_t(model.size()));
         }
         for (auto &kv : model) CHECK(idx.find(kv.first) == kv.second);
+    }
+    // order of last use: insert and touch put a chunk at the newest end, erase removes
+    // it; the victim is the oldest that is not pinned, not in flight, not of the call
+    for (int64_t n_slots : {1, 3, 64, 500}) {
+        lmc::ChunkIndex idx;
+        idx.reset(n_slots);
+        std::list<uint64_t> order;                       // oldest first
+        for (int s = 0; s < 40000; s++) {
+            uint64_t id = rng() % uint64_t(n_slots * 2 + 1);
+            int op = int(rng() % 6);
+            int64_t slot = idx.find(id);
+            if (op == 0 && slot < 0) {
+                if (idx.insert(id) >= 0) order.push_back(id);
+            } else if (op == 1 && slot >= 0) {
+                idx.erase(id);
+                order.remove(id);
+            } else if (op == 2 && slot >= 0) {
+                idx.touch(slot);
+                order.remove(id);
+                order.push_back(id);
+            } else if (op == 3 && slot >= 0) {
+                idx.meta(slot).pins = int32_t(rng() % 2);
+                idx.meta(slot).inflight = int32_t(rng() % 2);
+                idx.meta(slot).use_call = rng() % 3;
+            } else if (op >= 4) {
+                const uint64_t call = rng() % 3;
+                uint64_t want = ~0ull;
+                for (uint64_t o : order) {
+                    const lmc::SlotMeta &m = idx.meta(idx.find(o));
+                    if (m.pins == 0 && m.inflight == 0 && m.use_call != call) {
+                        want = o;
+                        break;
+                    }
+                }
+                const int64_t v = idx.victim(call);
+                CHECK((v < 0) == (want == ~0ull));
+                if (v >= 0) CHECK(idx.meta(v).id == want);
+            }
+            CHECK(idx.used() == int64_t(order.size()));
+            CHECK((idx.oldest() < 0) == order.empty());
+            if (!order.empty()) CHECK(idx.meta(idx.oldest()).id == order.front());
+        }
+        // walk the whole list once: same ids in the same order
+        int64_t sl = idx.oldest();
+        for (uint64_t o : order) {
+            CHECK(sl >= 0 && idx.meta(sl).id == o);
+            sl = idx.meta(sl).newer;
+        }
+        CHECK(sl == -1);
     }
     // chained id == FNV-1a over the concatenated little-endian message
     std::vector<int32_t> tok(300);
