@@ -181,6 +181,7 @@ typedef struct {
     uint8_t *used;      /* per slot: 0 free, 1 holds a chunk */
     uint64_t *key;      /* per slot: the chunk's hash when used */
     int32_t *pins;      /* per slot: pin count */
+    int32_t *refs;      /* per slot: transfers that are reading the chunk's bytes in place */
     /* optional eviction (off unless orc_store_set_evict): recency of use per slot.
      * Every store or retrieve call takes the next call number; a chunk it uses gets
      * (that number, its position in the call's chunk list). */
@@ -203,6 +204,7 @@ orc_store_t *orc_store_new(const orc_geom_t *g, int64_t n_slots)
     s->used = (uint8_t *)calloc((size_t)n_slots, 1);
     s->key = (uint64_t *)calloc((size_t)n_slots, sizeof(uint64_t));
     s->pins = (int32_t *)calloc((size_t)n_slots, sizeof(int32_t));
+    s->refs = (int32_t *)calloc((size_t)n_slots, sizeof(int32_t));
     s->use_call = (uint64_t *)calloc((size_t)n_slots, sizeof(uint64_t));
     s->use_pos = (int64_t *)calloc((size_t)n_slots, sizeof(int64_t));
     return s;
@@ -211,7 +213,7 @@ orc_store_t *orc_store_new(const orc_geom_t *g, int64_t n_slots)
 void orc_store_free(orc_store_t *s)
 {
     if (!s) return;
-    free(s->pool); free(s->used); free(s->key); free(s->pins);
+    free(s->pool); free(s->used); free(s->key); free(s->pins); free(s->refs);
     free(s->use_call); free(s->use_pos); free(s->evicted); free(s);
 }
 
@@ -270,7 +272,7 @@ static int64_t pick_victim(const orc_store_t *s)
 {
     int64_t v = -1;
     for (int64_t f = 0; f < s->n_slots; f++) {
-        if (!s->used[f] || s->pins[f] > 0 || s->use_call[f] == s->calls) continue;
+        if (!s->used[f] || s->pins[f] > 0 || s->refs[f] > 0 || s->use_call[f] == s->calls) continue;
         if (v < 0 || s->use_call[f] < s->use_call[v] ||
             (s->use_call[f] == s->use_call[v] && s->use_pos[f] > s->use_pos[v]))
             v = f;
@@ -336,6 +338,7 @@ int orc_store(orc_store_t *s, const uint8_t *const *layers, const int64_t *slot_
         s->used[f] = 1;
         s->key[f] = hashes[i];
         s->pins[f] = 0;
+        s->refs[f] = 0;
         s->use_call[f] = s->calls;
         n_new++;
     }
@@ -421,11 +424,42 @@ int orc_clear(orc_store_t *s, const uint64_t *hashes, int64_t n)
 {
     for (int64_t i = 0; i < n; i++) {
         int64_t f = orc_store_find(s, hashes[i]);
-        if (f >= 0 && s->pins[f] > 0) return ORC_BUSY;
+        if (f >= 0 && (s->pins[f] > 0 || s->refs[f] > 0)) return ORC_BUSY;
     }
     for (int64_t i = 0; i < n; i++) {
         int64_t f = orc_store_find(s, hashes[i]);
         if (f >= 0) s->used[f] = 0;
     }
     return ORC_OK;
+}
+
+/* The reference counter of section 5.3 "Zero-Copy Operations": a transfer that sends a
+ * chunk somewhere else (a write to disk, to a remote store, ...) does not copy it first;
+ * it raises the chunk's counter, reads the bytes where they are, and lowers the counter
+ * when it completes.  Several transfers of the same chunk at once, e.g. to two
+ * destinations, each hold their own count.  While the counter is above zero the chunk
+ * keeps its slot: clear answers ORC_BUSY (above) and eviction passes it over.
+ * acquire: ORC_MISS if the chunk is absent.  release: ORC_MISS if absent, ORC_INVAL if
+ * the counter is already zero. */
+int orc_acquire(orc_store_t *s, uint64_t h)
+{
+    int64_t f = orc_store_find(s, h);
+    if (f < 0) return ORC_MISS;
+    s->refs[f]++;
+    return ORC_OK;
+}
+
+int orc_release(orc_store_t *s, uint64_t h)
+{
+    int64_t f = orc_store_find(s, h);
+    if (f < 0) return ORC_MISS;
+    if (s->refs[f] == 0) return ORC_INVAL;
+    s->refs[f]--;
+    return ORC_OK;
+}
+
+int32_t orc_refs(const orc_store_t *s, uint64_t h)
+{
+    int64_t f = orc_store_find(s, h);
+    return f < 0 ? -1 : s->refs[f];
 }

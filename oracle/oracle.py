@@ -65,6 +65,9 @@ def _L():
             "orc_pin": (ctypes.c_int, [vp, vp, i64]),
             "orc_unpin": (ctypes.c_int, [vp, vp, i64]),
             "orc_clear": (ctypes.c_int, [vp, vp, i64]),
+            "orc_acquire": (ctypes.c_int, [vp, u64]),
+            "orc_release": (ctypes.c_int, [vp, u64]),
+            "orc_refs": (i32, [vp, u64]),
         }
         for name, (res, args) in sigs.items():
             f = getattr(lib, name)
@@ -228,3 +231,12 @@ class OracleStore:
     def clear(self, hashes):
         hashes = _u64(hashes)
         return _L().orc_clear(self._h, _ptr(hashes), hashes.size)
+
+    def acquire(self, h):
+        return _L().orc_acquire(self._h, int(h))
+
+    def release(self, h):
+        return _L().orc_release(self._h, int(h))
+
+    def refs(self, h):
+        return int(_L().orc_refs(self._h, int(h)))

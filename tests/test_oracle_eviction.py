@@ -120,6 +120,36 @@ def test_a_chunk_listed_twice_in_a_call_counts_at_its_first_position():
     s.close()
 
 
+def test_reference_counter_two_destinations_hold_the_chunk_until_both_are_done():
+    """Section 5.3, zero-copy operations, written out: a chunk on its way to two
+    destinations carries two counts; each completion takes one off; only at zero may the
+    chunk go (by clear or by eviction)."""
+    rng = np.random.default_rng(5)
+    layers = _layers(rng)
+    s = oracle.OracleStore(G, 2, evict=True)
+    assert s.store(layers, _slots(rng, 2), u64(1, 2)) == (0, 2)
+    assert s.acquire(9) == -3 and s.release(1) == -1            # absent; nothing to release
+    assert s.acquire(1) == 0 and s.acquire(1) == 0              # disk and remote store
+    assert s.refs(1) == 2
+    assert s.clear(u64(1)) == -6
+    # a new chunk needs room: 2 is the tail and goes first anyway; the next one would take
+    # 1 (oldest) but cannot, and nothing else may go (3 belongs to the call): no room
+    assert s.store(layers, _slots(rng, 2), u64(3, 4)) == (-2, 1)
+    assert s.drain_evicted().tolist() == [2]
+    assert s.release(1) == 0                                    # first destination done
+    assert s.refs(1) == 1 and s.clear(u64(1)) == -6
+    assert s.store(layers, _slots(rng, 1), u64(4)) == (0, 1)    # 3 is from an older call now: it goes
+    assert s.drain_evicted().tolist() == [3]
+    assert s.pin(u64(4)) == 0
+    assert s.store(layers, _slots(rng, 1), u64(5)) == (-2, 0)   # 4 pinned, 1 still counted: no room
+    assert s.release(1) == 0                                    # second destination done
+    assert s.refs(1) == 0 and s.release(1) == -1
+    assert s.store(layers, _slots(rng, 1), u64(5)) == (0, 1)    # now 1 can be evicted
+    assert s.drain_evicted().tolist() == [1]
+    assert s.refs(1) == -1 and s.unpin(u64(4)) == 0 and s.clear(u64(4, 5)) == 0 and s.used() == 0
+    s.close()
+
+
 def test_eviction_off_is_the_old_behaviour():
     rng = np.random.default_rng(3)
     layers = _layers(rng)
@@ -139,10 +169,10 @@ def test_invariants_on_random_multi_chunk_sequences(seed):
     layers = _layers(rng)
     cap = 7
     s = oracle.OracleStore(G, cap, evict=True)
-    content, pinned = {}, {}
+    content, pinned, held = {}, {}, {}
     dst = [np.zeros(G.layer_bytes, dtype=np.uint8)]
     for step in range(400):
-        op = rng.choice(["store", "store", "retrieve", "pin", "unpin", "clear"])
+        op = rng.choice(["store", "store", "retrieve", "pin", "unpin", "clear", "acquire", "release"])
         ids = rng.integers(0, 20, rng.integers(1, 5))
         hs = u64(*ids.tolist())
         if op == "store":
@@ -153,7 +183,7 @@ def test_invariants_on_random_multi_chunk_sequences(seed):
             assert len(set(ev)) == len(ev)
             for h in ev:
                 assert s.find(h) < 0 or h in ids.tolist()     # gone (unless stored again later in the call)
-                assert pinned.get(h, 0) == 0, (step, h)
+                assert pinned.get(h, 0) == 0 and held.get(h, 0) == 0, (step, h)
                 assert h not in present_before, (step, h)     # the call protects what it found
                 content.pop(h, None)
             stored = 0
@@ -167,7 +197,7 @@ def test_invariants_on_random_multi_chunk_sequences(seed):
             if rc == -2:
                 # only a call that really cannot fit fails
                 assert s.used() == cap
-                assert all(pinned.get(h, 0) > 0 or h in ids.tolist() for h in content)
+                assert all(pinned.get(h, 0) > 0 or held.get(h, 0) > 0 or h in ids.tolist() for h in content)
             else:
                 assert rc == 0 and all(s.find(int(h)) >= 0 for h in ids)
             assert evictable >= 0 and n_unique_new >= n_new
@@ -182,8 +212,21 @@ def test_invariants_on_random_multi_chunk_sequences(seed):
             if s.unpin(hs) == 0:
                 for h in ids.tolist():
                     pinned[h] -= 1
+        elif op == "acquire":
+            h = int(ids[0])
+            assert s.acquire(h) == (0 if h in content else -3)
+            if h in content:
+                held[h] = held.get(h, 0) + 1
+        elif op == "release":
+            h = int(ids[0])
+            want = -3 if h not in content else (0 if held.get(h, 0) > 0 else -1)
+            assert s.release(h) == want
+            if want == 0:
+                held[h] -= 1
         else:
-            if s.clear(hs) == 0:
+            busy = any(h in content and (pinned.get(h, 0) > 0 or held.get(h, 0) > 0) for h in ids.tolist())
+            assert s.clear(hs) == (-6 if busy else 0)
+            if not busy:
                 for h in ids.tolist():
                     content.pop(h, None)
         assert s.used() == len(content) <= cap
