@@ -62,7 +62,8 @@ enum {
     LMC_ERR_BADSLOT = -4,  /* a slot >= num_blocks*block_size */
     LMC_ERR_HIP = -5,      /* a HIP call failed; lmc_last_hip_error() has its code */
     LMC_ERR_BUSY = -6,     /* chunk pinned or in flight */
-    LMC_ERR_NODEVICE = -7  /* data-movement call on an index-only context */
+    LMC_ERR_NODEVICE = -7, /* data-movement call on an index-only context */
+    LMC_ERR_IO = -8        /* a file of a lower tier could not be written or read */
 };
 
 #define LMC_MAX_LAYERS 160        /* kv_layers travels as a kernel argument */
@@ -361,6 +362,51 @@ lmc_status_t lmc_window_get(lmc_window_t *w, int64_t *start, int64_t *current, i
 lmc_status_t lmc_pin(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n);
 lmc_status_t lmc_unpin(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n);
 lmc_status_t lmc_clear(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n);
+
+/* The reference counter of section 5.3 "Zero-Copy Operations": a reader that sends a
+ * stored chunk somewhere else (a lower tier, a peer) does not copy it first.
+ * lmc_chunk_acquire waits until the chunk's bytes are in the pool (LMC_ERR_BUSY if they
+ * belong to a layer-wise store that has not been submitted completely, LMC_ERR_MISS if
+ * the chunk is absent), raises the chunk's counter and returns the address of its
+ * chunk_bytes bytes in the pinned pool (HOST, read-only, valid until the matching
+ * release).  While the counter is above zero the chunk keeps its slot: lmc_clear
+ * answers LMC_ERR_BUSY and eviction passes it over.  Several readers each hold their own
+ * count.  lmc_chunk_release lowers it: LMC_ERR_MISS if absent, LMC_ERR_INVAL if zero. */
+lmc_status_t lmc_chunk_acquire(lmc_ctx_t *ctx, uint64_t chunk_id, const void **host_ptr_out);
+lmc_status_t lmc_chunk_release(lmc_ctx_t *ctx, uint64_t chunk_id);
+
+/* A lower tier made of directories, one file per chunk ("local disk and remote object
+ * storage" of section 5.3 stand behind mount points here).  lmc_tier_write sends each
+ * chunk to EVERY directory at once: one count on the chunk per destination
+ * (lmc_chunk_acquire), no copy of the data, writer threads that read the pinned pool in
+ * place, one release per finished file.  It returns as soon as the work is queued;
+ * all-or-nothing: if one id is absent (LMC_ERR_MISS) or not yet complete
+ * (LMC_ERR_BUSY) nothing is queued.  A file appears under its final name
+ * (<dir>/<16 hex digits of the id>.kv) only when it is complete.
+ * lmc_tier_wait blocks until everything queued has been written and returns LMC_ERR_IO
+ * if a file failed since the last wait (errno through lmc_tier_errno); the chunks'
+ * counts are given back either way.
+ * lmc_tier_lookup: the number of leading ids whose file exists in directory dir.
+ * lmc_tier_read brings chunks back from directory dir into the pool: ids already
+ * present are skipped, new ones are admitted like lmc_put_host (LMC_ERR_NOMEM when the
+ * pool is full and nothing can be evicted; LMC_ERR_MISS if a file is absent,
+ * LMC_ERR_IO if it is short or unreadable); ids before the failing one stay.  This
+ * direction goes through one bounce buffer.
+ * Close the tier (waits for queued writes) before destroying the context.  Calls on
+ * one tier may come from several threads.  dirs: HOST strings, copied. */
+typedef struct lmc_tier lmc_tier_t;
+lmc_status_t lmc_tier_open(lmc_ctx_t *ctx, const char *const *dirs, int32_t n_dirs,
+                           int32_t n_threads, lmc_tier_t **tier_out);
+lmc_status_t lmc_tier_close(lmc_tier_t *tier);
+lmc_status_t lmc_tier_write(lmc_tier_t *tier, const uint64_t *chunk_ids, int64_t n);
+lmc_status_t lmc_tier_wait(lmc_tier_t *tier);
+lmc_status_t lmc_tier_lookup(lmc_tier_t *tier, int32_t dir, const uint64_t *chunk_ids, int64_t n,
+                             int64_t *n_hit_out);
+lmc_status_t lmc_tier_read(lmc_tier_t *tier, int32_t dir, const uint64_t *chunk_ids, int64_t n);
+int32_t lmc_tier_errno(const lmc_tier_t *tier);
+/* files written / bytes written / chunks read back since the tier was opened */
+lmc_status_t lmc_tier_get_stats(lmc_tier_t *tier, uint64_t *files_written, uint64_t *bytes_written,
+                                uint64_t *chunks_read);
 
 /* LMC_FLAG_EVICT_LRU: the ids evicted since the last call, oldest eviction first, so
  * that a layer above can report them (batched_evict of section 7, Table 3).  Writes at

@@ -1166,6 +1166,35 @@ lmc_status_t lmc_get_host(lmc_ctx_t *c, uint64_t id, void *host_dst) {
     return LMC_OK;
 }
 
+lmc_status_t lmc_chunk_acquire(lmc_ctx_t *c, uint64_t id, const void **host_ptr_out) {
+    if (!c || !host_ptr_out) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    if (c->has_device) reap(c);
+    const int64_t s = c->index.find(id);
+    if (s < 0) return LMC_ERR_MISS;
+    // the bytes must have arrived: wait for the store that fills the slot
+    const uint64_t store_ticket = c->index.meta(s).ready_ticket;
+    if (store_ticket != 0) {
+        const Op *o = find_op(c, store_ticket);
+        if (o != nullptr && o->pending) return LMC_ERR_BUSY;
+        if (o != nullptr && o->done != nullptr) HIPCHK(c, hipEventSynchronize(o->done));
+    }
+    c->index.meta(s).refs++;
+    *host_ptr_out = c->pool + s * c->chunk_bytes;
+    return LMC_OK;
+}
+
+lmc_status_t lmc_chunk_release(lmc_ctx_t *c, uint64_t id) {
+    if (!c) return LMC_ERR_INVAL;
+    std::lock_guard<std::mutex> lock(c->mu);
+    const int64_t s = c->index.find(id);
+    if (s < 0) return LMC_ERR_MISS;
+    if (c->index.meta(s).refs == 0) return LMC_ERR_INVAL;
+    c->index.meta(s).refs--;
+    return LMC_OK;
+}
+
 lmc_status_t lmc_find_slot(lmc_ctx_t *c, uint64_t id, int64_t *slot_out) {
     if (!c || !slot_out) return LMC_ERR_INVAL;
     std::lock_guard<std::mutex> lock(c->mu);
@@ -1208,7 +1237,9 @@ lmc_status_t lmc_clear(lmc_ctx_t *c, const uint64_t *ids, int64_t n) {
     if (c->has_device) reap(c);
     for (int64_t i = 0; i < n; i++) {
         const int64_t s = c->index.find(ids[i]);
-        if (s >= 0 && (c->index.meta(s).pins > 0 || c->index.meta(s).inflight > 0)) return LMC_ERR_BUSY;
+        if (s < 0) continue;
+        const lmc::SlotMeta &m = c->index.meta(s);
+        if (m.pins > 0 || m.inflight > 0 || m.refs > 0) return LMC_ERR_BUSY;
     }
     for (int64_t i = 0; i < n; i++) c->index.erase(ids[i]);
     return LMC_OK;
@@ -1379,6 +1410,7 @@ const char *lmc_strerror(lmc_status_t s) {
         case LMC_ERR_BADSLOT: return "slot outside the paged KV memory";
         case LMC_ERR_HIP: return "HIP call failed";
         case LMC_ERR_BUSY: return "chunk pinned or in flight";
+        case LMC_ERR_IO: return "file input / output failed";
         case LMC_ERR_NODEVICE: return "context has no device";
     }
     return "unknown status";

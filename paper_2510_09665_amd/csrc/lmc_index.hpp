@@ -91,6 +91,7 @@ struct SlotMeta {
     uint64_t id = 0;
     int32_t pins = 0;
     int32_t inflight = 0;      // enqueued transfers that read or write this slot
+    int32_t refs = 0;          // readers that use the slot's bytes in place (lmc_chunk_acquire)
     uint64_t ready_ticket = 0; // the store whose D2H fills this slot (0 = already filled)
     uint64_t use_call = 0;     // number of the last store / retrieve call that used the chunk
     int64_t older = -1, newer = -1;  // neighbours in the order of last use
@@ -167,12 +168,12 @@ public:
         unlink(slot);
         link_newest(slot);
     }
-    // The least recently used chunk that may go: not pinned, no transfer in flight, not
-    // used by call number `call` (a call never evicts what it uses itself); -1 if none.
+    // The least recently used chunk that may go: not pinned, no transfer in flight, no
+    // reader holding it, not used by call number `call` (a call never evicts what it uses itself); -1 if none.
     int64_t victim(uint64_t call) const {
         for (int64_t s = oldest_; s >= 0; s = meta_[size_t(s)].newer) {
             const SlotMeta &m = meta_[size_t(s)];
-            if (m.pins == 0 && m.inflight == 0 && m.use_call != call) return s;
+            if (m.pins == 0 && m.inflight == 0 && m.refs == 0 && m.use_call != call) return s;
         }
         return -1;
     }

@@ -15,7 +15,7 @@ import os
 import numpy as np
 
 LMC_OK, LMC_ERR_INVAL, LMC_ERR_NOMEM, LMC_ERR_MISS, LMC_ERR_BADSLOT = 0, -1, -2, -3, -4
-LMC_ERR_HIP, LMC_ERR_BUSY, LMC_ERR_NODEVICE = -5, -6, -7
+LMC_ERR_HIP, LMC_ERR_BUSY, LMC_ERR_NODEVICE, LMC_ERR_IO = -5, -6, -7, -8
 LMC_MAX_LAYERS = 160
 LMC_DEVICE_NONE = -1
 LMC_FLAG_VALIDATE_SLOTS, LMC_FLAG_FORCE_SYNC, LMC_FLAG_POISON_STAGING, LMC_FLAG_TIMING = 1, 2, 4, 8
@@ -34,7 +34,9 @@ EXPORTS = [
     "lmc_store_begin", "lmc_store_layers", "lmc_wait_layer", "lmc_wait", "lmc_gather",
     "lmc_scatter", "lmc_put_host", "lmc_get_host", "lmc_find_slot", "lmc_pin", "lmc_unpin",
     "lmc_clear", "lmc_drain_evicted", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_measure_link_duplex",
-    "lmc_copy", "lmc_tune",
+    "lmc_copy", "lmc_tune", "lmc_chunk_acquire", "lmc_chunk_release", "lmc_tier_open", "lmc_tier_close",
+    "lmc_tier_write", "lmc_tier_wait", "lmc_tier_lookup", "lmc_tier_read", "lmc_tier_errno",
+    "lmc_tier_get_stats",
     "lmc_strerror", "lmc_last_hip_error",
 ]
 
@@ -110,6 +112,16 @@ def _lib():
             "lmc_window_offload": (st, [vp, vp, vp, ctypes.POINTER(i64)]),
             "lmc_window_acquire": (st, [vp, i64, vp, i32]),
             "lmc_window_get": (st, [vp] + [ctypes.POINTER(i64)] * 4 + [ctypes.POINTER(i32)]),
+            "lmc_chunk_acquire": (st, [vp, u64, ctypes.POINTER(vp)]),
+            "lmc_chunk_release": (st, [vp, u64]),
+            "lmc_tier_open": (st, [vp, ctypes.POINTER(ctypes.c_char_p), i32, i32, ctypes.POINTER(vp)]),
+            "lmc_tier_close": (st, [vp]),
+            "lmc_tier_write": (st, [vp, vp, i64]),
+            "lmc_tier_wait": (st, [vp]),
+            "lmc_tier_lookup": (st, [vp, i32, vp, i64, ctypes.POINTER(i64)]),
+            "lmc_tier_read": (st, [vp, i32, vp, i64]),
+            "lmc_tier_errno": (i32, [vp]),
+            "lmc_tier_get_stats": (st, [vp] + [ctypes.POINTER(u64)] * 3),
             "lmc_hash_chunks": (st, [vp, vp, i64, vp, ctypes.POINTER(i64)]),
             "lmc_lookup": (st, [vp, vp, i64, ctypes.POINTER(i64)]),
             "lmc_store": (st, [vp, vp, vp, vp, i64, vp, ctypes.POINTER(u64)]),
@@ -315,6 +327,21 @@ class Context:
         self._check(rc, "lmc_test")
         return True
 
+    def chunk_acquire(self, chunk_id):
+        """Raises the chunk's reference counter; returns a read-only numpy view of its
+        bytes in the pinned pool, valid until chunk_release."""
+        p = ctypes.c_void_p()
+        self._check(_lib().lmc_chunk_acquire(self._h, int(chunk_id), ctypes.byref(p)), "lmc_chunk_acquire")
+        a = np.ctypeslib.as_array(ctypes.cast(p, ctypes.POINTER(ctypes.c_uint8)), shape=(self.chunk_bytes(),))
+        a.flags.writeable = False
+        return a
+
+    def chunk_release(self, chunk_id):
+        self._check(_lib().lmc_chunk_release(self._h, int(chunk_id)), "lmc_chunk_release")
+
+    def tier_open(self, dirs, n_threads=2):
+        return Tier(self, dirs, n_threads)
+
     def window_create(self, window_pages, max_batch_pages=64):
         return Window(self, window_pages, max_batch_pages)
 
@@ -444,6 +471,54 @@ class Sequence:
             self.close()
         except Exception:
             pass
+
+
+class Tier:
+    """One lmc_tier_t: directories under the pool, every chunk written to all of them at once."""
+
+    def __init__(self, ctx, dirs, n_threads):
+        self._ctx, self._h = ctx, None
+        arr = (ctypes.c_char_p * len(dirs))(*[os.fsencode(d) for d in dirs])
+        h = ctypes.c_void_p()
+        ctx._check(_lib().lmc_tier_open(ctx._h, arr, len(dirs), n_threads, ctypes.byref(h)), "lmc_tier_open")
+        self._h = h
+
+    def write(self, chunk_ids):
+        ids, ip = _host(chunk_ids, np.uint64)
+        self._ctx._check(_lib().lmc_tier_write(self._h, ip, ids.size), "lmc_tier_write")
+
+    def wait(self):
+        self._ctx._check(_lib().lmc_tier_wait(self._h), "lmc_tier_wait")
+
+    def lookup(self, dir_index, chunk_ids):
+        ids, ip = _host(chunk_ids, np.uint64)
+        n = ctypes.c_int64()
+        self._ctx._check(_lib().lmc_tier_lookup(self._h, dir_index, ip, ids.size, ctypes.byref(n)),
+                         "lmc_tier_lookup")
+        return n.value
+
+    def read(self, dir_index, chunk_ids):
+        ids, ip = _host(chunk_ids, np.uint64)
+        self._ctx._check(_lib().lmc_tier_read(self._h, dir_index, ip, ids.size), "lmc_tier_read")
+
+    def errno(self):
+        return int(_lib().lmc_tier_errno(self._h))
+
+    def get_stats(self):
+        v = [ctypes.c_uint64() for _ in range(3)]
+        self._ctx._check(_lib().lmc_tier_get_stats(self._h, *[ctypes.byref(x) for x in v]), "lmc_tier_get_stats")
+        return dict(files_written=v[0].value, bytes_written=v[1].value, chunks_read=v[2].value)
+
+    def close(self):
+        if self._h is not None:
+            _lib().lmc_tier_close(self._h)
+            self._h = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
 
 
 class Window:

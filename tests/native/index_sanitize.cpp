@@ -84,13 +84,14 @@ int main() {
             } else if (op == 3 && slot >= 0) {
                 idx.meta(slot).pins = int32_t(rng() % 2);
                 idx.meta(slot).inflight = int32_t(rng() % 2);
+                idx.meta(slot).refs = int32_t(rng() % 3 == 0);
                 idx.meta(slot).use_call = rng() % 3;
             } else if (op >= 4) {
                 const uint64_t call = rng() % 3;
                 uint64_t want = ~0ull;
                 for (uint64_t o : order) {
                     const lmc::SlotMeta &m = idx.meta(idx.find(o));
-                    if (m.pins == 0 && m.inflight == 0 && m.use_call != call) {
+                    if (m.pins == 0 && m.inflight == 0 && m.refs == 0 && m.use_call != call) {
                         want = o;
                         break;
                     }

@@ -268,6 +268,48 @@ def test_eviction_spares_chunks_with_a_transfer_in_flight():
         assert st["chunks_evicted"] == nB and st["pool_slots_used"] == nA + nB
 
 
+def test_stored_chunks_go_to_two_directories_without_a_copy_and_come_back(tmp_path):
+    """Section 5.3: chunks stored from the GPU are written to two lower-tier directories at
+    once, straight from the pinned pool, right behind the store (the first count taken on a
+    chunk waits for the store that fills it).  Files must equal the oracle's chunks; after
+    the pool is emptied they are read back and retrieved into fresh pages."""
+    import os
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    lmc = _lmc()
+    name = "llama3_8b"
+    g = W.geometry(name, L=4, NB=1024)                       # 4 MiB chunks
+    n = 9
+    seq = W.sequence(name, g, n_tokens=n * g.CT)
+    rng = W.rng_for(name, stream=12)
+    src = PagedKV(g, seq["store_blocks"], rng)
+    dst = PagedKV(g, seq["load_blocks"], fill="sentinel")
+    dirs = [str(tmp_path / "disk"), str(tmp_path / "remote")]
+    for d in dirs:
+        os.mkdir(d)
+    stream = torch.cuda.current_stream()
+    chunks = oracle.gather(src.gc, src.host, src.compact_slots(seq["store_slots"]))
+    with lmc.Context(g, n * g.chunk_bytes, staging_chunks=2) as c, c.tier_open(dirs, n_threads=4) as t:
+        ids = c.hash_chunks(seq["tokens"])
+        d_store, d_load = slots_to_device(seq["store_slots"]), slots_to_device(seq["load_slots"])
+        c.store(src.dev, d_store, ids, stream)
+        t.write(ids)                                          # no lmc_wait in between
+        t.wait()
+        for d in dirs:
+            for k, i in enumerate(ids.tolist()):
+                got = np.fromfile(os.path.join(d, "%016x.kv" % i), dtype=np.uint8)
+                assert np.array_equal(got, chunks[k]), (d, k)
+        c.wait()
+        c.clear(ids)
+        assert c.lookup(ids) == 0 and t.lookup(1, ids) == n
+        t.read(1, ids)
+        c.wait(c.retrieve(ids, d_load, dst.dev, stream))
+        torch.cuda.synchronize()
+        oracle.scatter(dst.gc, chunks, dst.compact_slots(seq["load_slots"]), dst.host)
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host, "retrieve of chunks read back from a directory")
+        assert t.get_stats() == dict(files_written=2 * n, bytes_written=2 * n * g.chunk_bytes, chunks_read=n)
+
+
 def test_config3_llama3_70b_full_size_sampled_oracle():
     """Full size on the device (40 GiB of pages, 128 chunks = 10 GiB through the pinned
     pool).  The oracle checks sampled chunks byte for byte; the whole result is checked

@@ -1,6 +1,7 @@
 """ThreadSanitizer over the library's host side (context, index, pool bookkeeping): the
 host code of liblmc is rebuilt with -fsanitize=thread and six threads hammer one
-index-only context through the C ABI.  CPU only; no HIP call is made."""
+index-only context through the C ABI, with counted readers and the directory tier's
+writer threads reading the pool meanwhile.  CPU only; no HIP call is made."""
 import os
 import shutil
 import subprocess
@@ -18,7 +19,8 @@ CSRC = os.path.join(ROOT, "paper_2510_09665_amd", "csrc")
 def test_host_side_is_race_free_under_tsan(tmp_path):
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     lib = str(tmp_path / "liblmc_tsan.so")
-    srcs = [os.path.join(CSRC, f) for f in ("lmc_kernels.hip", "lmc_ctx.cpp", "lmc_seq.cpp", "lmc_window.cpp")]
+    srcs = [os.path.join(CSRC, f) for f in ("lmc_kernels.hip", "lmc_ctx.cpp", "lmc_seq.cpp", "lmc_window.cpp",
+                                                "lmc_tier.cpp")]
     build = [hipcc, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
              "-Xarch_host", "-fsanitize=thread", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
     res = subprocess.run(build + srcs + ["-o", lib], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -33,6 +35,9 @@ def test_host_side_is_race_free_under_tsan(tmp_path):
     assert res.returncode == 0, res.stdout[-3000:]
     env = dict(os.environ)
     env["TSAN_OPTIONS"] = "halt_on_error=1:report_signal_unsafe=0"
-    res = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env, timeout=300)
+    dirs = [str(tmp_path / "tier_a"), str(tmp_path / "tier_b")]
+    for d in dirs:
+        os.mkdir(d)
+    res = subprocess.run([exe] + dirs, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env, timeout=300)
     sys.stdout.write(res.stdout[-3000:])
     assert res.returncode == 0 and res.stdout.strip().endswith("ok"), res.stdout[-3000:]
