@@ -26,8 +26,13 @@ Also reported in the same JSON line:
   layerwise    the same request moved layer by layer (rectangle copies + kernels over
                one or four layers), as a fraction of the link peak, and how soon layer 0
                is usable compared with the bulk retrieve
+  fragmented_pool  the same request with every other pool slot taken beforehand, so that
+               no two of its chunks are neighbours in the pool (one copy per chunk)
+  small_request    one 0.5 MiB chunk (configuration 1): microseconds from the call to a
+               finished lmc_wait, through the staging ring and by the library's size rule
   cpu_baseline the CPU oracle doing the same store + retrieve on the same 16 chunks,
                chunks fanned out over host threads
+  configs      (only with --legs ...,configs) every benchmark configuration end to end
 """
 import argparse
 import json
@@ -94,6 +99,61 @@ def cpu_baseline(g, seq, budget_s=12.0):
     }
 
 
+def all_configs(torch, lmc, W, dev, stream, timed):
+    """Every benchmark configuration end to end (store, then retrieve into fresh blocks;
+    configuration 4: one batched retrieve of the hit chunks of 64 requests, pool slots in
+    shuffled order), each as a fraction of the link peak measured in the same context."""
+    res = {}
+    for name, staging in (("tiny", 1), ("llama3_8b", 16), ("llama3_70b", 8), ("mla_bf16", 32), ("mla_fp8", 32)):
+        g = W.geometry(name)
+        seq = W.sequence(name, g)
+        n = seq["tokens"].size // g.CT
+        kv = [torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev) for _ in range(g.L)]
+        d_s, d_l = torch.from_numpy(seq["store_slots"]).to(dev), torch.from_numpy(seq["load_slots"]).to(dev)
+        ctx = lmc.Context(g, max(n * g.chunk_bytes, 1 << 30), staging_chunks=staging, device=0)
+        ids = ctx.hash_chunks(seq["tokens"])
+
+        def st():
+            ctx.clear(ids)
+            ctx.wait(ctx.store(kv, d_s, ids, stream))
+        # best of a dozen: for a few seconds after memory of this size has been allocated or
+        # freed in the process, the runtime's device-to-host copies run at half speed
+        ts = timed(st, reps=12)
+        tl = timed(lambda: ctx.wait(ctx.retrieve(ids, d_l, kv, stream)), reps=4)
+        nbytes = n * g.chunk_bytes
+        h2d, d2h = ctx.measure_link(min(512 << 20, nbytes) // 16 * 16, reps=3)
+        res[name] = {"chunks": n, "payload_bytes": nbytes,
+                     "store_gbps": round(nbytes / ts / 1e9, 2), "retrieve_gbps": round(nbytes / tl / 1e9, 2),
+                     "store_frac_of_d2h_peak": round(nbytes / ts / 1e9 / d2h, 4),
+                     "retrieve_frac_of_h2d_peak": round(nbytes / tl / 1e9 / h2d, 4),
+                     "store_ms": round(ts * 1e3, 3), "retrieve_ms": round(tl * 1e3, 3)}
+        ctx.destroy()
+        del kv
+        torch.cuda.empty_cache()
+    g = W.geometry("batch_8b")
+    reqs = W.request_mix("batch_8b", g)
+    n_hit = sum(r["n_hit"] for r in reqs)
+    kv = [torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev) for _ in range(g.L)]
+    ctx = lmc.Context(g, (n_hit + 1) * g.chunk_bytes, staging_chunks=16, device=0)
+    zero = np.zeros(g.chunk_bytes, dtype=np.uint8)
+    ids_per = [ctx.hash_chunks(r["tokens"]) for r in reqs]
+    hit = [(ri, k) for ri, r in enumerate(reqs) for k in range(r["n_hit"])]
+    for j in np.random.default_rng(0).permutation(len(hit)):
+        ctx.put_host([ids_per[hit[j][0]][hit[j][1]]], zero)
+    off = np.concatenate([[0], np.cumsum([r["n_hit"] for r in reqs])])
+    ids_all = np.concatenate([ids_per[ri][:r["n_hit"]] for ri, r in enumerate(reqs)])
+    d_sl = torch.from_numpy(np.concatenate([r["load_slots"] for r in reqs])).to(dev)
+    t = timed(lambda: ctx.wait(ctx.retrieve_batch(off, ids_all, d_sl, kv, stream)), reps=3)
+    h2d, _ = ctx.measure_link(512 << 20, reps=3)
+    nbytes = n_hit * g.chunk_bytes
+    res["batch_8b"] = {"requests": len(reqs), "hit_chunks": n_hit, "payload_bytes": nbytes,
+                       "retrieve_batch_gbps": round(nbytes / t / 1e9, 2),
+                       "retrieve_frac_of_h2d_peak": round(nbytes / t / 1e9 / h2d, 4),
+                       "retrieve_ms": round(t * 1e3, 1)}
+    ctx.destroy()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -102,9 +162,10 @@ def main():
     ap.add_argument("--staging-chunks", type=int, default=16)
     ap.add_argument("--num-staging", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--legs", default="pipeline,link,device,duplex,direct,layerwise,cpu",
-                    help="comma list of pipeline (always run), link, device, duplex, direct, layerwise, cpu: the "
-                         "extra measurements to make; profiling runs use a subset")
+    ap.add_argument("--legs", default="pipeline,link,device,duplex,direct,layerwise,fragmented,small,cpu",
+                    help="comma list of pipeline (always run), link, device, duplex, direct, layerwise, "
+                         "fragmented, small, cpu, and configs (every benchmark configuration end to end; "
+                         "not in the default): the extra measurements to make; profiling runs use a subset")
     ap.add_argument("--tune", action="append", default=[], help="key=value for lmc_tune")
     args = ap.parse_args()
     legs = set(args.legs.split(","))
@@ -299,6 +360,9 @@ def main():
     direct = None
     if "direct" in legs:
         dctx = lmc.Context(g, max(n_chunks * g.chunk_bytes, 1 << 30), device=0, flags=lmc.LMC_FLAG_DIRECT)
+        for kv in args.tune:
+            k, v = kv.split("=")
+            dctx.tune(k, int(v))
         dids = dctx.hash_chunks(seq["tokens"])
 
         def d_store_only():
@@ -359,9 +423,63 @@ def main():
             "bulk": round(min(first_layer("bulk") for _ in range(4)), 3)}
         ctx.clear(ids)
 
+    # a pool in which every other slot is taken: no two chunks of the request are
+    # neighbours, so every group needs one copy per chunk (two copy streams take turns)
+    fragmented = None
+    if "fragmented" in legs:
+        fctx = lmc.Context(g, (2 * n_chunks + 1) * g.chunk_bytes, staging_chunks=args.staging_chunks,
+                           num_staging=args.num_staging, device=0)
+        filler = np.arange(1, 2 * n_chunks + 1, dtype=np.uint64) + np.uint64(1 << 40)
+        zero = np.zeros(g.chunk_bytes, dtype=np.uint8)
+        for f in filler:
+            fctx.put_host([f], zero)
+        fctx.clear(filler[1::2])
+        fids = fctx.hash_chunks(seq["tokens"])
+
+        def f_store_only():
+            fctx.clear(fids)
+            fctx.wait(fctx.store(src, d_store, fids, stream))
+        tf_s = timed(f_store_only)
+        assert [fctx.find_slot(i) for i in fids[:3]] == [1, 3, 5]
+        tf_l = timed(lambda: fctx.wait(fctx.retrieve(fids, d_load, dst, stream)))
+        h2d, d2h = fctx.measure_link(512 << 20, reps=3)
+        fragmented = {"store_gbps": round(payload_one_way / tf_s / 1e9, 2),
+                      "retrieve_gbps": round(payload_one_way / tf_l / 1e9, 2),
+                      "store_frac_of_d2h_peak": round(payload_one_way / tf_s / 1e9 / d2h, 4),
+                      "retrieve_frac_of_h2d_peak": round(payload_one_way / tf_l / 1e9 / h2d, 4)}
+        fctx.destroy()
+
     ctx.destroy()
     del src, dst
     torch.cuda.empty_cache()
+
+    # a request of one small chunk (config 1, 0.5 MiB): time from the call to a finished
+    # lmc_wait, through the staging ring and by the library's size rule (no staging)
+    small = None
+    if "small" in legs:
+        small = {}
+        tg = W.geometry("tiny")
+        tseq = W.sequence("tiny", tg)
+        tsrc = [torch.zeros(tg.layer_bytes, dtype=torch.uint8, device=dev) for _ in range(tg.L)]
+        ts_, tl_ = torch.from_numpy(tseq["store_slots"]).to(dev), torch.from_numpy(tseq["load_slots"]).to(dev)
+        for mode in ("staged", "size_rule"):
+            tctx = lmc.Context(tg, 4 * tg.chunk_bytes, device=0)
+            if mode == "staged":
+                tctx.tune("direct_store_below", 0)
+                tctx.tune("direct_retrieve_below", 0)
+            tids = tctx.hash_chunks(tseq["tokens"])
+
+            def t_store_only():
+                tctx.clear(tids)
+                tctx.wait(tctx.store(tsrc, ts_, tids, stream))
+            small[mode] = {"store_us": round(timed(t_store_only, reps=40) * 1e6, 1),
+                           "retrieve_us": round(timed(lambda: tctx.wait(tctx.retrieve(tids, tl_, tsrc, stream)),
+                                                      reps=40) * 1e6, 1)}
+            tctx.destroy()
+        small["payload_bytes"] = tg.chunk_bytes
+        del tsrc
+
+    configs = all_configs(torch, lmc, W, dev, stream, timed) if "configs" in legs else None
 
     out = {
         "metric": "KV store/retrieve GB/s", "value": round(value, 3), "unit": "GB/s",
@@ -385,6 +503,12 @@ def main():
         out["direct"] = direct
     if layerwise:
         out["layerwise"] = layerwise
+    if fragmented:
+        out["fragmented_pool"] = fragmented
+    if small:
+        out["small_request"] = small
+    if configs:
+        out["configs"] = configs
     if "cpu" in legs:
         out["cpu_baseline"] = cpu_baseline(g, seq)
     print(json.dumps(out), flush=True)

@@ -437,7 +437,14 @@ lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *ctx, uint64_t nbytes, int32_t re
 
 /* Run-time knobs for experiments; the defaults are the measured best.  Keys: "nt_load",
  * "nt_store" (0/1: non-temporal hints on the kernels' streaming accesses), "xcd_run"
- * (consecutive tiles handed to one XCD, 0 = hardware round-robin), "edge_chunks" (size
+ * (consecutive tiles handed to one XCD, 0 = hardware round-robin), "link_groups" (default
+ * 64: launches that read or write the pinned pool themselves run as that many workgroups
+ * taking tiles in turn, which is what the host link likes; 0 = one tile per workgroup as
+ * for launches inside HBM), "copy_kernel" (default 0; bit 0: copies from staging to the
+ * pool are made by the library's own link-paced copy kernel instead of hipMemcpyAsync;
+ * bit 1: copies from the pool to staging too.  2-3 % slower than the runtime's copies,
+ * but independent of which engine the runtime picks and of what else that engine is doing),
+ * "edge_chunks" (size
  * of the group at the exposed end of a pipeline, 0 = none), "timing" (0/1: switches
  * LMC_FLAG_TIMING), "direct_store_below" / "direct_retrieve_below" (bytes, defaults 4 MiB /
  * 2 MiB: an lmc_store with at most that many new bytes, or an lmc_retrieve /

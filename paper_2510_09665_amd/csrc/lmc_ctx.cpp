@@ -65,6 +65,16 @@ struct lmc_ctx {
     lmc_config_t cfg{};
     lmc::KernelGeom kg{};
     lmc::LaunchShape shape{};
+    uint32_t link_groups = 64;  // workgroups of a launch whose other side is the pinned pool; 0 = as for HBM
+    // Which copies between staging and the pool the library's own link-paced copy kernel
+    // makes instead of hipMemcpyAsync: bit 0 = to the host, bit 1 = from the host.  Off
+    // by default: the runtime's copies are 2-3 % faster.  But for some seconds after tens
+    // of GiB of device or pinned memory have been freed or allocated in the process, the
+    // runtime's device-to-host copies inside a store ran at 31.5 GB/s instead of 57 on
+    // the machine this was measured on (not with HSA_ENABLE_SDMA=0, which points at the
+    // copy engines being busy with the driver's own work on that memory); the kernel's
+    // 55 GB/s does not depend on that.
+    uint32_t copy_kernel = 0;
     int64_t edge_chunks = 1;  // size of the group at the exposed end of a pipeline; 0 = no special group
     // Bulk calls that move at most this many bytes skip staging and the copy engine (the
     // kernel itself crosses the link): below a few MiB the copy's launch and the extra
@@ -287,7 +297,11 @@ lmc_status_t timed_launch(lmc_ctx *c, bool gather, const lmc::LaunchView &view,
         if (rc == LMC_OK) rc = get_event(c, true, &e1);
         if (rc != LMC_OK) return rc;
     }
-    const lmc::LaunchShape &s = c->shape;
+    lmc::LaunchShape s = c->shape;
+    // a launch that reads or writes the pinned pool itself is paced by the host link
+    if (c->pool_dev != nullptr && staging >= c->pool_dev &&
+        staging < c->pool_dev + uint64_t(c->n_pool_slots) * uint64_t(c->chunk_bytes))
+        s.paced_groups = c->link_groups;
     const uint64_t moved = uint64_t(n_chunks) * view.by_n_lp.d * c->kg.plane_bytes;
     if (gather) {
         HIPCHK(c, lmc::launch_gather(c->kg, view, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1));
@@ -323,6 +337,20 @@ lmc_status_t copy_group(lmc_ctx *c, bool to_host, uint8_t *staging, uint64_t str
         int64_t m = 1;
         while (j + m < k && pool_slots[j + m] == pool_slots[j] + m) m++;
         hipStream_t stream = first;
+        const bool by_kernel = ((c->copy_kernel >> (to_host ? 0 : 1)) & 1u) != 0 && c->pool_dev != nullptr &&
+                               ((width | stride | cb | pool_off | reinterpret_cast<uintptr_t>(staging)) % 16) == 0;
+        if (by_kernel) {
+            // launches follow each other without a gap: one stream is enough
+            uint8_t *pool_at = c->pool_dev + uint64_t(pool_slots[j]) * cb + pool_off;
+            uint8_t *stage_at = staging + uint64_t(j) * stride;
+            const uint32_t groups = c->link_groups ? c->link_groups : 64u;
+            if (to_host) HIPCHK(c, lmc::launch_copy_rect(pool_at, cb, stage_at, stride, width, uint64_t(m), groups, stream));
+            else HIPCHK(c, lmc::launch_copy_rect(stage_at, stride, pool_at, cb, width, uint64_t(m), groups, stream));
+            if (to_host) c->stats.bytes_d2h += uint64_t(m) * width;
+            else c->stats.bytes_h2d += uint64_t(m) * width;
+            j += m;
+            continue;
+        }
         if (second != nullptr && (run & 1)) {
             stream = second;
             if (used_second) *used_second = true;
@@ -666,6 +694,7 @@ lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out) {
     c->shape.nt_load = true;
     c->shape.nt_store = true;
     c->shape.xcd_run = 32;
+    c->shape.paced_groups = 0;
     c->has_device = cfg->device != LMC_DEVICE_NONE;
     const size_t pool_bytes = size_t(c->n_pool_slots) * size_t(c->chunk_bytes);
     if (!c->has_device) {
@@ -1391,6 +1420,11 @@ lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
     } else if (k == "xcd_run") {
         if (value > (1 << 20)) return LMC_ERR_INVAL;
         c->shape.xcd_run = uint32_t(value);
+    } else if (k == "copy_kernel" && value <= 3) {
+        c->copy_kernel = uint32_t(value);
+    } else if (k == "link_groups") {
+        if (value > 65536) return LMC_ERR_INVAL;
+        c->link_groups = uint32_t(value);
     } else if (k == "nt_load" && value <= 1) {
         c->shape.nt_load = value != 0;
     } else if (k == "nt_store" && value <= 1) {

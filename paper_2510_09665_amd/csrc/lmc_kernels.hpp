@@ -66,6 +66,9 @@ struct LaunchShape {
     uint32_t xcd_run;         // workgroup ids are permuted so that each of the 8 XCDs
                               // takes runs of this many (rounded down to a power of
                               // two) consecutive tiles; 0 = off
+    uint32_t paced_groups;    // 0: one tile per workgroup (HBM-bound launches); n > 0: a
+                              // fixed grid of n workgroups that take tiles in turn, for
+                              // launches whose other side is host memory
 };
 
 // pages -> n_chunks chunks of the slot mapping, written back to back from `staging`
@@ -87,6 +90,11 @@ LaunchView layer_view(const KernelGeom &g, uint32_t planes_per_layer, uint32_t f
 hipError_t launch_check_slots(const int64_t *slot_mapping, uint64_t n, uint32_t n_slots,
                               int32_t *bad_flag, hipStream_t stream);
 hipError_t launch_copy(uint8_t *dst, const uint8_t *src, uint64_t nbytes, hipStream_t stream);
+// rows x width bytes, rows src_pitch / dst_pitch apart, by `groups` workgroups that take
+// tiles in turn (the shape that suits a copy whose one side is pinned host memory).
+// Everything must be a multiple of 16 bytes, else hipErrorInvalidValue.
+hipError_t launch_copy_rect(uint8_t *dst, uint64_t dst_pitch, const uint8_t *src, uint64_t src_pitch,
+                            uint64_t width, uint64_t rows, uint32_t groups, hipStream_t stream);
 hipError_t launch_fill(uint8_t *dst, uint8_t value, uint64_t nbytes, hipStream_t stream);
 
 // largest number of chunks one launch may cover (32-bit workgroup index)

@@ -20,6 +20,7 @@ CASES = {
     "hnd_k2": ("llama3_8b", dict(L=6, NB=512, layout="HND"), 8 * 256, 2, 2, 0),
     "blocks_outer_k2": ("llama3_8b", dict(L=6, NB=512, order="NP"), 8 * 256, 2, 2, "poison"),
     "max_layers_k7_ragged": ("tiny", dict(L=160, NB=128), 512, 1, 7, 0),    # 160 layers = 22 steps of 7 + one of 6
+    "own_copy_kernel_k3": ("llama3_8b", dict(L=8, NB=1024), 10 * 256, 1, 3, "kcopy"),
     "all_layers_in_one_step": ("tiny", {}, 256, 1, 99, 0),
     "direct_llama_k1": ("llama3_8b", dict(L=8, NB=1024), 10 * 256, 1, 1, "direct"),
     "direct_mla_k3": ("mla_bf16", dict(L=7), 4 * 256, 1, 3, "direct"),
@@ -35,9 +36,12 @@ def _setup(case):
     rng = W.rng_for(name, stream=3)
     src = PagedKV(g, seq["store_blocks"], rng)
     dst = PagedKV(g, seq["load_blocks"], fill="sentinel")
-    f = {"poison": lmc.LMC_FLAG_POISON_STAGING, "direct": lmc.LMC_FLAG_DIRECT}.get(flags, 0)
+    f = {"poison": lmc.LMC_FLAG_POISON_STAGING, "direct": lmc.LMC_FLAG_DIRECT,
+         "kcopy": lmc.LMC_FLAG_POISON_STAGING}.get(flags, 0)
     n_chunks = n_tok // g.CT
     ctx = lmc.Context(g, n_chunks * g.chunk_bytes, staging_chunks=staging, flags=f | lmc.LMC_FLAG_TIMING)
+    if flags == "kcopy":
+        ctx.tune("copy_kernel", 3)      # rectangle copies by the library's own copy kernel, both ways
     return lmc, g, seq, src, dst, ctx, k, n_chunks
 
 

@@ -158,6 +158,21 @@ def test_pipeline_modes_give_identical_results(flags):
     _run_sequence("llama3_8b", g, flags=f, n_tokens=24 * 256, num_staging=3, staging_chunks=5)
 
 
+@pytest.mark.parametrize("engines", [1, 2, 3])
+def test_own_copy_kernel_instead_of_the_runtimes_copies(engines):
+    """lmc_tune("copy_kernel"): the copies between staging and the pool made by the
+    library's link-paced copy kernel (bit 0 to the host, bit 1 from the host)."""
+    lmc = _lmc()
+    t = (("copy_kernel", engines),)
+    g = W.geometry("llama3_8b", L=4, NB=1024)
+    _run_sequence("llama3_8b", g, flags=lmc.LMC_FLAG_POISON_STAGING, n_tokens=24 * 256, num_staging=3,
+                  staging_chunks=5, tune=t)
+    _run_sequence("mla_fp8", W.geometry("mla_fp8", L=7), n_tokens=6 * 256, staging_chunks=2, tune=t)
+    # rows that are no multiple of 16 bytes stay with the runtime's copies
+    _run_sequence("tiny", W.KVGeometry(L=3, P=2, H=3, D=7, e=2, BS=4, NB=256, CT=32), n_tokens=5 * 32,
+                  staging_chunks=2, tune=t + (("direct_store_below", 0), ("direct_retrieve_below", 0)))
+
+
 def test_direct_mode_full_size_config2_and_mla():
     """LMC_FLAG_DIRECT: the kernels read and write the pinned pool themselves."""
     lmc = _lmc()
@@ -178,10 +193,12 @@ def test_blocks_outermost_page_order_through_the_pipeline():
     _run_sequence("llama3_8b", g, n_tokens=8 * 256, staging_chunks=1, flags=_lmc().LMC_FLAG_DIRECT)
 
 
-def test_fragmented_pool_copies_alternate_between_two_streams():
+@pytest.mark.parametrize("copy_kernel", [0, 3])
+def test_fragmented_pool_copies_alternate_between_two_streams(copy_kernel):
     """Every other pool slot is taken, so no two new chunks are neighbours in the pool:
-    each group needs one copy per chunk, and those go to two copy streams in turn.  Pool
-    image and pages must equal the oracle's, whose store went through the same history."""
+    each group needs one copy per chunk, and those go to two copy streams in turn (or, with
+    the library's own copy kernel, follow each other on one).  Pool image and pages must
+    equal the oracle's, whose store went through the same history."""
     import torch
     from gpu_util import PagedKV, assert_layers_equal, slots_to_device
     lmc = _lmc()
@@ -199,6 +216,7 @@ def test_fragmented_pool_copies_alternate_between_two_streams():
     filler_slots = np.tile(src.compact_slots(seq["store_slots"][:g.CT]), 2 * n)
     with lmc.Context(g, n_pool * g.chunk_bytes, staging_chunks=5, num_staging=2,
                      flags=lmc.LMC_FLAG_POISON_STAGING) as c:
+        c.tune("copy_kernel", copy_kernel)
         # history: 2n filler chunks, then every second one removed, in both stores
         d_fill = slots_to_device(np.tile(seq["store_slots"][:g.CT], 2 * n))
         c.wait(c.store(src.dev, d_fill, filler_ids, stream))
