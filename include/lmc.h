@@ -446,10 +446,10 @@ lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *ctx, uint64_t nbytes, int32_t re
  * but independent of which engine the runtime picks and of what else that engine is doing),
  * "edge_chunks" (size
  * of the group at the exposed end of a pipeline, 0 = none), "timing" (0/1: switches
- * LMC_FLAG_TIMING), "direct_store_below" / "direct_retrieve_below" (bytes, defaults 4 MiB /
- * 2 MiB: an lmc_store with at most that many new bytes, or an lmc_retrieve /
- * lmc_retrieve_batch of at most that many bytes, goes the LMC_FLAG_DIRECT way because
- * a transfer that small is bound by launch latencies, not by the link; 0 = never).  Unknown key or out-of-range value: LMC_ERR_INVAL. */
+ * LMC_FLAG_TIMING), "direct_store_below" / "direct_retrieve_below" (bytes, default 64 MiB
+ * each: an lmc_store with at most that many new bytes, or an lmc_retrieve /
+ * lmc_retrieve_batch of at most that many bytes, goes the LMC_FLAG_DIRECT way: one launch
+ * instead of kernel, event, copy, event; 0 = never).  Unknown key or out-of-range value: LMC_ERR_INVAL. */
 lmc_status_t lmc_tune(lmc_ctx_t *ctx, const char *key, int64_t value);
 
 const char *lmc_strerror(lmc_status_t status);

@@ -76,13 +76,15 @@ struct lmc_ctx {
     // 55 GB/s does not depend on that.
     uint32_t copy_kernel = 0;
     int64_t edge_chunks = 1;  // size of the group at the exposed end of a pipeline; 0 = no special group
-    // Bulk calls that move at most this many bytes skip staging and the copy engine (the
-    // kernel itself crosses the link): below a few MiB the copy's launch and the extra
-    // event hand-over cost more than the kernel's lower link efficiency.  0 = never.
     uint64_t use_calls = 0;         // number of the latest call that used chunks (recency of use)
     std::vector<uint64_t> evicted;  // LMC_FLAG_EVICT_LRU: ids evicted and not yet drained
-    int64_t direct_store_below = int64_t(4) << 20;
-    int64_t direct_retrieve_below = int64_t(2) << 20;
+    // Bulk calls that move at most this many bytes skip staging and the copy engine (the
+    // kernel itself crosses the link).  Small transfers are bound by launch latencies, which
+    // one launch instead of kernel, event, copy, event halves; up to 64 MiB the single
+    // launch is still 2-5 % faster and is over within a millisecond or so, beyond that
+    // the staged pipeline keeps the compute units free.  0 = never.
+    int64_t direct_store_below = int64_t(64) << 20;
+    int64_t direct_retrieve_below = int64_t(64) << 20;
     int64_t chunk_bytes = 0;
     int64_t n_pool_slots = 0;
     uint8_t *pool = nullptr;

@@ -40,6 +40,8 @@ def _setup(case):
          "kcopy": lmc.LMC_FLAG_POISON_STAGING}.get(flags, 0)
     n_chunks = n_tok // g.CT
     ctx = lmc.Context(g, n_chunks * g.chunk_bytes, staging_chunks=staging, flags=f | lmc.LMC_FLAG_TIMING)
+    ctx.tune("direct_store_below", 0)       # the bulk stores and retrieves beside the layer-wise
+    ctx.tune("direct_retrieve_below", 0)    # calls go through staging whatever their size
     if flags == "kcopy":
         ctx.tune("copy_kernel", 3)      # rectangle copies by the library's own copy kernel, both ways
     return lmc, g, seq, src, dst, ctx, k, n_chunks
@@ -206,10 +208,12 @@ def test_pending_layerwise_store_rules():
         c.wait()
 
 
-def test_bulk_and_layerwise_calls_share_the_rings_safely():
+@pytest.mark.parametrize("bulk_staged", [True, False])
+def test_bulk_and_layerwise_calls_share_the_rings_safely(bulk_staged):
     """Bulk and layer-wise calls divide the same staging memory differently.  Enqueue them
     back to back without host waits, with released staging overwritten at once: every
-    result must still be exact."""
+    result must still be exact.  bulk_staged=False leaves the bulk calls (30 and 60 MiB) to
+    the size rule: they then cross the link in one launch, beside the staged layer-wise ones."""
     import torch
     from gpu_util import PagedKV, assert_layers_equal, slots_to_device
     from paper_2510_09665_amd import lmc
@@ -224,6 +228,9 @@ def test_bulk_and_layerwise_calls_share_the_rings_safely():
     stream = torch.cuda.current_stream()
     ids = np.arange(100, 100 + n, dtype=np.uint64)
     with lmc.Context(g, 2 * n * g.chunk_bytes, staging_chunks=3, flags=lmc.LMC_FLAG_POISON_STAGING) as c:
+        if bulk_staged:
+            c.tune("direct_store_below", 0)
+            c.tune("direct_retrieve_below", 0)
         d_s = slots_to_device(s_slots)
         # store: first half in bulk, second half layer by layer, enqueued back to back
         t1 = c.store(src.dev, d_s, ids[:5], stream)

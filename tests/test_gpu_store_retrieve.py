@@ -15,9 +15,16 @@ def _lmc():
     return lmc
 
 
+STAGED = (("direct_store_below", 0), ("direct_retrieve_below", 0))
+
+
 def _run_sequence(name, geom=None, flags=0, num_staging=2, staging_chunks=1, n_tokens=None,
-                  pool_chunks=None, tune=()):
-    """Store a whole request, retrieve it into fresh blocks, compare pool and pages."""
+                  pool_chunks=None, tune=(), size_rule=False):
+    """Store a whole request, retrieve it into fresh blocks, compare pool and pages.
+    Unless size_rule is set the request goes through the staging rings whatever its size
+    (most cases here are kept small to be quick, and it is the pipeline they are after)."""
+    if not size_rule:
+        tune = STAGED + tuple(tune)
     import torch
     from gpu_util import PagedKV, assert_layers_equal, slots_to_device
     lmc = _lmc()
@@ -72,10 +79,13 @@ def _run_sequence(name, geom=None, flags=0, num_staging=2, staging_chunks=1, n_t
 
 def test_config1_tiny():
     # half a MiB: by the library's size rule both directions skip staging ...
-    st = _run_sequence("tiny")
+    st = _run_sequence("tiny", size_rule=True)
     assert st["gather_launches"] == 1 and st["scatter_launches"] == 1
     # ... and with the rule switched off the same bytes come through the staging ring
-    _run_sequence("tiny", tune=(("direct_store_below", 0), ("direct_retrieve_below", 0)))
+    _run_sequence("tiny")
+    # 12 chunks of 4 MiB are still below the threshold: one launch each way
+    st = _run_sequence("llama3_8b", W.geometry("llama3_8b", L=4, NB=1024), n_tokens=12 * 256, size_rule=True)
+    assert st["gather_launches"] == 1 and st["scatter_launches"] == 1
 
 
 def test_small_direct_and_large_staged_calls_interleaved_without_waiting():
@@ -100,6 +110,8 @@ def test_small_direct_and_large_staged_calls_interleaved_without_waiting():
     for rep in range(3):
         dst = PagedKV(g, lb, fill="sentinel")
         with lmc.Context(g, n * g.chunk_bytes, staging_chunks=2, flags=lmc.LMC_FLAG_POISON_STAGING) as c:
+            c.tune("direct_store_below", 4 << 20)
+            c.tune("direct_retrieve_below", 2 << 20)
             ids = c.hash_chunks(toks)
             d_s, d_l = slots_to_device(s_slots), slots_to_device(l_slots)
             cut = n_big * g.CT
@@ -170,7 +182,7 @@ def test_own_copy_kernel_instead_of_the_runtimes_copies(engines):
     _run_sequence("mla_fp8", W.geometry("mla_fp8", L=7), n_tokens=6 * 256, staging_chunks=2, tune=t)
     # rows that are no multiple of 16 bytes stay with the runtime's copies
     _run_sequence("tiny", W.KVGeometry(L=3, P=2, H=3, D=7, e=2, BS=4, NB=256, CT=32), n_tokens=5 * 32,
-                  staging_chunks=2, tune=t + (("direct_store_below", 0), ("direct_retrieve_below", 0)))
+                  staging_chunks=2, tune=t)
 
 
 def test_direct_mode_full_size_config2_and_mla():
@@ -217,6 +229,8 @@ def test_fragmented_pool_copies_alternate_between_two_streams(copy_kernel):
     with lmc.Context(g, n_pool * g.chunk_bytes, staging_chunks=5, num_staging=2,
                      flags=lmc.LMC_FLAG_POISON_STAGING) as c:
         c.tune("copy_kernel", copy_kernel)
+        for key, value in STAGED:
+            c.tune(key, value)
         # history: 2n filler chunks, then every second one removed, in both stores
         d_fill = slots_to_device(np.tile(seq["store_slots"][:g.CT], 2 * n))
         c.wait(c.store(src.dev, d_fill, filler_ids, stream))
