@@ -36,6 +36,22 @@ def test_chain_is_fnv_of_previous_hash_and_le32_tokens():
     assert int(h7[0]) != int(h[0])
 
 
+def test_chain_worked_example_tokens_0_to_511():
+    """Seed 0, tokens 0..511: the two chunk ids, as obtained twice independently of the
+    oracle (a byte-at-a-time FNV-1a in plain Python here, and once before when the hash
+    was chosen)."""
+    def fnv(data):
+        x = 0xcbf29ce484222325
+        for c in data:
+            x = ((x ^ c) * 0x100000001b3) & 0xFFFFFFFFFFFFFFFF
+        return x
+    h0 = fnv(struct.pack("<Q", 0) + struct.pack("<256i", *range(256)))
+    h1 = fnv(struct.pack("<Q", h0) + struct.pack("<256i", *range(256, 512)))
+    assert (h0, h1) == (0xc89cc5e687031dc5, 0x8e1d41f5a643ff04)
+    got = oracle.hash_chunks(np.arange(512, dtype=np.int32), CT=256, seed=0)
+    assert [int(x) for x in got] == [h0, h1]
+
+
 def test_only_full_chunks_and_prefix_property():
     rng = np.random.default_rng(11)
     a = W.tokens_for(rng, 256 * 6 + 100)
