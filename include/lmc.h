@@ -79,10 +79,12 @@ enum {
 #define LMC_FLAG_POISON_STAGING 4u /* overwrite a staging buffer with 0xA5 as soon as the
                                       pipeline releases it: a reuse that came too early
                                       then shows as corrupt data.  For tests. */
-#define LMC_FLAG_DIRECT 16u        /* no staging buffer and no copy engine: the gather kernel
-                                      writes, and the scatter kernel reads, the pinned pool
-                                      over the host link.  Same results; the kernels then
-                                      occupy compute units for the length of the transfer. */
+#define LMC_FLAG_DIRECT 16u        /* no staging buffer and no copy engine for any call: the
+                                      gather kernel writes, and the scatter kernel reads, the
+                                      pinned pool over the host link (64 workgroups, resident
+                                      for the length of the transfer).  Same results.
+                                      Without the flag only calls of at most 64 MiB go this
+                                      way (lmc_tune "direct_store_below" / "..._retrieve_below"). */
 #define LMC_FLAG_EVICT_LRU 32u     /* a new chunk that finds the pool full takes the slot of
                                       the least recently used chunk that is not pinned, has
                                       no transfer in flight and is not used by the same
@@ -181,7 +183,9 @@ lmc_status_t lmc_lookup(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n,
 
 /* Store (sections 4 and 5.1).  For each of the n_chunks chunks in order: if its id is
  * present it is skipped (first writer wins); otherwise it takes the lowest free pool
- * slot, is gathered from the pages into a staging buffer and copied to that slot.
+ * slot, is gathered from the pages into a staging buffer and copied to that slot (a
+ * call with few new bytes, or any call under LMC_FLAG_DIRECT, is gathered straight into
+ * the slot).
  * slot_mapping: DEVICE int64[n_chunks*chunk_tokens].  chunk_ids: HOST.
  * stream_to_wait_on: a hipStream_t (NULL names the null stream): the library's work is
  * ordered after everything enqueued on it so far (the kernels that produced the KV and
@@ -198,7 +202,8 @@ lmc_status_t lmc_store(lmc_ctx_t *ctx, void *const *kv_layers, const int64_t *sl
 
 /* Retrieve (sections 4 and 5.1).  All n_chunks ids must be present, else LMC_ERR_MISS
  * and no page byte is written.  Each chunk is copied from its pool slot into a staging
- * buffer and scattered into the pages named by slot_mapping (DEVICE
+ * buffer (or, for a small call or under LMC_FLAG_DIRECT, read where it is) and scattered
+ * into the pages named by slot_mapping (DEVICE
  * int64[n_chunks*chunk_tokens]); bytes of the pages that no slot names are not
  * touched.  stream_to_signal: a hipStream_t (NULL names the null stream).  The scatter
  * is ordered after everything enqueued on it so far (earlier users of the pages, the
