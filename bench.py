@@ -10,6 +10,10 @@ configuration (32 layers, K and V, 8 KV heads x 128, bf16, 16-token pages in a p
 Inputs are synthetic and resident in HBM before the timed region.  `value` is payload
 bytes moved (store + retrieve) per second of wall time.
 
+Before the warm-up the benchmark settles: it runs untimed steps until sixty in a row
+reach 90 % of the link rate (see the comment at that loop; `settle` in the JSON says what
+it took).  On a machine in its normal state that is a second.
+
 Also reported in the same JSON line:
   roofline     the gather / scatter kernel launches of the timed steps, timed with HIP
                events on the library's own streams, against the 8 TB/s HBM peak;
@@ -162,6 +166,8 @@ def main():
     ap.add_argument("--staging-chunks", type=int, default=16)
     ap.add_argument("--num-staging", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--settle-seconds", type=float, default=30.0,
+                    help="upper limit for the untimed settling phase before the warm-up (0 = none)")
     ap.add_argument("--legs", default="pipeline,link,device,duplex,direct,layerwise,fragmented,small,cpu",
                     help="comma list of pipeline (always run), link, device, duplex, direct, layerwise, "
                          "fragmented, small, cpu, and configs (every benchmark configuration end to end; "
@@ -220,6 +226,33 @@ def main():
         t = ctx.retrieve(ids, d_load, dst, stream)
         ctx.wait(t)
         ctx.clear(ids)
+
+    # Settle.  For some seconds after tens of GiB of device or pinned memory have been
+    # freed on the host (by this process while it set up, or by the process that had the
+    # GPU before), the runtime's device-to-host copies inside a store run at about half
+    # speed; the state sets in a few steps after the first copies and passes by itself.
+    # It is a state of the machine, not of this path, so steps are run, untimed, for at
+    # least a second and until sixty in a row (more than a second's worth) reach 90 % of
+    # the link rate measured now (a lone copy is not affected), or until the time limit;
+    # what it took is reported.
+    settle = {"steps": 0, "seconds": 0.0, "settled": args.settle_seconds <= 0}
+    if args.settle_seconds > 0:
+        _, d2h_now = ctx.measure_link(256 << 20, reps=2)
+        t_begin, good, slow = time.perf_counter(), 0, 0
+        while time.perf_counter() - t_begin < args.settle_seconds:
+            a = time.perf_counter()
+            step()
+            torch.cuda.synchronize()
+            settle["steps"] += 1
+            if 2 * payload_one_way / (time.perf_counter() - a) / 1e9 >= 0.9 * d2h_now:
+                good += 1
+            else:
+                good, slow = 0, slow + 1
+            if good >= 60 and time.perf_counter() - t_begin >= 1.0:
+                settle["settled"] = True
+                break
+        settle["seconds"] = round(time.perf_counter() - t_begin, 2)
+        settle["slow_steps"] = slow
 
     for _ in range(args.warmup):
         step()
@@ -492,6 +525,7 @@ def main():
                    "payload_bytes_per_step": 2 * payload_one_way, "chunk_bytes": g.chunk_bytes,
                    "staging_chunks": args.staging_chunks, "num_staging": args.num_staging},
         "roofline": roofline,
+        "settle": settle,
     }
     if device:
         out["device"] = device
