@@ -140,11 +140,14 @@ typedef struct {
     uint64_t retrieve_misses;     /* calls refused with LMC_ERR_MISS */
     uint64_t alloc_failures;      /* calls that hit LMC_ERR_NOMEM */
     uint64_t chunks_evicted;      /* LMC_FLAG_EVICT_LRU: chunks that gave up their slot */
+    uint64_t d2h_guard_switches;  /* times the copies to the host went over to the copy kernel */
     uint64_t bytes_gathered, bytes_scattered; /* chunk payload through the kernels */
     uint64_t bytes_d2h, bytes_h2d;            /* chunk payload over the host link */
     uint64_t gather_launches, scatter_launches;
     uint64_t timed_gather_launches, timed_scatter_launches; /* LMC_FLAG_TIMING, completed */
     double gather_ms, scatter_ms;             /* sum of their HIP-event durations */
+    double d2h_copy_best_gbps;    /* best rate seen of a runtime copy to the host of 32 MiB or
+                                     more (what "d2h_guard" compares with); 0 = none seen */
 } lmc_stats_t;
 
 /* Create a context: allocates the pinned host pool, 2*num_staging device staging
@@ -449,6 +452,10 @@ lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *ctx, uint64_t nbytes, int32_t re
  * pool are made by the library's own link-paced copy kernel instead of hipMemcpyAsync;
  * bit 1: copies from the pool to staging too.  2-3 % slower than the runtime's copies,
  * but independent of which engine the runtime picks and of what else that engine is doing),
+ * "d2h_guard" (default 1: the library times the runtime's copies to the host of 32 MiB
+ * and more, and when two in a row fall below three quarters of the best rate it has seen
+ * it makes these copies with its own kernel for 1 s, then tries the runtime again,
+ * doubling the pause up to 8 s while the runtime stays slow; 0 = never),
  * "edge_chunks" (size
  * of the group at the exposed end of a pipeline, 0 = none), "timing" (0/1: switches
  * LMC_FLAG_TIMING), "direct_store_below" / "direct_retrieve_below" (bytes, default 64 MiB

@@ -13,6 +13,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cstdlib>
 #include <cstring>
 #include <deque>
@@ -22,6 +23,7 @@
 #include <vector>
 
 #include "../../include/lmc.h"
+#include "lmc_guard.hpp"
 #include "lmc_index.hpp"
 #include "lmc_kernels.hpp"
 
@@ -59,6 +61,11 @@ struct Timing {
     bool is_gather;
 };
 
+struct CopyTiming {   // a large device-to-host copy by the runtime, watched by the guard
+    hipEvent_t start, stop;
+    uint64_t bytes;
+};
+
 }  // namespace
 
 struct lmc_ctx {
@@ -75,6 +82,12 @@ struct lmc_ctx {
     // copy engines being busy with the driver's own work on that memory); the kernel's
     // 55 GB/s does not depend on that.
     uint32_t copy_kernel = 0;
+    // ... and the guard that switches device-to-host copies to the kernel by itself while
+    // the runtime's are slow (lmc_guard.hpp)
+    bool d2h_guard_on = true;
+    lmc::CopyEngineGuard d2h_guard;
+    std::vector<CopyTiming> copy_timings;
+    std::chrono::steady_clock::time_point born = std::chrono::steady_clock::now();
     int64_t edge_chunks = 1;  // size of the group at the exposed end of a pipeline; 0 = no special group
     uint64_t use_calls = 0;         // number of the latest call that used chunks (recency of use)
     std::vector<uint64_t> evicted;  // LMC_FLAG_EVICT_LRU: ids evicted and not yet drained
@@ -219,9 +232,28 @@ Op *find_op(lmc_ctx *c, uint64_t ticket) {
     return nullptr;
 }
 
+double seconds_now(const lmc_ctx *c) {
+    return std::chrono::duration<double>(std::chrono::steady_clock::now() - c->born).count();
+}
+
 // Finish every operation whose last device step has completed: drop its in-flight
 // counts, collect kernel timings, recycle events.
 void reap(lmc_ctx *c) {
+    for (size_t i = 0; i < c->copy_timings.size();) {
+        CopyTiming &t = c->copy_timings[i];
+        if (hipEventQuery(t.stop) != hipSuccess) {
+            i++;
+            continue;
+        }
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess)
+            c->d2h_guard.observe(t.bytes, double(ms) * 1e-3, seconds_now(c));
+        c->free_time_events.push_back(t.start);
+        c->free_time_events.push_back(t.stop);
+        c->copy_timings.erase(c->copy_timings.begin() + long(i));
+    }
+    c->stats.d2h_guard_switches = c->d2h_guard.switches();
+    c->stats.d2h_copy_best_gbps = c->d2h_guard.best_rate() * 1e-9;
     for (size_t i = 0; i < c->ops.size();) {
         Op &op = c->ops[i];
         const bool finished = op.done != nullptr ? hipEventQuery(op.done) == hipSuccess : !op.pending;
@@ -334,12 +366,15 @@ lmc_status_t copy_group(lmc_ctx *c, bool to_host, uint8_t *staging, uint64_t str
     const uint64_t cb = uint64_t(c->chunk_bytes);
     const hipMemcpyKind kind = to_host ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice;
     if (used_second) *used_second = false;
+    bool watched = false;
     int64_t run = 0;
     for (int64_t j = 0; j < k; run++) {
         int64_t m = 1;
         while (j + m < k && pool_slots[j + m] == pool_slots[j] + m) m++;
         hipStream_t stream = first;
-        const bool by_kernel = ((c->copy_kernel >> (to_host ? 0 : 1)) & 1u) != 0 && c->pool_dev != nullptr &&
+        const bool wanted = ((c->copy_kernel >> (to_host ? 0 : 1)) & 1u) != 0 ||
+                            (to_host && c->d2h_guard_on && c->d2h_guard.use_kernel(seconds_now(c)));
+        const bool by_kernel = wanted && c->pool_dev != nullptr &&
                                ((width | stride | cb | pool_off | reinterpret_cast<uintptr_t>(staging)) % 16) == 0;
         if (by_kernel) {
             // launches follow each other without a gap: one stream is enough
@@ -359,6 +394,18 @@ lmc_status_t copy_group(lmc_ctx *c, bool to_host, uint8_t *staging, uint64_t str
         }
         uint8_t *host = c->pool + uint64_t(pool_slots[j]) * cb + pool_off;
         uint8_t *dev = staging + uint64_t(j) * stride;
+        // one large copy to the host per group is timed for the guard (two markers around
+        // milliseconds of copy; one per group, so that a group of many copies keeps its pace)
+        CopyTiming watch{nullptr, nullptr, uint64_t(m) * width};
+        if (to_host && c->d2h_guard_on && !watched && watch.bytes >= lmc::CopyEngineGuard::kMinBytes &&
+            get_event(c, true, &watch.start) == LMC_OK) {
+            if (get_event(c, true, &watch.stop) != LMC_OK) {
+                c->free_time_events.push_back(watch.start);
+                watch.start = nullptr;
+            } else {
+                HIPCHK(c, hipEventRecord(watch.start, stream));
+            }
+        }
         if (m == 1 || (width == cb && stride == cb)) {
             if (to_host) HIPCHK(c, hipMemcpyAsync(host, dev, size_t(m * width), kind, stream));
             else HIPCHK(c, hipMemcpyAsync(dev, host, size_t(m * width), kind, stream));
@@ -375,6 +422,11 @@ lmc_status_t copy_group(lmc_ctx *c, bool to_host, uint8_t *staging, uint64_t str
             } else {
                 HIPCHK(c, e);
             }
+        }
+        if (watch.start != nullptr) {
+            HIPCHK(c, hipEventRecord(watch.stop, stream));
+            c->copy_timings.push_back(watch);
+            watched = true;
         }
         if (to_host) c->stats.bytes_d2h += uint64_t(m) * width;
         else c->stats.bytes_h2d += uint64_t(m) * width;
@@ -1422,6 +1474,8 @@ lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
     } else if (k == "xcd_run") {
         if (value > (1 << 20)) return LMC_ERR_INVAL;
         c->shape.xcd_run = uint32_t(value);
+    } else if (k == "d2h_guard" && value <= 1) {
+        c->d2h_guard_on = value != 0;
     } else if (k == "copy_kernel" && value <= 3) {
         c->copy_kernel = uint32_t(value);
     } else if (k == "link_groups") {

@@ -1,0 +1,53 @@
+// Watches the rate of the runtime's large device-to-host copies and says when the
+// library's own copy kernel should take over for a while.
+//
+// Why: on the machine this was written on, for seconds after tens of GiB of device or
+// pinned memory had been freed (by this or by the previous process), the runtime's
+// device-to-host copies inside a store ran at 31.5 GB/s instead of 57, on and off, while
+// a copy kernel's rate (55 GB/s) did not change.  When healthy, the runtime's copy is the
+// faster one (and leaves the duplex case alone), so it stays the first choice.
+//
+// Policy: remember the best rate a runtime copy has reached.  Two copies in a row below
+// three quarters of it switch to the kernel for `hold` seconds; then the runtime is tried
+// again, and if it is still slow the hold doubles (1 s ... 8 s); a healthy copy resets it.
+// Plain C++, no HIP: times and rates are passed in.
+#pragma once
+
+#include <algorithm>
+#include <cstdint>
+
+namespace lmc {
+
+class CopyEngineGuard {
+public:
+    static constexpr uint64_t kMinBytes = uint64_t(32) << 20;  // smaller copies are latency, not rate
+
+    // A runtime copy of `bytes` that took `seconds` has been seen finished at time `now` (s).
+    void observe(uint64_t bytes, double seconds, double now) {
+        if (bytes < kMinBytes || seconds <= 0.0) return;
+        const double rate = double(bytes) / seconds;
+        if (rate > best_) best_ = rate;
+        if (rate < 0.75 * best_) {
+            if (++slow_in_row_ >= 2) {
+                kernel_until_ = now + hold_;
+                hold_ = std::min(hold_ * 2.0, 8.0);
+                slow_in_row_ = 0;
+                switches_++;
+            }
+        } else {
+            slow_in_row_ = 0;
+            hold_ = 1.0;
+        }
+    }
+    // Should a copy enqueued at time `now` be made by the kernel?
+    bool use_kernel(double now) const { return now < kernel_until_; }
+    double best_rate() const { return best_; }
+    uint64_t switches() const { return switches_; }
+
+private:
+    double best_ = 0.0, hold_ = 1.0, kernel_until_ = -1.0;
+    int slow_in_row_ = 0;
+    uint64_t switches_ = 0;
+};
+
+}  // namespace lmc
