@@ -148,6 +148,7 @@ typedef struct {
     double gather_ms, scatter_ms;             /* sum of their HIP-event durations */
     double d2h_copy_best_gbps;    /* best rate seen of a runtime copy to the host of 32 MiB or
                                      more (what "d2h_guard" compares with); 0 = none seen */
+    double d2h_copy_last_gbps;    /* rate of the latest such copy */
 } lmc_stats_t;
 
 /* Create a context: allocates the pinned host pool, 2*num_staging device staging
@@ -453,7 +454,7 @@ lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *ctx, uint64_t nbytes, int32_t re
  * bit 1: copies from the pool to staging too.  2-3 % slower than the runtime's copies,
  * but independent of which engine the runtime picks and of what else that engine is doing),
  * "d2h_guard" (default 1: the library times the runtime's copies to the host of 32 MiB
- * and more, and when two in a row fall below three quarters of the best rate it has seen
+ * and more, and when two of the last four fell below three quarters of the best rate it has seen
  * it makes these copies with its own kernel for 1 s, then tries the runtime again,
  * doubling the pause up to 8 s while the runtime stays slow; 0 = never),
  * "edge_chunks" (size

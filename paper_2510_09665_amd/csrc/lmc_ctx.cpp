@@ -254,6 +254,7 @@ void reap(lmc_ctx *c) {
     }
     c->stats.d2h_guard_switches = c->d2h_guard.switches();
     c->stats.d2h_copy_best_gbps = c->d2h_guard.best_rate() * 1e-9;
+    c->stats.d2h_copy_last_gbps = c->d2h_guard.last_rate() * 1e-9;
     for (size_t i = 0; i < c->ops.size();) {
         Op &op = c->ops[i];
         const bool finished = op.done != nullptr ? hipEventQuery(op.done) == hipSuccess : !op.pending;

@@ -7,9 +7,11 @@
 // a copy kernel's rate (55 GB/s) did not change.  When healthy, the runtime's copy is the
 // faster one (and leaves the duplex case alone), so it stays the first choice.
 //
-// Policy: remember the best rate a runtime copy has reached.  Two copies in a row below
-// three quarters of it switch to the kernel for `hold` seconds; then the runtime is tried
-// again, and if it is still slow the hold doubles (1 s ... 8 s); a healthy copy resets it.
+// Policy: remember the best rate a runtime copy has reached.  When two of the last four
+// watched copies were below three quarters of it (in the slow state the small copy at the
+// head of a store stays fast, so slow ones need not be neighbours), the kernel takes over
+// for `hold` seconds; then the runtime is tried again, and if it is slow again at once
+// the hold doubles (1 s ... 8 s); four healthy copies in a row reset it.
 // Plain C++, no HIP: times and rates are passed in.
 #pragma once
 
@@ -26,27 +28,29 @@ public:
     void observe(uint64_t bytes, double seconds, double now) {
         if (bytes < kMinBytes || seconds <= 0.0) return;
         const double rate = double(bytes) / seconds;
+        last_ = rate;
         if (rate > best_) best_ = rate;
-        if (rate < 0.75 * best_) {
-            if (++slow_in_row_ >= 2) {
-                kernel_until_ = now + hold_;
-                hold_ = std::min(hold_ * 2.0, 8.0);
-                slow_in_row_ = 0;
-                switches_++;
-            }
-        } else {
-            slow_in_row_ = 0;
+        history_ = ((history_ << 1) | (rate < 0.75 * best_ ? 1u : 0u)) & 0xFu;
+        if (__builtin_popcount(history_) >= 2) {
+            kernel_until_ = now + hold_;
+            hold_ = std::min(hold_ * 2.0, 8.0);
+            history_ = 0;
+            switches_++;
+        } else if (history_ == 0 && ++healthy_in_row_ >= 4) {
             hold_ = 1.0;
         }
+        if (history_ != 0) healthy_in_row_ = 0;
     }
     // Should a copy enqueued at time `now` be made by the kernel?
     bool use_kernel(double now) const { return now < kernel_until_; }
     double best_rate() const { return best_; }
+    double last_rate() const { return last_; }
     uint64_t switches() const { return switches_; }
 
 private:
-    double best_ = 0.0, hold_ = 1.0, kernel_until_ = -1.0;
-    int slow_in_row_ = 0;
+    double best_ = 0.0, last_ = 0.0, hold_ = 1.0, kernel_until_ = -1.0;
+    unsigned history_ = 0;     // the last four watched copies, one bit each: 1 = slow
+    int healthy_in_row_ = 0;
     uint64_t switches_ = 0;
 };
 

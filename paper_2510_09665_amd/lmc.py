@@ -64,7 +64,7 @@ class lmc_stats_t(ctypes.Structure):
                  "bytes_scattered", "bytes_d2h", "bytes_h2d", "gather_launches",
                  "scatter_launches", "timed_gather_launches", "timed_scatter_launches")] + \
                [("gather_ms", ctypes.c_double), ("scatter_ms", ctypes.c_double),
-                ("d2h_copy_best_gbps", ctypes.c_double)]
+                ("d2h_copy_best_gbps", ctypes.c_double), ("d2h_copy_last_gbps", ctypes.c_double)]
 
 
 class LMCError(RuntimeError):

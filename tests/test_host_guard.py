@@ -54,15 +54,17 @@ def test_healthy_copies_never_switch(lib):
     g.close()
 
 
-def test_two_slow_copies_switch_for_a_second_then_the_runtime_is_tried_again(lib):
+def test_two_slow_copies_of_the_last_four_switch_then_the_runtime_is_tried_again(lib):
     g = Guard(lib)
     g.copy(57.0, 0.00)
     g.copy(31.5, 0.01)                                # one slow copy alone is not enough
     assert not g.kernel(0.011)
-    g.copy(56.5, 0.02)                                # and a healthy one forgets it
+    for i in range(3):
+        g.copy(56.5, 0.02 + 0.001 * i)                # ... and three healthy ones push it out
     g.copy(31.5, 0.03)
     assert not g.kernel(0.031)
-    g.copy(31.5, 0.04)                                # two in a row: kernel for 1 s
+    g.copy(56.0, 0.035)                               # the fast small copy at the head of a store
+    g.copy(31.5, 0.04)                                # second slow one of the last four: kernel for 1 s
     assert g.kernel(0.041) and g.kernel(1.039) and not g.kernel(1.041)
     # the runtime is tried again and is still slow: two probes, then 2 s, then 4, 8, 8
     t = 1.05
@@ -72,9 +74,10 @@ def test_two_slow_copies_switch_for_a_second_then_the_runtime_is_tried_again(lib
         g.copy(31.5, t + 0.02)
         assert g.kernel(t + 0.021) and g.kernel(t + 0.02 + hold - 0.001) and not g.kernel(t + 0.02 + hold + 0.001)
         t += 0.02 + hold + 0.01
-    # healthy again: back to the runtime, and the next episode starts at 1 s again
-    g.copy(56.8, t)
-    assert not g.kernel(t + 0.001)
+    # healthy again for a while: back to the runtime, and the next episode starts at 1 s again
+    for i in range(4):
+        g.copy(56.8, t + 0.01 * i)
+        assert not g.kernel(t + 0.01 * i + 0.001)
     g.copy(30.0, t + 0.1)
     g.copy(30.0, t + 0.2)
     assert g.kernel(t + 0.9) and not g.kernel(t + 1.21)
