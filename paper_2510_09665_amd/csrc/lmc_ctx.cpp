@@ -408,8 +408,8 @@ lmc_status_t copy_group(lmc_ctx *c, bool to_host, uint8_t *staging, uint64_t str
             }
         }
         if (m == 1 || (width == cb && stride == cb)) {
-            if (to_host) HIPCHK(c, hipMemcpyAsync(host, dev, size_t(m * width), kind, stream));
-            else HIPCHK(c, hipMemcpyAsync(dev, host, size_t(m * width), kind, stream));
+            if (to_host) HIPCHK(c, hipMemcpyAsync(host, dev, size_t(uint64_t(m) * width), kind, stream));
+            else HIPCHK(c, hipMemcpyAsync(dev, host, size_t(uint64_t(m) * width), kind, stream));
         } else {
             hipError_t e = to_host ? hipMemcpy2DAsync(host, cb, dev, stride, width, size_t(m), kind, stream)
                                    : hipMemcpy2DAsync(dev, stride, host, cb, width, size_t(m), kind, stream);
@@ -1227,8 +1227,8 @@ lmc_status_t lmc_drain_evicted(lmc_ctx_t *c, uint64_t *ids_out, int64_t cap, int
     if (!c || cap < 0 || !n_out || (cap > 0 && !ids_out)) return LMC_ERR_INVAL;
     std::lock_guard<std::mutex> lock(c->mu);
     const size_t n = std::min(c->evicted.size(), size_t(cap));
-    std::copy(c->evicted.begin(), c->evicted.begin() + n, ids_out);
-    c->evicted.erase(c->evicted.begin(), c->evicted.begin() + n);
+    std::copy(c->evicted.begin(), c->evicted.begin() + long(n), ids_out);
+    c->evicted.erase(c->evicted.begin(), c->evicted.begin() + long(n));
     *n_out = int64_t(n);
     return LMC_OK;
 }

@@ -56,7 +56,7 @@ public:
         if (free_ == 0) return -1;
         int64_t idx = 0;
         for (int lv = int(levels_.size()) - 1; lv >= 0; lv--)
-            idx = idx * 64 + __builtin_ctzll(levels_[lv][size_t(idx)]);
+            idx = idx * 64 + __builtin_ctzll(levels_[size_t(lv)][size_t(idx)]);
         clear_bit(idx);
         free_--;
         return idx;
