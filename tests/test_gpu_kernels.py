@@ -27,6 +27,7 @@ SHAPES = {
     "vec1_pad": dict(L=2, P=1, H=2, D=5, e=1, BS=3, NB=70, CT=24, block_pad=1),
     "bs_not_pow2": dict(L=17, P=2, H=2, D=32, e=2, BS=12, NB=30, CT=48),
     "many_lp": dict(L=37, P=2, H=1, D=64, e=2, BS=16, NB=32, CT=128),
+    "one_token_pages": dict(L=3, P=2, H=8, D=64, e=2, BS=1, NB=4096, CT=64),        # token-granular engines
     "max_layer_planes": dict(L=160, P=2, H=1, D=32, e=2, BS=8, NB=24, CT=32),     # LMC_MAX_LAYERS, K and V
     "blocks_outer": dict(L=4, P=2, H=4, D=64, e=2, BS=16, NB=48, CT=256, order="NP"),
     "blocks_outer_hnd_pad": dict(L=3, P=2, H=3, D=12, e=2, BS=4, NB=64, CT=32, order="NP", layout="HND",
