@@ -103,6 +103,26 @@ def cpu_baseline(g, seq, budget_s=12.0):
     }
 
 
+def kernel_only(torch, ctx, kv, d_slots, n_chunks, staging, stream, iters=4):
+    """Seconds per launch of the gather and of the scatter over n_chunks chunks (HIP events)."""
+    out = []
+    for fn in (lambda: ctx.gather(kv, d_slots, n_chunks, staging, stream),
+               lambda: ctx.scatter(staging, d_slots, n_chunks, kv, stream)):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        best = 1e30
+        for _ in range(3):
+            e0.record(stream)
+            for _ in range(iters):
+                fn()
+            e1.record(stream)
+            e1.synchronize()
+            best = min(best, e0.elapsed_time(e1) / iters * 1e-3)
+        out.append(best)
+    ctx.wait()
+    return out
+
+
 def all_configs(torch, lmc, W, dev, stream, timed):
     """Every benchmark configuration end to end (store, then retrieve into fresh blocks;
     configuration 4: one batched retrieve of the hit chunks of 64 requests, pool slots in
@@ -126,7 +146,16 @@ def all_configs(torch, lmc, W, dev, stream, timed):
         tl = timed(lambda: ctx.wait(ctx.retrieve(ids, d_l, kv, stream)), reps=4)
         nbytes = n * g.chunk_bytes
         h2d, d2h = ctx.measure_link(min(512 << 20, nbytes) // 16 * 16, reps=3)
+        # the kernels alone: the whole request in one launch, HBM to HBM.  Requests smaller
+        # than the 256 MB Infinity Cache are served from it in part, so those are no
+        # measure of HBM (configuration 1 and the fp8 variant of 5).
+        staging = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        kg, ks = kernel_only(torch, ctx, kv, d_s, n, staging, stream)
+        del staging
         res[name] = {"chunks": n, "payload_bytes": nbytes,
+                     "kernel_only_gather_hbm_gbps": round(2 * nbytes / kg / 1e9, 1),
+                     "kernel_only_scatter_hbm_gbps": round(2 * nbytes / ks / 1e9, 1),
+                     "kernel_only_in_cache": nbytes < (512 << 20),
                      "store_gbps": round(nbytes / ts / 1e9, 2), "retrieve_gbps": round(nbytes / tl / 1e9, 2),
                      "store_frac_of_d2h_peak": round(nbytes / ts / 1e9 / d2h, 4),
                      "retrieve_frac_of_h2d_peak": round(nbytes / tl / 1e9 / h2d, 4),
@@ -150,7 +179,12 @@ def all_configs(torch, lmc, W, dev, stream, timed):
     t = timed(lambda: ctx.wait(ctx.retrieve_batch(off, ids_all, d_sl, kv, stream)), reps=3)
     h2d, _ = ctx.measure_link(512 << 20, reps=3)
     nbytes = n_hit * g.chunk_bytes
+    staging = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    kg, ks = kernel_only(torch, ctx, kv, d_sl, n_hit, staging, stream)
+    del staging
     res["batch_8b"] = {"requests": len(reqs), "hit_chunks": n_hit, "payload_bytes": nbytes,
+                       "kernel_only_gather_hbm_gbps": round(2 * nbytes / kg / 1e9, 1),
+                       "kernel_only_scatter_hbm_gbps": round(2 * nbytes / ks / 1e9, 1),
                        "retrieve_batch_gbps": round(nbytes / t / 1e9, 2),
                        "retrieve_frac_of_h2d_peak": round(nbytes / t / 1e9 / h2d, 4),
                        "retrieve_ms": round(t * 1e3, 1)}
