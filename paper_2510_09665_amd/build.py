@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblmc.so")
 SOURCES = ["lmc_kernels.hip", "lmc_ctx.cpp", "lmc_seq.cpp", "lmc_window.cpp", "lmc_tier.cpp"]
-HEADERS = ["lmc_kernels.hpp", "lmc_index.hpp", "lmc_window.hpp", os.path.join("..", "..", "include", "lmc.h")]
+HEADERS = ["lmc_kernels.hpp", "lmc_index.hpp", "lmc_window.hpp", "lmc_guard.hpp", os.path.join("..", "..", "include", "lmc.h")]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
