@@ -30,6 +30,10 @@ Also reported in the same JSON line:
   layerwise    the same request moved layer by layer (rectangle copies + kernels over
                one or four layers), as a fraction of the link peak, and how soon layer 0
                is usable compared with the bulk retrieve
+  overlap_with_compute  retrieve the request while a consumer stream runs a stand-in for 32
+               layers of compute (dense bf16 products, about as long as the transfer):
+               compute alone, after a bulk retrieve, and behind a layer-wise retrieve layer
+               by layer (section 5.2), each through staging and in direct mode
   fragmented_pool  the same request with every other pool slot taken beforehand, so that
                no two of its chunks are neighbours in the pool (one copy per chunk)
   small_request    one 0.5 MiB chunk (configuration 1): microseconds from the call to a
@@ -202,8 +206,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--settle-seconds", type=float, default=30.0,
                     help="upper limit for the untimed settling phase before the warm-up (0 = none)")
-    ap.add_argument("--legs", default="pipeline,link,device,duplex,direct,layerwise,fragmented,small,cpu",
-                    help="comma list of pipeline (always run), link, device, duplex, direct, layerwise, "
+    ap.add_argument("--legs", default="pipeline,link,device,duplex,direct,layerwise,overlap,fragmented,small,cpu",
+                    help="comma list of pipeline (always run), link, device, duplex, direct, layerwise, overlap, "
                          "fragmented, small, cpu, and configs (every benchmark configuration end to end; "
                          "not in the default): the extra measurements to make; profiling runs use a subset")
     ap.add_argument("--tune", action="append", default=[], help="key=value for lmc_tune")
@@ -490,6 +494,78 @@ def main():
             "bulk": round(min(first_layer("bulk") for _ in range(4)), 3)}
         ctx.clear(ids)
 
+    # what layer-wise loading is for (section 5.2): a consumer computes on layer l while
+    # layer l+1 is still on its way.  A dense matrix product stands in for a layer's
+    # compute, sized so that 32 layers take about as long as the transfer.
+    overlap = None
+    if "overlap" in legs:
+        ctx.tune("timing", 0)
+        ids = ctx.hash_chunks(seq["tokens"])
+        ctx.wait(ctx.store(src, d_store, ids, stream))
+        octx = lmc.Context(g, max(n_chunks * g.chunk_bytes, 1 << 30), device=0, flags=lmc.LMC_FLAG_DIRECT)
+        octx.wait(octx.store(src, d_store, ids, stream))
+        # HIP maps streams onto a few hardware queues (GPU_MAX_HW_QUEUES, 4 by default), and a
+        # stream that shares a queue with one of the library's host-to-device copy streams
+        # stands still while such a copy runs.  lmc_probe_stream tells: the consumer is a
+        # stream that shares none; one that does is measured as well, if there is one.
+        candidates = [torch.cuda.Stream() for _ in range(8)]
+        masks = [ctx.probe_stream(c_) & 3 for c_ in candidates]
+        consumer = candidates[masks.index(0)] if 0 in masks else candidates[0]
+        shared = next((c_ for c_, m in zip(candidates, masks) if m), None)
+        dmasks = [octx.probe_stream(c_) & 0x20 for c_ in candidates]      # the direct context's scatter stream
+        dconsumer = candidates[dmasks.index(0)] if 0 in dmasks else candidates[0]
+        staged_consumer = consumer
+        a_mat = torch.randn(4096, 4096, device=dev, dtype=torch.bfloat16)
+        b_mat = torch.randn(4096, 4096, device=dev, dtype=torch.bfloat16)
+        with torch.cuda.stream(consumer):
+            for _ in range(10):
+                torch.mm(a_mat, b_mat)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(consumer)
+            for _ in range(50):
+                torch.mm(a_mat, b_mat)
+            e1.record(consumer)
+        e1.synchronize()
+        t_mm = e0.elapsed_time(e1) / 50                      # ms per product
+        per_layer = max(1, int(round(9.4 / g.L / t_mm)))      # products per layer: ~9.4 ms in all
+
+        def compute(l):
+            for _ in range(per_layer):
+                torch.mm(a_mat, b_mat)
+
+        def run(mode, consumer=None):
+            c = octx if mode.endswith("direct") else ctx
+            consumer = consumer or (dconsumer if mode.endswith("direct") else staged_consumer)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            if mode == "compute_only":
+                t = None
+            elif mode.startswith("layerwise"):
+                t = c.retrieve_layerwise(ids, d_load, dst, 1, stream)
+            else:
+                t = c.retrieve(ids, d_load, dst, consumer)    # the consumer waits for all of it
+            with torch.cuda.stream(consumer):
+                for l in range(g.L):
+                    if t is not None and mode.startswith("layerwise"):
+                        c.wait_layer(t, l, consumer)
+                    compute(l)
+            consumer.synchronize()
+            dt = time.perf_counter() - t0
+            if t is not None:
+                c.wait(t)
+            return dt * 1e3
+        overlap = {"compute_ms_per_layer": round(per_layer * t_mm, 3), "layers": g.L,
+                   "consumer_shares_a_queue_with_h2d_copies": masks[candidates.index(consumer)] != 0,
+                   "streams_probed": len(masks), "streams_sharing": sum(1 for m in masks if m)}
+        for mode in ("compute_only", "bulk", "layerwise", "bulk_direct", "layerwise_direct"):
+            overlap[mode + "_ms"] = round(min(run(mode) for _ in range(4)), 3)
+        if shared is not None:
+            overlap["layerwise_ms_on_a_stream_sharing_a_queue"] = round(
+                min(run("layerwise", shared) for _ in range(4)), 3)
+        octx.destroy()
+        ctx.clear(ids)
+        del a_mat, b_mat
+
     # a pool in which every other slot is taken: no two chunks of the request are
     # neighbours, so every group needs one copy per chunk (two copy streams take turns)
     fragmented = None
@@ -571,6 +647,8 @@ def main():
         out["direct"] = direct
     if layerwise:
         out["layerwise"] = layerwise
+    if overlap:
+        out["overlap_with_compute"] = overlap
     if fragmented:
         out["fragmented_pool"] = fragmented
     if small:

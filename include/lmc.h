@@ -444,6 +444,22 @@ lmc_status_t lmc_copy(lmc_ctx_t *ctx, void *dst_dev, const void *src_dev, uint64
 lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *ctx, uint64_t nbytes, int32_t reps,
                                      double *sum_gbps_out);
 
+/* Would work on `stream` (a hipStream_t of the caller, e.g. the stream its model runs on)
+ * have to wait behind the library's copies?  HIP maps streams onto a few hardware queues
+ * (GPU_MAX_HW_QUEUES, 4 by default) and a queue runs its entries in order, so a stream
+ * that shares a queue with one of the library's copy streams stands still while a copy
+ * of that stream is under way, whatever the streams' own dependencies say: the overlap
+ * of loading with compute (section 5.2) is then lost.  The call enqueues, on each of the
+ * library's streams in turn, a copy of up to 64 MiB that only reads the pool, and right
+ * behind it an independent small kernel on `stream`; bit i of *mask_out (HOST) is set if
+ * that kernel finished only with the copy (bit 0: host-to-device stream, 1: the second
+ * one, 2: device-to-host, 3: the second one; bits 4 and 5: the gather and the scatter
+ * stream, which matter under LMC_FLAG_DIRECT, when link-paced kernels run there for the
+ * length of a transfer).  0 = no sharing: pick such a stream
+ * for compute, or raise GPU_MAX_HW_QUEUES so that every stream has a queue of its own.
+ * Blocks for some milliseconds; waits for the device first.  LMC_ERR_NOMEM, LMC_ERR_HIP. */
+lmc_status_t lmc_probe_stream(lmc_ctx_t *ctx, void *stream, uint32_t *mask_out);
+
 /* Run-time knobs for experiments; the defaults are the measured best.  Keys: "nt_load",
  * "nt_store" (0/1: non-temporal hints on the kernels' streaming accesses), "xcd_run"
  * (consecutive tiles handed to one XCD, 0 = hardware round-robin), "link_groups" (default

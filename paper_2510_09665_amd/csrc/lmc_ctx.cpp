@@ -1399,6 +1399,65 @@ lmc_status_t lmc_measure_link(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, doubl
     return rc;
 }
 
+lmc_status_t lmc_probe_stream(lmc_ctx_t *c, void *stream, uint32_t *mask_out) {
+    if (!c || !mask_out) return LMC_ERR_INVAL;
+    if (!c->has_device) return LMC_ERR_NODEVICE;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    HIPCHK(c, hipDeviceSynchronize());
+    reap(c);
+    const uint64_t pool_bytes = uint64_t(c->n_pool_slots) * uint64_t(c->chunk_bytes);
+    const uint64_t nbytes = std::min<uint64_t>(uint64_t(64) << 20, pool_bytes) / 16 * 16;
+    uint8_t *devbuf = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&devbuf), nbytes + 256);
+    if (e != hipSuccess) {
+        c->last_hip_error = int32_t(e);
+        (void)hipGetLastError();
+        return LMC_ERR_NOMEM;
+    }
+    hipEvent_t a0 = nullptr, a1 = nullptr, k1 = nullptr;
+    lmc_status_t rc = get_event(c, true, &a0);
+    if (rc == LMC_OK) rc = get_event(c, true, &a1);
+    if (rc == LMC_OK) rc = get_event(c, true, &k1);
+    hipStream_t user = static_cast<hipStream_t>(stream);
+    const hipStream_t copy_streams[6] = {c->s_h2d, c->s_h2d2, c->s_d2h, c->s_d2h2, c->s_gather, c->s_scatter};
+    uint32_t mask = 0;
+    for (int i = 0; i < 6 && rc == LMC_OK; i++) {
+        float t_copy = 0.f, t_kernel = 0.f;
+        for (int pass = 0; pass < 2 && rc == LMC_OK; pass++) {  // the first pass warms up
+            // a copy that only reads the pool, and right behind it, on the caller's stream,
+            // a kernel that depends on nothing: does it have to wait for the copy?
+            const hipError_t steps[] = {
+                hipEventRecord(a0, copy_streams[i]),
+                // (on the two kernel streams: the link-paced kernel that direct mode runs there)
+                i < 4 ? hipMemcpyAsync(devbuf, c->pool, nbytes, hipMemcpyHostToDevice, copy_streams[i])
+                      : lmc::launch_copy_rect(devbuf, nbytes, c->pool_dev, nbytes, nbytes, 1,
+                                              c->link_groups ? c->link_groups : 64u, copy_streams[i]),
+                hipEventRecord(a1, copy_streams[i]),
+                lmc::launch_fill(devbuf + nbytes, 0, 256, user),
+                hipEventRecord(k1, user),
+                hipEventSynchronize(a1),
+                hipEventSynchronize(k1),
+                hipEventElapsedTime(&t_copy, a0, a1),
+                hipEventElapsedTime(&t_kernel, a0, k1),
+            };
+            for (hipError_t x : steps)
+                if (x != hipSuccess) {
+                    c->last_hip_error = int32_t(x);
+                    (void)hipGetLastError();
+                    rc = LMC_ERR_HIP;
+                }
+        }
+        if (rc == LMC_OK && t_kernel > 0.5f * t_copy) mask |= 1u << i;
+    }
+    for (hipEvent_t ev : {a0, a1, k1})
+        if (ev) c->free_time_events.push_back(ev);
+    (void)hipDeviceSynchronize();
+    (void)hipFree(devbuf);
+    *mask_out = mask;
+    return rc;
+}
+
 lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, double *gbps_out) {
     if (!c || !gbps_out || reps < 1 || nbytes == 0) return LMC_ERR_INVAL;
     if (!c->has_device) return LMC_ERR_NODEVICE;

@@ -34,7 +34,7 @@ EXPORTS = [
     "lmc_store_begin", "lmc_store_layers", "lmc_wait_layer", "lmc_wait", "lmc_gather",
     "lmc_scatter", "lmc_put_host", "lmc_get_host", "lmc_find_slot", "lmc_pin", "lmc_unpin",
     "lmc_clear", "lmc_drain_evicted", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_measure_link_duplex",
-    "lmc_copy", "lmc_tune", "lmc_chunk_acquire", "lmc_chunk_release", "lmc_tier_open", "lmc_tier_close",
+    "lmc_copy", "lmc_tune", "lmc_probe_stream", "lmc_chunk_acquire", "lmc_chunk_release", "lmc_tier_open", "lmc_tier_close",
     "lmc_tier_write", "lmc_tier_wait", "lmc_tier_lookup", "lmc_tier_read", "lmc_tier_errno",
     "lmc_tier_get_stats",
     "lmc_strerror", "lmc_last_hip_error",
@@ -114,6 +114,7 @@ def _lib():
             "lmc_window_offload": (st, [vp, vp, vp, ctypes.POINTER(i64)]),
             "lmc_window_acquire": (st, [vp, i64, vp, i32]),
             "lmc_window_get": (st, [vp] + [ctypes.POINTER(i64)] * 4 + [ctypes.POINTER(i32)]),
+            "lmc_probe_stream": (st, [vp, vp, ctypes.POINTER(ctypes.c_uint32)]),
             "lmc_chunk_acquire": (st, [vp, u64, ctypes.POINTER(vp)]),
             "lmc_chunk_release": (st, [vp, u64]),
             "lmc_tier_open": (st, [vp, ctypes.POINTER(ctypes.c_char_p), i32, i32, ctypes.POINTER(vp)]),
@@ -427,6 +428,13 @@ class Context:
     def copy(self, dst_dev, src_dev, nbytes, stream=None):
         self._check(_lib().lmc_copy(self._h, _dev(dst_dev), _dev(src_dev), nbytes, _stream(stream)),
                     "lmc_copy")
+
+    def probe_stream(self, stream):
+        """Bit mask of the library's copy streams that share a hardware queue with `stream`
+        (0 = work on it never waits behind the library's copies)."""
+        m = ctypes.c_uint32()
+        self._check(_lib().lmc_probe_stream(self._h, _stream(stream), ctypes.byref(m)), "lmc_probe_stream")
+        return m.value
 
     def tune(self, key, value):
         self._check(_lib().lmc_tune(self._h, key.encode(), int(value)), "lmc_tune")

@@ -256,3 +256,34 @@ def test_bulk_and_layerwise_calls_share_the_rings_safely(bulk_staged):
                 oracle.scatter_chunk(d.gc, ch, s, d.host)
             assert_layers_equal(d.device_blocks_to_host(), d.host)
             assert d.untracked_blocks_untouched()
+
+
+def test_probe_stream_reports_queue_sharing_consistently():
+    """lmc_probe_stream: which of the library's streams a caller's stream shares a hardware
+    queue with.  What the answer is depends on the machine's queue count; it must be a
+    valid mask, the same when asked twice, and the library must work as before afterwards."""
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    from paper_2510_09665_amd import lmc
+    g = W.geometry("llama3_8b", L=4, NB=1024)
+    seq = W.sequence("llama3_8b", g, n_tokens=20 * g.CT)            # 80 MiB: more than the probe's copy
+    rng = W.rng_for("llama3_8b", stream=5)
+    src = PagedKV(g, seq["store_blocks"], rng)
+    dst = PagedKV(g, seq["load_blocks"], fill="sentinel")
+    stream = torch.cuda.current_stream()
+    with lmc.Context(g, 20 * g.chunk_bytes, staging_chunks=4) as c:
+        ids = c.hash_chunks(seq["tokens"])
+        d_s, d_l = slots_to_device(seq["store_slots"]), slots_to_device(seq["load_slots"])
+        t = c.store(src.dev, d_s, ids, stream)                       # in flight while the probe starts: it waits
+        streams = [torch.cuda.Stream() for _ in range(6)]
+        first = [c.probe_stream(s) for s in streams]
+        again = [c.probe_stream(s) for s in streams]
+        assert first == again and all(0 <= m < 64 for m in first)
+        c.wait(t)
+        want = oracle.gather(src.gc, src.host, src.compact_slots(seq["store_slots"]))
+        for k, i in enumerate(ids.tolist()):                        # the probe only read the pool
+            assert np.array_equal(c.get_host(i), want[k]), k
+        c.wait(c.retrieve(ids, d_l, dst.dev, streams[0]))
+        torch.cuda.synchronize()
+        oracle.scatter(dst.gc, want, dst.compact_slots(seq["load_slots"]), dst.host)
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host)
