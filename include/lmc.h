@@ -141,6 +141,7 @@ typedef struct {
     uint64_t alloc_failures;      /* calls that hit LMC_ERR_NOMEM */
     uint64_t chunks_evicted;      /* LMC_FLAG_EVICT_LRU: chunks that gave up their slot */
     uint64_t d2h_guard_switches;  /* times the copies to the host went over to the copy kernel */
+    uint64_t d2h_guard_active;    /* 1 while they are with the copy kernel, else 0 */
     uint64_t bytes_gathered, bytes_scattered; /* chunk payload through the kernels */
     uint64_t bytes_d2h, bytes_h2d;            /* chunk payload over the host link */
     uint64_t gather_launches, scatter_launches;

@@ -253,6 +253,7 @@ void reap(lmc_ctx *c) {
         c->copy_timings.erase(c->copy_timings.begin() + long(i));
     }
     c->stats.d2h_guard_switches = c->d2h_guard.switches();
+    c->stats.d2h_guard_active = (c->d2h_guard_on && c->d2h_guard.use_kernel(seconds_now(c))) ? 1 : 0;
     c->stats.d2h_copy_best_gbps = c->d2h_guard.best_rate() * 1e-9;
     c->stats.d2h_copy_last_gbps = c->d2h_guard.last_rate() * 1e-9;
     for (size_t i = 0; i < c->ops.size();) {

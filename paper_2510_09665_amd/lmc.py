@@ -59,7 +59,7 @@ class lmc_config_t(ctypes.Structure):
 class lmc_stats_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint64) for n in
                 ("pool_slots_total", "pool_slots_used", "chunks_stored", "chunks_skipped_dup",
-                 "chunks_retrieved", "retrieve_misses", "alloc_failures", "chunks_evicted", "d2h_guard_switches",
+                 "chunks_retrieved", "retrieve_misses", "alloc_failures", "chunks_evicted", "d2h_guard_switches", "d2h_guard_active",
                  "bytes_gathered",
                  "bytes_scattered", "bytes_d2h", "bytes_h2d", "gather_launches",
                  "scatter_launches", "timed_gather_launches", "timed_scatter_launches")] + \

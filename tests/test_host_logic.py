@@ -28,7 +28,7 @@ def test_struct_sizes_match_the_header_layout():
     import ctypes
     assert ctypes.sizeof(lmc.lmc_kv_geom_t) == 8 * 4 + 4 * 8
     assert ctypes.sizeof(lmc.lmc_config_t) == 64 + 8 + 4 * 4 + 8
-    assert ctypes.sizeof(lmc.lmc_stats_t) == 21 * 8
+    assert ctypes.sizeof(lmc.lmc_stats_t) == 22 * 8
 
 
 def _ctx(g, n_slots, **kw):
