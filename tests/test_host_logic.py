@@ -24,6 +24,17 @@ def test_library_exports_every_declared_symbol():
         assert getattr(lib, name) is not None
 
 
+def test_header_is_plain_c(tmp_path):
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "t.c"
+    src.write_text('#include "lmc.h"\nint main(void) { lmc_stats_t s; (void)s; return LMC_OK; }\n')
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                           "-I", os.path.join(ROOT, "include"), str(src)])
+
+
 def test_struct_sizes_match_the_header_layout():
     import ctypes
     assert ctypes.sizeof(lmc.lmc_kv_geom_t) == 8 * 4 + 4 * 8
