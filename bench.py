@@ -33,7 +33,8 @@ Also reported in the same JSON line:
   overlap_with_compute  retrieve the request while a consumer stream runs a stand-in for 32
                layers of compute (dense bf16 products, about as long as the transfer):
                compute alone, after a bulk retrieve, and behind a layer-wise retrieve layer
-               by layer (section 5.2), each through staging and in direct mode
+               by layer (section 5.2), each through staging and in direct mode; and the
+               store side: compute then bulk store, against layers stored as they are computed
   fragmented_pool  the same request with every other pool slot taken beforehand, so that
                no two of its chunks are neighbours in the pool (one copy per chunk)
   small_request    one 0.5 MiB chunk (configuration 1): microseconds from the call to a
@@ -570,6 +571,31 @@ def main():
         if shared is not None:
             overlap["layerwise_ms_on_a_stream_sharing_a_queue"] = round(
                 min(run("layerwise", shared) for _ in range(4)), 3)
+        # the store side of the same idea: a producer computes layer l and hands it to
+        # lmc_store_layers while it goes on with layer l+1; against computing all layers
+        # first and storing in bulk afterwards
+        full = [ctx.probe_stream(c_) for c_ in candidates]
+        producer = next((c_ for c_, m in zip(candidates, full) if (m & 0xC) == 0), candidates[0])
+
+        def run_store(mode):
+            ctx.clear(ids)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            with torch.cuda.stream(producer):
+                if mode == "layerwise":
+                    t = ctx.store_begin(d_store, ids, producer)
+                    for l in range(g.L):
+                        compute(l)
+                        ctx.store_layers(t, l, 1, src, producer)
+                else:
+                    for l in range(g.L):
+                        compute(l)
+                    t = ctx.store(src, d_store, ids, producer)
+            ctx.wait(t)
+            producer.synchronize()
+            return (time.perf_counter() - t0) * 1e3
+        overlap["compute_then_bulk_store_ms"] = round(min(run_store("bulk") for _ in range(4)), 3)
+        overlap["compute_with_layerwise_store_ms"] = round(min(run_store("layerwise") for _ in range(4)), 3)
         octx.destroy()
         ctx.clear(ids)
         del a_mat, b_mat
