@@ -518,7 +518,7 @@ def main():
         # stands still while such a copy runs.  lmc_probe_stream tells: the consumer is a
         # stream that shares none; one that does is measured as well, if there is one.
         candidates = [torch.cuda.Stream() for _ in range(8)]
-        masks = [ctx.probe_stream(c_) & 3 for c_ in candidates]
+        masks = [ctx.probe_stream(c_) & 0x23 for c_ in candidates]      # both H2D streams and the scatter stream
         consumer = candidates[masks.index(0)] if 0 in masks else candidates[0]
         shared = next((c_ for c_, m in zip(candidates, masks) if m), None)
         dmasks = [octx.probe_stream(c_) & 0x20 for c_ in candidates]      # the direct context's scatter stream
@@ -564,7 +564,7 @@ def main():
                 c.wait(t)
             return dt * 1e3
         overlap = {"compute_ms_per_layer": round(per_layer * t_mm, 3), "layers": g.L,
-                   "consumer_shares_a_queue_with_h2d_copies": masks[candidates.index(consumer)] != 0,
+                   "consumer_shares_a_queue_with_the_retrieve_streams": masks[candidates.index(consumer)] != 0,
                    "streams_probed": len(masks), "streams_sharing": sum(1 for m in masks if m)}
         for mode in ("compute_only", "bulk", "layerwise", "bulk_direct", "layerwise_direct"):
             overlap[mode + "_ms"] = round(min(run(mode) for _ in range(4)), 3)
@@ -575,7 +575,7 @@ def main():
         # lmc_store_layers while it goes on with layer l+1; against computing all layers
         # first and storing in bulk afterwards
         full = [ctx.probe_stream(c_) for c_ in candidates]
-        producer = next((c_ for c_, m in zip(candidates, full) if (m & 0xC) == 0), candidates[0])
+        producer = next((c_ for c_, m in zip(candidates, full) if (m & 0x1C) == 0), candidates[0])
 
         def run_store(mode):
             ctx.clear(ids)

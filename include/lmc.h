@@ -455,8 +455,11 @@ lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *ctx, uint64_t nbytes, int32_t re
  * behind it an independent small kernel on `stream`; bit i of *mask_out (HOST) is set if
  * that kernel finished only with the copy (bit 0: host-to-device stream, 1: the second
  * one, 2: device-to-host, 3: the second one; bits 4 and 5: the gather and the scatter
- * stream, which matter under LMC_FLAG_DIRECT, when link-paced kernels run there for the
- * length of a transfer).  0 = no sharing: pick such a stream
+ * stream.  Those two count as well: the scatter stream's entries wait for the copies of a
+ * retrieve and the gather stream's for those of a store, and under LMC_FLAG_DIRECT the
+ * link-paced kernels run there for the length of a transfer.  A stream overlaps with
+ * retrieves if bits 0, 1 and 5 are clear, with stores if bits 2, 3 and 4 are).
+ * 0 = no sharing: pick such a stream
  * for compute, or raise GPU_MAX_HW_QUEUES so that every stream has a queue of its own.
  * Blocks for some milliseconds; waits for the device first.  LMC_ERR_NOMEM, LMC_ERR_HIP. */
 lmc_status_t lmc_probe_stream(lmc_ctx_t *ctx, void *stream, uint32_t *mask_out);
