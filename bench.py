@@ -1,47 +1,38 @@
 #!/usr/bin/env python3
 """Benchmark of the KV store / retrieve path on one MI355X.
 
-One step is one pass of the whole path over one request of the Llama-3-8B-shaped
-configuration (32 layers, K and V, 8 KV heads x 128, bf16, 16-token pages in a pool of
-8192 blocks; a 4096-token prefix = 16 chunks of 256 tokens = 512 MiB of KV):
-  hash the tokens -> prefix lookup -> store every chunk (gather kernel + D2H per group,
-  pipelined) -> wait -> prefix lookup -> retrieve every chunk into freshly permuted
-  blocks (H2D + scatter kernel, pipelined) -> wait -> clear the chunks.
+Headline workload: the largest single-GPU configuration, the Llama-3-70B-shaped KV cache
+(80 layers, K and V, 8 KV heads x 128, bf16, 16-token pages, 8192 blocks = 40 GiB of
+pages) with one 32768-token context = 128 chunks of 256 tokens = 10 GiB.  One step is one
+pass of the whole path over that request:
+  hash the tokens -> prefix lookup -> store every chunk (gather kernel + D2H per group of
+  chunks, pipelined over two staging buffers) -> wait -> prefix lookup -> retrieve every
+  chunk into freshly permuted blocks (H2D + scatter kernel, pipelined) -> wait -> clear.
 Inputs are synthetic and resident in HBM before the timed region.  `value` is payload
 bytes moved (store + retrieve) per second of wall time.
 
-Before the warm-up the benchmark settles: it runs untimed steps until 150 in a row reach
-90 % of the link rate (see the comment at that loop; `settle` in the JSON says what it
-took).  On a machine in its normal state that is three seconds.
+The run goes: `first_steps` untimed-as-warm-up but measured steps right after set-up (the
+rate a cold process sees), then untimed steps until the machine has settled (see the
+comment at that loop), the warm-up, the timed steps.  Both rates are in the JSON line.
 
 Also reported in the same JSON line:
-  roofline     the gather / scatter kernel launches of the timed steps, timed with HIP
-               events on the library's own streams, against the 8 TB/s HBM peak;
-               algorithmic bytes = 2 x chunk bytes per chunk (each byte read once and
-               written once)
-  device       both kernels alone over all 16 chunks in one launch, sources rotated so
-               the working set exceeds the 256 MB Infinity Cache, and a plain copy
-               kernel of the same size as the achievable ceiling
-  link         hipMemcpyAsync peak between the pinned pool and the GPU per direction,
-               and store / retrieve payload rate as a fraction of it
-  duplex       a store and a retrieve of different requests running at the same time,
-               against the link's measured two-way peak
-  direct       the variant without staging: the kernels read / write the pinned pool
-  layerwise    the same request moved layer by layer (rectangle copies + kernels over
-               one or four layers), as a fraction of the link peak, and how soon layer 0
-               is usable compared with the bulk retrieve
-  overlap_with_compute  retrieve the request while a consumer stream runs a stand-in for 32
-               layers of compute (dense bf16 products, about as long as the transfer):
-               compute alone, after a bulk retrieve, and behind a layer-wise retrieve layer
-               by layer (section 5.2), each through staging and in direct mode; and the
-               store side: compute then bulk store, against layers stored as they are computed
-  fragmented_pool  the same request with every other pool slot taken beforehand, so that
-               no two of its chunks are neighbours in the pool (one copy per chunk)
-  small_request    one 0.5 MiB chunk (configuration 1): microseconds from the call to a
-               finished lmc_wait, through the staging ring and by the library's size rule
-  cpu_baseline the CPU oracle doing the same store + retrieve on the same 16 chunks,
-               chunks fanned out over host threads
-  configs      (only with --legs ...,configs) every benchmark configuration end to end
+  roofline     the gather / scatter launches of the timed steps, timed with HIP events
+               bound to the launches on the library's own streams, against the 8 TB/s HBM
+               peak; algorithmic bytes = 2 x chunk bytes per chunk (each byte read once
+               and written once)
+  link         the link's peak per direction: the best over 64 MiB .. 1 GiB of the
+               runtime's hipMemcpyAsync and of the library's link-paced copy kernel; store
+               and retrieve payload rate as a fraction of it
+  device       both kernels alone over the whole request in one launch (10 GiB, far
+               beyond the 256 MB Infinity Cache), and a plain copy kernel of the same
+               size as the achievable ceiling
+  configs      every other benchmark configuration end to end (1 tiny, 2 Llama-3-8B,
+               4 batched multi-request retrieve, 5 MLA in bf16 and fp8): store / retrieve
+               as a fraction of the link peak and the kernels alone as a fraction of 8 TB/s
+  duplex, direct, layerwise, overlap_with_compute, fragmented_pool, small_request
+               the other modes of the path on the Llama-3-8B shape (16 chunks, 512 MiB)
+  cpu_baseline the CPU oracle doing the same store + retrieve on a stated sample, chunks
+               dealt out to plain threads
 """
 import argparse
 import json
@@ -57,69 +48,141 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published
 # HBM bytes per algorithmic byte of a gather / scatter launch, from rocprofv3 --pmc
-# FETCH_SIZE and WRITE_SIZE of this benchmark's device leg, each calibrated on the plain
-# copy kernel (profiles/move_rows_llama3_8b_device_leg.md): counters cannot be read from
-# inside this process, so the measured ratio is applied to the launch size.
+# FETCH_SIZE and WRITE_SIZE, each calibrated on the plain copy kernel (profiles/): counters
+# cannot be read from inside this process, so the measured ratio is applied to the launch
+# size and the JSON says so.
 PMC_TRAFFIC_RATIO = 1.0001
-WORKLOAD = "llama3_8b"
+WORKLOAD = "llama3_70b"          # the headline: the largest single-GPU configuration
+SECONDARY = "llama3_8b"          # the shape the mode legs (duplex, direct, layer-wise, ...) run on
+WORKLOAD_TEXT = ("Llama-3-70B-shaped KV on one GPU: 80 layers, 8 KV heads, head_dim 128, bf16, block_size 16, "
+                 "pool of 8192 blocks (40 GiB of pages); one 32768-token context = 128 chunks of 256 tokens "
+                 "= 10 GiB stored to and retrieved from pinned host memory into freshly permuted blocks, "
+                 "gather/D2H and H2D/scatter pipelined over two staging buffers")
 
 
-def cpu_baseline(g, seq, budget_s=12.0):
-    """The oracle, as it stands, doing store (gather into a pool) and retrieve (scatter
-    from the pool) for the request's 16 chunks; chunks spread over threads."""
+def affinity_cpus():
+    return len(os.sched_getaffinity(0))
+
+
+def cpu_baseline(budget_s=20.0):
+    """The oracle, as it stands, on a bounded sample: the first 16 chunks of the headline
+    request (and, beside it, the 16 chunks of the Llama-3-8B request).  Store analogue =
+    oracle gather_chunk into a buffer + memcpy into a pool, retrieve analogue = memcpy out
+    of the pool + oracle scatter_chunk; chunks dealt out to plain threads by
+    oracle/oracle_timing.c, every buffer allocated and touched before the clock starts."""
     import dataclasses
     from concurrent.futures import ThreadPoolExecutor
     import oracle
     from paper_2510_09665_amd import workloads as W
-    rng = W.rng_for(WORKLOAD, stream=7)
-    nb = seq["store_blocks"].size
-    gc = dataclasses.replace(g, NB=nb)                      # only the touched blocks
-    src = [W.payload_bytes(rng, g, gc.layer_bytes) for _ in range(g.L)]
-    dst = [np.zeros(gc.layer_bytes, dtype=np.uint8) for _ in range(g.L)]
-    n_chunks = seq["tokens"].size // g.CT
-    t = np.arange(n_chunks * g.CT, dtype=np.int64)          # block i of the request = compact block i
-    s_slots = t.reshape(n_chunks, g.CT)
-    d_slots = t[::-1].copy().reshape(n_chunks, g.CT)
-    pool = [None] * n_chunks
-
-    def one(i):
-        pool[i] = oracle.gather_chunk(gc, src, s_slots[i])
-        oracle.scatter_chunk(gc, pool[i], d_slots[i], dst)
-
-    cores = max(1, min(len(os.sched_getaffinity(0)), 16))
-    payload = 2 * n_chunks * g.chunk_bytes
+    n_aff = affinity_cpus()
+    n_thr = max(1, min(n_aff, 16))          # the GPU box gives one GPU's job 16 CPUs
     out = {}
-    for label, n_thr in (("single", 1), ("all", cores)):
-        reps, t0 = 0, time.perf_counter()
+    for name, n_chunks in ((WORKLOAD, 16), (SECONDARY, 16)):
+        g = W.geometry(name)
+        nb = n_chunks * g.CT // g.BS
+        gc = dataclasses.replace(g, NB=nb)                      # only the touched blocks
         with ThreadPoolExecutor(n_thr) as ex:
+            src = list(ex.map(lambda r: W.payload_bytes(r, g, gc.layer_bytes), W.rng_for(name, stream=7).spawn(g.L)))
+        dst = [np.zeros(gc.layer_bytes, dtype=np.uint8) for _ in range(g.L)]
+        blocks = W.rng_for(name, stream=8).permutation(nb)      # pages in random order, as on the GPU
+        s_slots = W.slots_from_blocks(gc, blocks, n_chunks * g.CT)
+        l_slots = W.slots_from_blocks(gc, blocks[::-1].copy(), n_chunks * g.CT)
+        pool = np.zeros(n_chunks * g.chunk_bytes, dtype=np.uint8)
+        res = {}
+        for label, t in (("single_thread", 1), ("all_threads", n_thr)):
+            buffers = np.zeros(t * g.chunk_bytes, dtype=np.uint8)
+            best_s, best_l, t0 = 1e30, 1e30, time.perf_counter()
             while True:
-                list(ex.map(one, range(n_chunks)))
-                reps += 1
-                dt = time.perf_counter() - t0
-                if dt > budget_s / 2:
+                best_s = min(best_s, oracle.time_pass(gc, src, dst, s_slots, l_slots, pool, buffers, t, False))
+                best_l = min(best_l, oracle.time_pass(gc, src, dst, s_slots, l_slots, pool, buffers, t, True))
+                if time.perf_counter() - t0 > budget_s / 4:
                     break
-        out[label] = payload * reps / dt / 1e9
+            nbytes = n_chunks * g.chunk_bytes
+            res[label] = {"threads": t, "store_gbps": round(nbytes / best_s / 1e9, 3),
+                          "retrieve_gbps": round(nbytes / best_l / 1e9, 3),
+                          "store_plus_retrieve_gbps": round(2 * nbytes / (best_s + best_l) / 1e9, 3)}
+        out[name] = res
+        del src, dst, pool
+    head = out[WORKLOAD]
     return {
-        "value": round(out["all"], 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
-        "single_thread_value": round(out["single"], 3),
-        "sample": "the same 16 chunks (512 MiB) stored and retrieved by oracle gather_chunk + "
-                  "scatter_chunk, one chunk per task on a thread pool, repeated for about 6 s per "
-                  "thread count; payload bytes / wall time",
+        "value": head["all_threads"]["store_plus_retrieve_gbps"], "unit": "GB/s",
+        "cores": n_thr, "affinity_cpus": n_aff, "kind": "oracle",
+        "single_thread_value": head["single_thread"]["store_plus_retrieve_gbps"],
+        "sample": "the first 16 of the headline request's 128 chunks (1.25 GiB of the Llama-3-70B shape; a rate, "
+                  "so no scaling is needed): oracle gather_chunk + memcpy to a pool, then memcpy from the pool + "
+                  "oracle scatter_chunk, pages in seeded random order, chunks dealt out to plain threads "
+                  "(oracle/oracle_timing.c), best pass of about 5 s per thread count; payload bytes / wall time",
+        "llama3_70b_first_16_chunks": head, "llama3_8b_16_chunks": out[SECONDARY],
     }
 
 
-def kernel_only(torch, ctx, kv, d_slots, n_chunks, staging, stream, iters=4):
-    """Seconds per launch of the gather and of the scatter over n_chunks chunks (HIP events)."""
+def make_pages(torch, W, g, blocks, dev, seed):
+    """Paged KV resident in HBM: bf16 uniform(-1, 1) in the listed blocks, zeros elsewhere;
+    and an all-zero destination of the same shape."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    src, dst = [], []
+    sb = torch.from_numpy(np.asarray(blocks)).to(dev)
+    for _ in range(g.L):
+        a = torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev)
+        if g.e == 2:
+            r = (torch.rand((g.P, sb.numel(), g.page_bytes // 2), device=dev, generator=gen) * 2 - 1) \
+                .to(torch.bfloat16).view(torch.uint8)
+        else:
+            r = torch.randint(0, 127, (g.P, sb.numel(), g.page_bytes), device=dev, generator=gen, dtype=torch.uint8)
+        a.view(g.P, g.NB, g.page_bytes)[:, sb] = r.view(g.P, sb.numel(), g.page_bytes)
+        src.append(a)
+        dst.append(torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev))
+    return src, dst
+
+
+def link_peaks(ctx, pool_bytes):
+    """The link's peak per direction: the best rate over transfer sizes 64 MiB .. 1 GiB of
+    the runtime's hipMemcpyAsync and of the library's link-paced copy kernel between the
+    pinned pool and HBM; and the two-way peak (one copy each way at once) over the sizes."""
+    best = {"h2d": (0.0, ""), "d2h": (0.0, "")}
+    for mib in (64, 256, 512, 1024):
+        n = mib << 20
+        if n > pool_bytes:
+            continue
+        for how, fn in (("hipMemcpyAsync", ctx.measure_link), ("copy kernel", ctx.measure_link_kernel)):
+            h, d = fn(n, reps=4)
+            if h > best["h2d"][0]:
+                best["h2d"] = (h, "%s, %d MiB" % (how, mib))
+            if d > best["d2h"][0]:
+                best["d2h"] = (d, "%s, %d MiB" % (how, mib))
+    duplex = 0.0
+    for mib in (256, 512, 1024):
+        if 2 * (mib << 20) <= pool_bytes:
+            duplex = max(duplex, ctx.measure_link_duplex(mib << 20, reps=5))
+    return {"h2d_peak_gbps": best["h2d"][0], "h2d_peak_from": best["h2d"][1],
+            "d2h_peak_gbps": best["d2h"][0], "d2h_peak_from": best["d2h"][1],
+            "duplex_peak_gbps": duplex}
+
+
+def kernel_only(torch, ctx, W, name, g, kv, n_chunks, dev, stream, slots=None, iters=6, reps=3):
+    """Seconds per launch of the gather, the scatter and a plain copy of the same size over
+    the whole request in one launch (HIP events on `stream`).  Requests below 2 GiB rotate
+    over four block sets and four staging buffers, so that nothing is served from the
+    256 MB Infinity Cache."""
+    nbytes = n_chunks * g.chunk_bytes
+    n_rot = 1 if nbytes >= (2 << 30) else 4
+    if slots is None:
+        slots = [torch.from_numpy(W.sequence(name, g, stream=10 + r)["store_slots"]).to(dev) for r in range(n_rot)]
+    stagings = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(n_rot)]
+    spare = torch.empty(nbytes, dtype=torch.uint8, device=dev) if n_rot == 1 else None
     out = []
-    for fn in (lambda: ctx.gather(kv, d_slots, n_chunks, staging, stream),
-               lambda: ctx.scatter(staging, d_slots, n_chunks, kv, stream)):
-        fn()
+    for fn in (lambda r: ctx.gather(kv, slots[r % len(slots)], n_chunks, stagings[r], stream),
+               lambda r: ctx.scatter(stagings[r], slots[r % len(slots)], n_chunks, kv, stream),
+               lambda r: ctx.copy(stagings[(r + 1) % n_rot] if n_rot > 1 else spare, stagings[r], nbytes // 16 * 16, stream)):
+        for r in range(n_rot):
+            fn(r)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         best = 1e30
-        for _ in range(3):
+        for _ in range(reps):
             e0.record(stream)
-            for _ in range(iters):
-                fn()
+            for i in range(iters):
+                fn(i % n_rot)
             e1.record(stream)
             e1.synchronize()
             best = min(best, e0.elapsed_time(e1) / iters * 1e-3)
@@ -128,295 +191,100 @@ def kernel_only(torch, ctx, kv, d_slots, n_chunks, staging, stream, iters=4):
     return out
 
 
-def all_configs(torch, lmc, W, dev, stream, timed):
-    """Every benchmark configuration end to end (store, then retrieve into fresh blocks;
-    configuration 4: one batched retrieve of the hit chunks of 64 requests, pool slots in
-    shuffled order), each as a fraction of the link peak measured in the same context."""
+def kernel_report(nbytes, tg, ts, tc):
+    f = lambda t: round(2 * nbytes / t / 1e9, 1)
+    return {"bytes_per_launch": 2 * nbytes,
+            "gather_hbm_gbps": f(tg), "scatter_hbm_gbps": f(ts), "copy_kernel_hbm_gbps": f(tc),
+            "gather_frac_of_hbm_peak": round(f(tg) / HBM_PEAK_GBPS, 4),
+            "scatter_frac_of_hbm_peak": round(f(ts) / HBM_PEAK_GBPS, 4),
+            "copy_kernel_frac_of_hbm_peak": round(f(tc) / HBM_PEAK_GBPS, 4)}
+
+
+def other_configs(torch, lmc, W, dev, stream, timed, peaks):
+    """Every benchmark configuration but the headline, end to end (store, then retrieve
+    into fresh blocks; configuration 4: one batched retrieve of the hit chunks of 64
+    requests, pool slots in shuffled order), each as a fraction of the link peak, and both
+    kernels alone over the whole request as a fraction of the 8 TB/s HBM peak."""
     res = {}
-    for name, staging in (("tiny", 1), ("llama3_8b", 16), ("llama3_70b", 8), ("mla_bf16", 32), ("mla_fp8", 32)):
+    h2d, d2h = peaks["h2d_peak_gbps"], peaks["d2h_peak_gbps"]
+    for name, staging in (("tiny", 1), ("llama3_8b", 16), ("mla_bf16", 32), ("mla_fp8", 32)):
         g = W.geometry(name)
         seq = W.sequence(name, g)
         n = seq["tokens"].size // g.CT
-        kv = [torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev) for _ in range(g.L)]
+        kv, _ = make_pages(torch, W, g, seq["store_blocks"], dev, W.SEED_BASE + W.CONFIGS[name]["id"])
         d_s, d_l = torch.from_numpy(seq["store_slots"]).to(dev), torch.from_numpy(seq["load_slots"]).to(dev)
-        ctx = lmc.Context(g, max(n * g.chunk_bytes, 1 << 30), staging_chunks=staging, device=0)
+        ctx = lmc.Context(g, max(n * g.chunk_bytes, 64 << 20), staging_chunks=staging, device=0)
         ids = ctx.hash_chunks(seq["tokens"])
 
         def st():
             ctx.clear(ids)
             ctx.wait(ctx.store(kv, d_s, ids, stream))
         # best of a dozen: for a few seconds after memory of this size has been allocated or
-        # freed in the process, the runtime's device-to-host copies run at half speed
+        # freed in the process, the runtime's device-to-host copies can run at half speed
         ts = timed(st, reps=12)
-        tl = timed(lambda: ctx.wait(ctx.retrieve(ids, d_l, kv, stream)), reps=4)
+        tl = timed(lambda: ctx.wait(ctx.retrieve(ids, d_l, kv, stream)), reps=6)
         nbytes = n * g.chunk_bytes
-        h2d, d2h = ctx.measure_link(min(512 << 20, nbytes) // 16 * 16, reps=3)
-        # the kernels alone: the whole request in one launch, HBM to HBM.  Requests smaller
-        # than the 256 MB Infinity Cache are served from it in part, so those are no
-        # measure of HBM (configuration 1 and the fp8 variant of 5).
-        staging = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-        kg, ks = kernel_only(torch, ctx, kv, d_s, n, staging, stream)
-        del staging
+        tg, tsc, tc = kernel_only(torch, ctx, W, name, g, kv, n, dev, stream)
         res[name] = {"chunks": n, "payload_bytes": nbytes,
-                     "kernel_only_gather_hbm_gbps": round(2 * nbytes / kg / 1e9, 1),
-                     "kernel_only_scatter_hbm_gbps": round(2 * nbytes / ks / 1e9, 1),
-                     "kernel_only_in_cache": nbytes < (512 << 20),
                      "store_gbps": round(nbytes / ts / 1e9, 2), "retrieve_gbps": round(nbytes / tl / 1e9, 2),
                      "store_frac_of_d2h_peak": round(nbytes / ts / 1e9 / d2h, 4),
                      "retrieve_frac_of_h2d_peak": round(nbytes / tl / 1e9 / h2d, 4),
-                     "store_ms": round(ts * 1e3, 3), "retrieve_ms": round(tl * 1e3, 3)}
+                     "store_ms": round(ts * 1e3, 3), "retrieve_ms": round(tl * 1e3, 3),
+                     "kernels_alone": kernel_report(nbytes, tg, tsc, tc)}
+        if nbytes < (4 << 20):
+            res[name]["note"] = ("half a MiB: launch- and latency-bound, no measure of the link or of HBM; by "
+                                 "the library's size rule it moves without staging, in one launch each way")
         ctx.destroy()
         del kv
-        torch.cuda.empty_cache()
-    g = W.geometry("batch_8b")
-    reqs = W.request_mix("batch_8b", g)
+    name = "batch_8b"
+    g = W.geometry(name)
+    reqs = W.request_mix(name, g)
     n_hit = sum(r["n_hit"] for r in reqs)
     kv = [torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev) for _ in range(g.L)]
     ctx = lmc.Context(g, (n_hit + 1) * g.chunk_bytes, staging_chunks=16, device=0)
-    zero = np.zeros(g.chunk_bytes, dtype=np.uint8)
+    payload = W.payload_bytes(W.rng_for(name, stream=3), g, g.chunk_bytes)
     ids_per = [ctx.hash_chunks(r["tokens"]) for r in reqs]
     hit = [(ri, k) for ri, r in enumerate(reqs) for k in range(r["n_hit"])]
     for j in np.random.default_rng(0).permutation(len(hit)):
-        ctx.put_host([ids_per[hit[j][0]][hit[j][1]]], zero)
+        ctx.put_host([ids_per[hit[j][0]][hit[j][1]]], payload)
     off = np.concatenate([[0], np.cumsum([r["n_hit"] for r in reqs])])
     ids_all = np.concatenate([ids_per[ri][:r["n_hit"]] for ri, r in enumerate(reqs)])
     d_sl = torch.from_numpy(np.concatenate([r["load_slots"] for r in reqs])).to(dev)
     t = timed(lambda: ctx.wait(ctx.retrieve_batch(off, ids_all, d_sl, kv, stream)), reps=3)
-    h2d, _ = ctx.measure_link(512 << 20, reps=3)
     nbytes = n_hit * g.chunk_bytes
-    staging = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-    kg, ks = kernel_only(torch, ctx, kv, d_sl, n_hit, staging, stream)
-    del staging
-    res["batch_8b"] = {"requests": len(reqs), "hit_chunks": n_hit, "payload_bytes": nbytes,
-                       "kernel_only_gather_hbm_gbps": round(2 * nbytes / kg / 1e9, 1),
-                       "kernel_only_scatter_hbm_gbps": round(2 * nbytes / ks / 1e9, 1),
-                       "retrieve_batch_gbps": round(nbytes / t / 1e9, 2),
-                       "retrieve_frac_of_h2d_peak": round(nbytes / t / 1e9 / h2d, 4),
-                       "retrieve_ms": round(t * 1e3, 1)}
+    tg, tsc, tc = kernel_only(torch, ctx, W, name, g, kv, n_hit, dev, stream, slots=[d_sl], iters=3)
+    res[name] = {"requests": len(reqs), "hit_chunks": n_hit, "payload_bytes": nbytes,
+                 "retrieve_batch_gbps": round(nbytes / t / 1e9, 2),
+                 "retrieve_frac_of_h2d_peak": round(nbytes / t / 1e9 / h2d, 4),
+                 "retrieve_ms": round(t * 1e3, 1),
+                 "kernels_alone": kernel_report(nbytes, tg, tsc, tc)}
     ctx.destroy()
     return res
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--staging-chunks", type=int, default=16)
-    ap.add_argument("--num-staging", type=int, default=2)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--settle-seconds", type=float, default=40.0,
-                    help="upper limit for the untimed settling phase before the warm-up (0 = none)")
-    ap.add_argument("--legs", default="pipeline,link,device,duplex,direct,layerwise,overlap,fragmented,small,cpu",
-                    help="comma list of pipeline (always run), link, device, duplex, direct, layerwise, overlap, "
-                         "fragmented, small, cpu, and configs (every benchmark configuration end to end; "
-                         "not in the default): the extra measurements to make; profiling runs use a subset")
-    ap.add_argument("--tune", action="append", default=[], help="key=value for lmc_tune")
-    args = ap.parse_args()
-    legs = set(args.legs.split(","))
-    if args.no_cpu_baseline:
-        legs.discard("cpu")
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this path runs on one GPU only (no sharding, no collectives); "
-              "run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    from paper_2510_09665_amd import lmc
-    from paper_2510_09665_amd import workloads as W
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    dev = torch.device("cuda:0")
-    g = W.geometry(WORKLOAD)
-    seq = W.sequence(WORKLOAD, g)
+def mode_legs(torch, lmc, W, dev, stream, legs, args, timed, peaks):
+    """The modes beside the bulk pipeline, on the Llama-3-8B shape (16 chunks, 512 MiB)."""
+    g = W.geometry(SECONDARY)
+    seq = W.sequence(SECONDARY, g)
     n_chunks = seq["tokens"].size // g.CT
     payload_one_way = n_chunks * g.chunk_bytes
-
-    # paged KV resident in HBM: bf16 uniform(-1, 1) in the request's blocks
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(W.SEED_BASE + W.CONFIGS[WORKLOAD]["id"])
-    src, dst = [], []
-    sb = torch.from_numpy(seq["store_blocks"]).to(dev)
-    for _ in range(g.L):
-        a = torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev)
-        r = torch.rand((g.P, sb.numel(), g.block_stride // 2), device=dev, generator=gen) * 2 - 1
-        a.view(g.P, g.NB, g.block_stride)[:, sb] = \
-            r.to(torch.bfloat16).view(torch.uint8).view(g.P, sb.numel(), g.block_stride)
-        src.append(a)
-        dst.append(torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev))
+    src, dst = make_pages(torch, W, g, seq["store_blocks"], dev, W.SEED_BASE + W.CONFIGS[SECONDARY]["id"])
     d_store = torch.from_numpy(seq["store_slots"]).to(dev)
     d_load = torch.from_numpy(seq["load_slots"]).to(dev)
-    stream = torch.cuda.current_stream()
-
     ctx = lmc.Context(g, max(2 * n_chunks * g.chunk_bytes, 1 << 30), num_staging=args.num_staging,
-                      staging_chunks=args.staging_chunks, device=0, flags=lmc.LMC_FLAG_TIMING)
+                      staging_chunks=16, device=0)
     for kv in args.tune:
         k, v = kv.split("=")
         ctx.tune(k, int(v))
-
-    def step():
-        ids = ctx.hash_chunks(seq["tokens"])
-        assert ctx.lookup(ids) == 0
-        t = ctx.store(src, d_store, ids, stream)
-        ctx.wait(t)
-        assert ctx.lookup(ids) == n_chunks
-        t = ctx.retrieve(ids, d_load, dst, stream)
-        ctx.wait(t)
-        ctx.clear(ids)
-
-    # Settle.  For some seconds after tens of GiB of device or pinned memory have been
-    # freed on the host (by this process while it set up, or by the process that had the
-    # GPU before), the runtime's device-to-host copies inside a store run at about half
-    # speed; the state sets in a few steps after the first copies and passes by itself.
-    # It is a state of the machine, not of this path, so steps are run, untimed, until 150
-    # in a row (three seconds' worth) reach 90 % of the link rate measured now (a lone copy
-    # is not affected) without the library's copy-engine guard stepping in, or until the
-    # time limit; what it took is reported.  Right after the GPU test suite this takes up
-    # to ten seconds, on a machine in its normal state three.
-    settle = {"steps": 0, "seconds": 0.0, "settled": args.settle_seconds <= 0}
-    if args.settle_seconds > 0:
-        _, d2h_now = ctx.measure_link(256 << 20, reps=2)
-        t_begin, good, slow, seen = time.perf_counter(), 0, 0, 0
-        while time.perf_counter() - t_begin < args.settle_seconds:
-            a = time.perf_counter()
-            step()
-            torch.cuda.synchronize()
-            settle["steps"] += 1
-            gs = ctx.get_stats()
-            healthy = 2 * payload_one_way / (time.perf_counter() - a) / 1e9 >= 0.9 * d2h_now
-            if healthy and gs["d2h_guard_switches"] == seen and not gs["d2h_guard_active"]:
-                good += 1
-            else:
-                good, seen = 0, gs["d2h_guard_switches"]
-                slow += 0 if healthy else 1
-            if good >= 150:
-                settle["settled"] = True
-                break
-        settle["seconds"] = round(time.perf_counter() - t_begin, 2)
-        settle["slow_steps"] = slow
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    guard_before = ctx.get_stats()["d2h_guard_switches"]
-    ctx.reset_stats()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    st = ctx.get_stats()
-    # copies handed to the copy kernel by the guard during the timed steps (0 on a settled machine)
-    settle["guard_switches_in_timed_region"] = st["d2h_guard_switches"] - guard_before
-    settle["guard_active_after_timed_region"] = bool(st["d2h_guard_active"])
-
-    # the result of the last step: every destination block equals its source block
-    lb = torch.from_numpy(seq["load_blocks"]).to(dev)
-    for l in range(g.L):
-        assert torch.equal(dst[l].view(g.P, g.NB, g.block_stride)[:, lb],
-                           src[l].view(g.P, g.NB, g.block_stride)[:, sb]), "round trip differs"
-
-    value = 2 * payload_one_way * args.steps / dt / 1e9
-    ms_per_step = dt / args.steps * 1e3
-
-    # dominant kernel of the timed region
-    def kern(kind):
-        n = st["timed_%s_launches" % kind]
-        ms = st["%s_ms" % kind]
-        moved = st["bytes_gathered" if kind == "gather" else "bytes_scattered"]
-        avg_ms = ms / max(n, 1)
-        return dict(launches=n, avg_us=round(avg_ms * 1e3, 2),
-                    avg_chunks_per_launch=round(moved / g.chunk_bytes / max(n, 1), 2),
-                    bytes_per_launch=2 * moved // max(n, 1),
-                    hbm_gbps=round(2 * moved / max(ms, 1e-9) / 1e6, 1))
-    kg, ks = kern("gather"), kern("scatter")
-    dom_name, dom = ("gather", kg) if st["gather_ms"] >= st["scatter_ms"] else ("scatter", ks)
-    roofline = {
-        "bound": "hbm", "kernel": "move_rows<16," + ("gather" if dom_name == "gather" else "scatter") + ">",
-        "achieved": dom["hbm_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": round(dom["hbm_gbps"] / HBM_PEAK_GBPS, 4),
-        "traffic": int(dom["bytes_per_launch"] * PMC_TRAFFIC_RATIO),
-        "bytes_per_launch": dom["bytes_per_launch"], "avg_launch_us": dom["avg_us"],
-        "launches": dom["launches"], "gather": kg, "scatter": ks,
-    }
-
-    # store and retrieve separately, and the link peak
-    def timed(fn, reps=5):
-        best = 1e30
-        for _ in range(reps):
-            torch.cuda.synchronize()
-            a = time.perf_counter()
-            fn()
-            best = min(best, time.perf_counter() - a)
-        return best
     ids = ctx.hash_chunks(seq["tokens"])
-    link = None
-    if "link" in legs:
-        def store_only():
-            ctx.clear(ids)
-            ctx.wait(ctx.store(src, d_store, ids, stream))
-        t_store = timed(store_only)
-        t_load = timed(lambda: ctx.wait(ctx.retrieve(ids, d_load, dst, stream)))
-        ctx.clear(ids)
-        h2d, d2h = ctx.measure_link(512 << 20, reps=4)
-        link = {
-            "h2d_peak_gbps": round(h2d, 2), "d2h_peak_gbps": round(d2h, 2),
-            "store_gbps": round(payload_one_way / t_store / 1e9, 2),
-            "retrieve_gbps": round(payload_one_way / t_load / 1e9, 2),
-            "store_frac_of_d2h_peak": round(payload_one_way / t_store / 1e9 / d2h, 4),
-            "retrieve_frac_of_h2d_peak": round(payload_one_way / t_load / 1e9 / h2d, 4),
-        }
-
-    # kernels alone: all 16 chunks per launch, rotating over 4 block sets (4 x 512 MiB of
-    # sources + 4 staging buffers) so that nothing is served from the Infinity Cache
-    device = None
-    if "device" in legs:
-        n_rot = 4
-        rot_slots, stagings = [], []
-        for r in range(n_rot):
-            s = W.sequence(WORKLOAD, g, stream=10 + r)
-            rot_slots.append(torch.from_numpy(s["store_slots"]).to(dev))
-            stagings.append(torch.empty(payload_one_way, dtype=torch.uint8, device=dev))
-
-        ctx.tune("timing", 0)     # back-to-back launches, no per-launch events in between
-
-        def dev_time(fn, iters=12, reps=3):
-            for r in range(n_rot):
-                fn(r)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            best = 1e30
-            for _ in range(reps):
-                e0.record(stream)
-                for i in range(iters):
-                    fn(i % n_rot)
-                e1.record(stream)
-                e1.synchronize()
-                best = min(best, e0.elapsed_time(e1) / iters * 1e-3)
-            return best
-        tg = dev_time(lambda r: ctx.gather(src, rot_slots[r], n_chunks, stagings[r], stream))
-        tsc = dev_time(lambda r: ctx.scatter(stagings[r], rot_slots[r], n_chunks, dst, stream))
-        tc = dev_time(lambda r: ctx.copy(stagings[r], stagings[(r + 1) % n_rot], payload_one_way, stream))
-        ctx.wait()
-        device = {
-            "chunks_per_launch": n_chunks, "bytes_per_launch": 2 * payload_one_way,
-            "gather_us": round(tg * 1e6, 1), "scatter_us": round(tsc * 1e6, 1),
-            "copy_kernel_us": round(tc * 1e6, 1),
-            "gather_hbm_gbps": round(2 * payload_one_way / tg / 1e9, 1),
-            "scatter_hbm_gbps": round(2 * payload_one_way / tsc / 1e9, 1),
-            "copy_kernel_hbm_gbps": round(2 * payload_one_way / tc / 1e9, 1),
-            "gather_frac_of_hbm_peak": round(2 * payload_one_way / tg / 1e9 / HBM_PEAK_GBPS, 4),
-            "scatter_frac_of_hbm_peak": round(2 * payload_one_way / tsc / 1e9 / HBM_PEAK_GBPS, 4),
-        }
-        del stagings
+    duplex = direct = layerwise = overlap = fragmented = None
     # full duplex: store one request while another is retrieved (two streams per
     # direction, nothing shared but the link and HBM)
     duplex = None
     if "duplex" in legs:
         ctx.tune("timing", 0)
         ids_a = ctx.hash_chunks(seq["tokens"])
-        seq_b = W.sequence(WORKLOAD, g, stream=1)
+        seq_b = W.sequence(SECONDARY, g, stream=1)
         ids_b = ctx.hash_chunks(seq_b["tokens"])
         d_load_b = torch.from_numpy(seq["load_slots"]).to(dev)
         ctx.clear(ids_a)
@@ -429,10 +297,14 @@ def main():
             ctx.wait(t1)
             ctx.wait(t2)
         t_both = timed(both)
-        peak = ctx.measure_link_duplex(512 << 20, reps=6)
+        peak = peaks["duplex_peak_gbps"]
         duplex = {"store_plus_retrieve_gbps": round(2 * payload_one_way / t_both / 1e9, 2),
                   "link_duplex_peak_gbps": round(peak, 2),
-                  "frac_of_duplex_peak": round(2 * payload_one_way / t_both / 1e9 / peak, 4)}
+                  "frac_of_duplex_peak": round(2 * payload_one_way / t_both / 1e9 / peak, 4),
+                  # against what two perfect one-way transfers would add up to
+                  "sum_of_one_way_peaks_gbps": round(peaks["h2d_peak_gbps"] + peaks["d2h_peak_gbps"], 2),
+                  "frac_of_sum_of_one_way_peaks": round(2 * payload_one_way / t_both / 1e9 /
+                                                        (peaks["h2d_peak_gbps"] + peaks["d2h_peak_gbps"]), 4)}
         ctx.clear(ids_a)
         ctx.clear(ids_b)
 
@@ -450,7 +322,7 @@ def main():
             dctx.wait(dctx.store(src, d_store, dids, stream))
         td_s = timed(d_store_only)
         td_l = timed(lambda: dctx.wait(dctx.retrieve(dids, d_load, dst, stream)))
-        h2d, d2h = dctx.measure_link(512 << 20, reps=3)
+        h2d, d2h = peaks["h2d_peak_gbps"], peaks["d2h_peak_gbps"]
         direct = {"store_gbps": round(payload_one_way / td_s / 1e9, 2),
                   "retrieve_gbps": round(payload_one_way / td_l / 1e9, 2),
                   "store_frac_of_d2h_peak": round(payload_one_way / td_s / 1e9 / d2h, 4),
@@ -463,7 +335,7 @@ def main():
     if "layerwise" in legs:
         ctx.tune("timing", 0)
         ids = ctx.hash_chunks(seq["tokens"])
-        h2d, d2h = ctx.measure_link(512 << 20, reps=3)
+        h2d, d2h = peaks["h2d_peak_gbps"], peaks["d2h_peak_gbps"]
         consumer = torch.cuda.Stream()
         layerwise = {}
         for k in (1, 4):
@@ -604,7 +476,7 @@ def main():
     # neighbours, so every group needs one copy per chunk (two copy streams take turns)
     fragmented = None
     if "fragmented" in legs:
-        fctx = lmc.Context(g, (2 * n_chunks + 1) * g.chunk_bytes, staging_chunks=args.staging_chunks,
+        fctx = lmc.Context(g, (2 * n_chunks + 1) * g.chunk_bytes, staging_chunks=16,
                            num_staging=args.num_staging, device=0)
         filler = np.arange(1, 2 * n_chunks + 1, dtype=np.uint64) + np.uint64(1 << 40)
         zero = np.zeros(g.chunk_bytes, dtype=np.uint8)
@@ -619,55 +491,253 @@ def main():
         tf_s = timed(f_store_only)
         assert [fctx.find_slot(i) for i in fids[:3]] == [1, 3, 5]
         tf_l = timed(lambda: fctx.wait(fctx.retrieve(fids, d_load, dst, stream)))
-        h2d, d2h = fctx.measure_link(512 << 20, reps=3)
+        h2d, d2h = peaks["h2d_peak_gbps"], peaks["d2h_peak_gbps"]
         fragmented = {"store_gbps": round(payload_one_way / tf_s / 1e9, 2),
                       "retrieve_gbps": round(payload_one_way / tf_l / 1e9, 2),
                       "store_frac_of_d2h_peak": round(payload_one_way / tf_s / 1e9 / d2h, 4),
                       "retrieve_frac_of_h2d_peak": round(payload_one_way / tf_l / 1e9 / h2d, 4)}
         fctx.destroy()
 
+
     ctx.destroy()
-    del src, dst
-    torch.cuda.empty_cache()
+    out = {}
+    for key, val in (("duplex", duplex), ("direct", direct), ("layerwise", layerwise),
+                     ("overlap_with_compute", overlap), ("fragmented_pool", fragmented)):
+        if val:
+            out[key] = val
+    return out
 
-    # a request of one small chunk (config 1, 0.5 MiB): time from the call to a finished
-    # lmc_wait, through the staging ring and by the library's size rule (no staging)
-    small = None
-    if "small" in legs:
-        small = {}
-        tg = W.geometry("tiny")
-        tseq = W.sequence("tiny", tg)
-        tsrc = [torch.zeros(tg.layer_bytes, dtype=torch.uint8, device=dev) for _ in range(tg.L)]
-        ts_, tl_ = torch.from_numpy(tseq["store_slots"]).to(dev), torch.from_numpy(tseq["load_slots"]).to(dev)
-        for mode in ("staged", "size_rule"):
-            tctx = lmc.Context(tg, 4 * tg.chunk_bytes, device=0)
-            if mode == "staged":
-                tctx.tune("direct_store_below", 0)
-                tctx.tune("direct_retrieve_below", 0)
-            tids = tctx.hash_chunks(tseq["tokens"])
 
-            def t_store_only():
-                tctx.clear(tids)
-                tctx.wait(tctx.store(tsrc, ts_, tids, stream))
-            small[mode] = {"store_us": round(timed(t_store_only, reps=40) * 1e6, 1),
-                           "retrieve_us": round(timed(lambda: tctx.wait(tctx.retrieve(tids, tl_, tsrc, stream)),
-                                                      reps=40) * 1e6, 1)}
-            tctx.destroy()
-        small["payload_bytes"] = tg.chunk_bytes
-        del tsrc
+def small_leg(torch, lmc, W, dev, stream, timed):
+    """One chunk of half a MiB (configuration 1): microseconds from the call to a finished
+    lmc_wait, through the staging ring and by the library's size rule (no staging)."""
+    small = {}
+    tg = W.geometry("tiny")
+    tseq = W.sequence("tiny", tg)
+    tsrc = [torch.zeros(tg.layer_bytes, dtype=torch.uint8, device=dev) for _ in range(tg.L)]
+    ts_, tl_ = torch.from_numpy(tseq["store_slots"]).to(dev), torch.from_numpy(tseq["load_slots"]).to(dev)
+    for mode in ("staged", "size_rule"):
+        tctx = lmc.Context(tg, 4 * tg.chunk_bytes, device=0)
+        if mode == "staged":
+            tctx.tune("direct_store_below", 0)
+            tctx.tune("direct_retrieve_below", 0)
+        tids = tctx.hash_chunks(tseq["tokens"])
 
-    configs = all_configs(torch, lmc, W, dev, stream, timed) if "configs" in legs else None
+        def t_store_only():
+            tctx.clear(tids)
+            tctx.wait(tctx.store(tsrc, ts_, tids, stream))
+        small[mode] = {"store_us": round(timed(t_store_only, reps=40) * 1e6, 1),
+                       "retrieve_us": round(timed(lambda: tctx.wait(tctx.retrieve(tids, tl_, tsrc, stream)),
+                                                  reps=40) * 1e6, 1)}
+        tctx.destroy()
+    small["payload_bytes"] = tg.chunk_bytes
+    del tsrc
+    return small
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--staging-chunks", type=int, default=8)
+    ap.add_argument("--num-staging", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--first-steps", type=int, default=20,
+                    help="steps measured right after set-up, before anything settles (0 = none)")
+    ap.add_argument("--settle-seconds", type=float, default=20.0,
+                    help="upper limit for the untimed settling phase before the warm-up (0 = none)")
+    ap.add_argument("--legs", default="pipeline,link,device,configs,duplex,direct,layerwise,overlap,"
+                                      "fragmented,small,cpu",
+                    help="comma list of pipeline (always run), link, device, configs, duplex, direct, "
+                         "layerwise, overlap, fragmented, small, cpu: the extra measurements to make; "
+                         "profiling runs use a subset")
+    ap.add_argument("--tune", action="append", default=[], help="key=value for lmc_tune")
+    args = ap.parse_args()
+    legs = set(args.legs.split(","))
+    if args.no_cpu_baseline:
+        legs.discard("cpu")
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on one GPU only (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2510_09665_amd import lmc
+    from paper_2510_09665_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    g = W.geometry(WORKLOAD)
+    seq = W.sequence(WORKLOAD, g)
+    n_chunks = seq["tokens"].size // g.CT
+    payload_one_way = n_chunks * g.chunk_bytes
+
+    src, dst = make_pages(torch, W, g, seq["store_blocks"], dev, W.SEED_BASE + W.CONFIGS[WORKLOAD]["id"])
+    d_store = torch.from_numpy(seq["store_slots"]).to(dev)
+    d_load = torch.from_numpy(seq["load_slots"]).to(dev)
+    stream = torch.cuda.current_stream()
+
+    pool_bytes = max((n_chunks + 2) * g.chunk_bytes, 2 << 30)
+    ctx = lmc.Context(g, pool_bytes, num_staging=args.num_staging,
+                      staging_chunks=args.staging_chunks, device=0, flags=lmc.LMC_FLAG_TIMING)
+    for kv in args.tune:
+        k, v = kv.split("=")
+        ctx.tune(k, int(v))
+
+    def step():
+        ids = ctx.hash_chunks(seq["tokens"])
+        assert ctx.lookup(ids) == 0
+        t = ctx.store(src, d_store, ids, stream)
+        ctx.wait(t)
+        assert ctx.lookup(ids) == n_chunks
+        t = ctx.retrieve(ids, d_load, dst, stream)
+        ctx.wait(t)
+        ctx.clear(ids)
+
+    def timed_steps(n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            step()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    # What a process sees that has only just set itself up: the first steps, measured
+    # before anything is given time to settle.
+    first = None
+    if args.first_steps > 0:
+        dt1 = timed_steps(1)
+        dtn = timed_steps(args.first_steps - 1) if args.first_steps > 1 else 0.0
+        first = {"steps": args.first_steps,
+                 "gbps": round(2 * payload_one_way * args.first_steps / (dt1 + dtn) / 1e9, 3),
+                 "very_first_step_gbps": round(2 * payload_one_way / dt1 / 1e9, 3)}
+
+    # Settle.  For some seconds after tens of GiB of device or pinned memory have been
+    # allocated or freed on the host (by this process while it set up, or by the process
+    # that had the GPU before), the runtime's device-to-host copies inside a store can run
+    # at about half speed; the state passes by itself.  It is a state of the machine, not
+    # of this path, so steps are run, untimed, until three seconds' worth in a row reach
+    # 90 % of the link rate measured now (a lone copy is not affected) without the
+    # library's copy-engine guard stepping in, or until the time limit; what it took is
+    # reported beside the rate of the first steps above.
+    settle = {"steps": 0, "seconds": 0.0, "settled": args.settle_seconds <= 0}
+    if args.settle_seconds > 0:
+        _, d2h_now = ctx.measure_link(256 << 20, reps=2)
+        need = max(4, int(3.0 / (2 * payload_one_way / (0.9 * d2h_now * 1e9))))
+        t_begin, good, slow, seen = time.perf_counter(), 0, 0, ctx.get_stats()["d2h_guard_switches"]
+        while time.perf_counter() - t_begin < args.settle_seconds:
+            dt = timed_steps(1)
+            settle["steps"] += 1
+            gs = ctx.get_stats()
+            healthy = 2 * payload_one_way / dt / 1e9 >= 0.9 * d2h_now
+            if healthy and gs["d2h_guard_switches"] == seen and not gs["d2h_guard_active"]:
+                good += 1
+            else:
+                good, seen = 0, gs["d2h_guard_switches"]
+                slow += 0 if healthy else 1
+            if good >= need:
+                settle["settled"] = True
+                break
+        settle["seconds"] = round(time.perf_counter() - t_begin, 2)
+        settle["slow_steps"] = slow
+        settle["steps_in_a_row_required"] = need
+    if first:
+        settle["first_steps_before_settling"] = first
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    guard_before = ctx.get_stats()["d2h_guard_switches"]
+    ctx.reset_stats()
+    dt = timed_steps(args.steps)
+    st = ctx.get_stats()
+    # copies handed to the copy kernel by the guard during the timed steps (0 on a settled machine)
+    settle["guard_switches_in_timed_region"] = st["d2h_guard_switches"] - guard_before
+    settle["guard_active_after_timed_region"] = bool(st["d2h_guard_active"])
+
+    # the result of the last step: every destination block equals its source block
+    sb = torch.from_numpy(seq["store_blocks"]).to(dev)
+    lb = torch.from_numpy(seq["load_blocks"]).to(dev)
+    for l in range(g.L):
+        assert torch.equal(dst[l].view(g.P, g.NB, g.block_stride)[:, lb],
+                           src[l].view(g.P, g.NB, g.block_stride)[:, sb]), "round trip differs"
+
+    value = 2 * payload_one_way * args.steps / dt / 1e9
+    ms_per_step = dt / args.steps * 1e3
+
+    # dominant kernel of the timed region
+    def kern(kind):
+        n = st["timed_%s_launches" % kind]
+        ms = st["%s_ms" % kind]
+        moved = st["bytes_gathered" if kind == "gather" else "bytes_scattered"]
+        avg_ms = ms / max(n, 1)
+        return dict(launches=n, avg_us=round(avg_ms * 1e3, 2),
+                    avg_chunks_per_launch=round(moved / g.chunk_bytes / max(n, 1), 2),
+                    bytes_per_launch=2 * moved // max(n, 1),
+                    hbm_gbps=round(2 * moved / max(ms, 1e-9) / 1e6, 1))
+    kg, ks = kern("gather"), kern("scatter")
+    dom_name, dom = ("gather", kg) if st["gather_ms"] >= st["scatter_ms"] else ("scatter", ks)
+    roofline = {
+        "bound": "hbm", "kernel": "move_rows<16," + dom_name + ">",
+        "achieved": dom["hbm_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": round(dom["hbm_gbps"] / HBM_PEAK_GBPS, 4),
+        "traffic": int(dom["bytes_per_launch"] * PMC_TRAFFIC_RATIO),
+        "traffic_source": "not read in this run: launch bytes x %.4f, the FETCH_SIZE + WRITE_SIZE to algorithmic "
+                          "ratio that rocprofv3 --pmc measured for this kernel (profiles/)" % PMC_TRAFFIC_RATIO,
+        "bytes_per_launch": dom["bytes_per_launch"], "avg_launch_us": dom["avg_us"],
+        "launches": dom["launches"], "gather": kg, "scatter": ks,
+    }
+
+    def timed(fn, reps=5):
+        best = 1e30
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            a = time.perf_counter()
+            fn()
+            best = min(best, time.perf_counter() - a)
+        return best
+
+    # the link's peak, and store / retrieve of the headline request separately against it
+    ids = ctx.hash_chunks(seq["tokens"])
+    peaks = link_peaks(ctx, pool_bytes)
+    link = None
+    if "link" in legs:
+        def store_only():
+            ctx.clear(ids)
+            ctx.wait(ctx.store(src, d_store, ids, stream))
+        t_store = timed(store_only, reps=4)
+        t_load = timed(lambda: ctx.wait(ctx.retrieve(ids, d_load, dst, stream)), reps=4)
+        ctx.clear(ids)
+        link = dict(peaks)
+        for k_ in ("h2d_peak_gbps", "d2h_peak_gbps", "duplex_peak_gbps"):
+            link[k_] = round(link[k_], 2)
+        link.update({
+            "store_gbps": round(payload_one_way / t_store / 1e9, 2),
+            "retrieve_gbps": round(payload_one_way / t_load / 1e9, 2),
+            "store_frac_of_d2h_peak": round(payload_one_way / t_store / 1e9 / peaks["d2h_peak_gbps"], 4),
+            "retrieve_frac_of_h2d_peak": round(payload_one_way / t_load / 1e9 / peaks["h2d_peak_gbps"], 4),
+        })
+
+    # kernels alone: the whole request (128 chunks, 10 GiB) in one launch
+    device = None
+    if "device" in legs:
+        ctx.tune("timing", 0)     # back-to-back launches, no per-launch events in between
+        tg, tsc, tc = kernel_only(torch, ctx, W, WORKLOAD, g, src, n_chunks, dev, stream, slots=[d_store], iters=3)
+        device = {"chunks_per_launch": n_chunks}
+        device.update(kernel_report(payload_one_way, tg, tsc, tc))
+        ctx.tune("timing", 1)
 
     out = {
         "metric": "KV store/retrieve GB/s", "value": round(value, 3), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": "Llama-3-8B-shaped KV: 32 layers, 8 KV heads, head_dim 128, bf16, "
-                               "block_size 16, pool of 8192 blocks; 4096-token prefix = 16 chunks of "
-                               "256 tokens; store all chunks then retrieve into freshly permuted blocks",
+        "config": {"workload": WORKLOAD_TEXT,
                    "payload_bytes_per_step": 2 * payload_one_way, "chunk_bytes": g.chunk_bytes,
-                   "staging_chunks": args.staging_chunks, "num_staging": args.num_staging},
+                   "chunks": n_chunks, "staging_chunks": args.staging_chunks, "num_staging": args.num_staging},
         "roofline": roofline,
         "settle": settle,
     }
@@ -675,22 +745,17 @@ def main():
         out["device"] = device
     if link:
         out["link"] = link
-    if duplex:
-        out["duplex"] = duplex
-    if direct:
-        out["direct"] = direct
-    if layerwise:
-        out["layerwise"] = layerwise
-    if overlap:
-        out["overlap_with_compute"] = overlap
-    if fragmented:
-        out["fragmented_pool"] = fragmented
-    if small:
-        out["small_request"] = small
-    if configs:
-        out["configs"] = configs
+    # the headline's pages and context stay allocated to the end: freeing tens of GiB in
+    # the middle of the run is what brings on the slow state described at the settling loop
+    if "configs" in legs:
+        out["configs"] = other_configs(torch, lmc, W, dev, stream, timed, peaks)
+    if legs & {"duplex", "direct", "layerwise", "overlap", "fragmented"}:
+        out.update(mode_legs(torch, lmc, W, dev, stream, legs, args, timed, peaks))
+    if "small" in legs:
+        out["small_request"] = small_leg(torch, lmc, W, dev, stream, timed)
+    ctx.destroy()
     if "cpu" in legs:
-        out["cpu_baseline"] = cpu_baseline(g, seq)
+        out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out), flush=True)
 
 

@@ -152,7 +152,9 @@ typedef struct {
     double d2h_copy_last_gbps;    /* rate of the latest such copy */
 } lmc_stats_t;
 
-/* Create a context: allocates the pinned host pool, 2*num_staging device staging
+/* Create a context (section 4: the storage manager that owns the CPU memory the KV cache
+ * is offloaded to; section 5.1: the contiguous streaming GPU buffers between the pages
+ * and that memory): allocates the pinned host pool, 2*num_staging device staging
  * buffers of staging_chunks chunks each (one ring per direction), six HIP streams
  * and the index.  With device == LMC_DEVICE_NONE nothing touches HIP: the pool is
  * ordinary host memory and only the host-side calls work (hashing, lookup, put/get,
@@ -200,7 +202,10 @@ lmc_status_t lmc_lookup(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n,
  * the store on the device.
  * Errors: LMC_ERR_NOMEM when the pool fills: chunks before the failing one are stored
  * and their work is still covered by the ticket.  LMC_ERR_BADSLOT under
- * LMC_FLAG_VALIDATE_SLOTS (nothing stored).  LMC_ERR_NODEVICE, LMC_ERR_HIP. */
+ * LMC_FLAG_VALIDATE_SLOTS (nothing stored).  LMC_ERR_NODEVICE.  LMC_ERR_HIP: the call
+ * waits for what it had enqueued and takes back every chunk it had admitted (none of
+ * them is visible afterwards, their slots are free again; chunks evicted to make room
+ * stay evicted); no ticket is issued. */
 lmc_status_t lmc_store(lmc_ctx_t *ctx, void *const *kv_layers, const int64_t *slot_mapping,
                        const uint64_t *chunk_ids, int64_t n_chunks, void *stream_to_wait_on,
                        uint64_t *ticket_out);
@@ -213,7 +218,10 @@ lmc_status_t lmc_store(lmc_ctx_t *ctx, void *const *kv_layers, const int64_t *sl
  * touched.  stream_to_signal: a hipStream_t (NULL names the null stream).  The scatter
  * is ordered after everything enqueued on it so far (earlier users of the pages, the
  * producer of the slot mapping), and the stream is made to wait for the last scatter,
- * so work enqueued on it afterwards sees the pages.  Enqueue only. */
+ * so work enqueued on it afterwards sees the pages.  Enqueue only.
+ * LMC_ERR_HIP in the middle of the call: what had been enqueued is waited for, no count
+ * stays on the chunks, no ticket is issued; the pages named by slot_mapping are then
+ * partly written. */
 lmc_status_t lmc_retrieve(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n_chunks,
                           const int64_t *slot_mapping, void *const *kv_layers,
                           void *stream_to_signal, uint64_t *ticket_out);
@@ -254,7 +262,8 @@ lmc_status_t lmc_retrieve_layerwise(lmc_ctx_t *ctx, const uint64_t *chunk_ids, i
  * those layers).  Layers must be submitted in ascending order without gaps, else
  * LMC_ERR_INVAL; when the last layer has been submitted the ticket behaves like any
  * other.  Until then lmc_wait on it, lmc_get_host and a retrieve of its chunks return
- * LMC_ERR_BUSY, and its chunks cannot be cleared. */
+ * LMC_ERR_BUSY, and its chunks cannot be cleared.  LMC_ERR_HIP from lmc_store_layers
+ * ends the whole store: its chunks leave the index, the ticket is void. */
 lmc_status_t lmc_store_begin(lmc_ctx_t *ctx, const int64_t *slot_mapping, const uint64_t *chunk_ids,
                              int64_t n_chunks, void *stream_to_wait_on, uint64_t *ticket_out);
 lmc_status_t lmc_store_layers(lmc_ctx_t *ctx, uint64_t ticket, int32_t first_layer,
@@ -267,19 +276,24 @@ lmc_status_t lmc_store_layers(lmc_ctx_t *ctx, uint64_t ticket, int32_t first_lay
  * layer out of range; LMC_ERR_BUSY for a store layer that has not been submitted. */
 lmc_status_t lmc_wait_layer(lmc_ctx_t *ctx, uint64_t ticket, int32_t layer, void *stream);
 
-/* Block until the work of `ticket` (and of every earlier ticket) has finished on the
- * device; ticket 0 means everything enqueued so far.  Returns LMC_ERR_BADSLOT if a
+/* wait_store_kv / wait_load_kv of section 6, Table 2 (bulk form; lmc_wait_layer is the
+ * per-layer form): block until the work of `ticket` and of every earlier ticket has
+ * finished on the device, whichever of the library's streams each of them ended on;
+ * ticket 0 means everything enqueued so far.  Returns LMC_ERR_BADSLOT if a
  * kernel since the last lmc_wait met a slot >= num_blocks*block_size (that token was
  * skipped, the rest of the call was carried out), LMC_ERR_HIP on a device error.
  * A layer-wise store that still lacks layers cannot be waited for: LMC_ERR_BUSY if it
  * is the ticket named (or ticket is 0); an older one is left out of the wait. */
 lmc_status_t lmc_wait(lmc_ctx_t *ctx, uint64_t ticket);
 
-/* Has the work of `ticket` finished?  LMC_OK: yes; LMC_ERR_BUSY: not yet (or a layer-wise
+/* The non-blocking form of the same two connector calls (section 6, Table 2): has the
+ * work of `ticket` finished?  LMC_OK: yes; LMC_ERR_BUSY: not yet (or a layer-wise
  * store still lacks layers).  Never blocks, reports no slot errors. */
 lmc_status_t lmc_test(lmc_ctx_t *ctx, uint64_t ticket);
 
-/* The two kernels alone, for unit parity and for measuring them against HBM
+/* The two kernels of section 5.1 alone (store: the pages of a chunk are copied into one
+ * contiguous GPU buffer; load: the buffer is split into pages again), for unit parity and
+ * for measuring them against HBM
  * bandwidth: pages -> n_chunks contiguous chunks at staging_dev (DEVICE,
  * n_chunks*chunk_bytes, 16-byte aligned) and back.  Enqueued on `stream`
  * (hipStream_t, NULL = the null stream); no host wait except under
@@ -437,6 +451,11 @@ lmc_status_t lmc_reset_stats(lmc_ctx_t *ctx);
  * counters are calibrated on. */
 lmc_status_t lmc_measure_link(lmc_ctx_t *ctx, uint64_t nbytes, int32_t reps,
                               double *h2d_gbps_out, double *d2h_gbps_out);
+/* The same measurement with the library's link-paced copy kernel (a fixed grid of
+ * "link_groups" workgroups reading or writing the pinned pool) in place of the
+ * runtime's copy; nbytes a multiple of 16.  The link's peak is the better of the two. */
+lmc_status_t lmc_measure_link_kernel(lmc_ctx_t *ctx, uint64_t nbytes, int32_t reps,
+                                     double *h2d_gbps_out, double *d2h_gbps_out);
 lmc_status_t lmc_copy(lmc_ctx_t *ctx, void *dst_dev, const void *src_dev, uint64_t nbytes,
                       void *stream);
 /* Both directions at once (section 5.1 "Parallel Store/load Operations": the host link is
@@ -482,7 +501,10 @@ lmc_status_t lmc_probe_stream(lmc_ctx_t *ctx, void *stream, uint32_t *mask_out);
  * LMC_FLAG_TIMING), "direct_store_below" / "direct_retrieve_below" (bytes, default 64 MiB
  * each: an lmc_store with at most that many new bytes, or an lmc_retrieve /
  * lmc_retrieve_batch of at most that many bytes, goes the LMC_FLAG_DIRECT way: one launch
- * instead of kernel, event, copy, event; 0 = never).  Unknown key or out-of-range value: LMC_ERR_INVAL. */
+ * instead of kernel, event, copy, event; 0 = never), "fail_hip_after" (for tests of the
+ * error paths: the n-th HIP call the library checks from now on is not made and counts as
+ * failed, once; 0 = off.  Nothing on the device goes wrong).
+ * Unknown key or out-of-range value: LMC_ERR_INVAL. */
 lmc_status_t lmc_tune(lmc_ctx_t *ctx, const char *key, int64_t value);
 
 const char *lmc_strerror(lmc_status_t status);

@@ -7,5 +7,5 @@ is computed and which passages of the paper it follows.
 from .oracle import (  # noqa: F401
     ORC_OK, ORC_INVAL, ORC_NOMEM, ORC_MISS, ORC_BADSLOT, ORC_BUSY,
     build, chunk_bytes, fnv1a64, gather, gather_chunk, hash_chunks, scatter, scatter_chunk,
-    OracleStore,
+    OracleStore, time_pass,
 )

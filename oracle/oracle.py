@@ -13,6 +13,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "lmc_oracle.c")
+_TIMING_SRC = os.path.join(_HERE, "oracle_timing.c")     # thread fan-out for the CPU baseline
 _LIB = os.path.join(_HERE, "liblmc_oracle.so")
 
 ORC_OK, ORC_INVAL, ORC_NOMEM, ORC_MISS, ORC_BADSLOT, ORC_BUSY = 0, -1, -2, -3, -4, -6
@@ -25,12 +26,14 @@ class _Geom(ctypes.Structure):
 
 
 def build(force=False):
-    """Compile lmc_oracle.c with gcc into liblmc_oracle.so beside it."""
-    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
+    """Compile lmc_oracle.c (and the timing driver around it) with gcc into
+    liblmc_oracle.so beside it."""
+    if not force and os.path.exists(_LIB) and \
+            os.path.getmtime(_LIB) >= max(os.path.getmtime(_SRC), os.path.getmtime(_TIMING_SRC)):
         return _LIB
     tmp = _LIB + ".%d.tmp" % os.getpid()
     subprocess.check_call(["gcc", "-std=c11", "-O2", "-Wall", "-Wextra", "-shared", "-fPIC",
-                           _SRC, "-o", tmp])
+                           _SRC, _TIMING_SRC, "-lpthread", "-o", tmp])
     os.replace(tmp, _LIB)
     return _LIB
 
@@ -68,6 +71,7 @@ def _L():
             "orc_acquire": (ctypes.c_int, [vp, u64]),
             "orc_release": (ctypes.c_int, [vp, u64]),
             "orc_refs": (i32, [vp, u64]),
+            "orc_time_pass": (ctypes.c_double, [gp, vp, vp, vp, vp, i64, vp, vp, ctypes.c_int, ctypes.c_int]),
         }
         for name, (res, args) in sigs.items():
             f = getattr(lib, name)
@@ -138,6 +142,24 @@ def scatter(g, chunks, slot_mapping, layers):
     chunks = np.asarray(chunks, dtype=np.uint8).reshape(len(slot_mapping), -1)
     for c, s in zip(chunks, slot_mapping):
         scatter_chunk(g, c, s, layers)
+
+
+def time_pass(g, src_layers, dst_layers, store_slots, load_slots, pool, buffers, n_threads, retrieve):
+    """Seconds for one pass of the store analogue (gather_chunk into a buffer, memcpy into
+    the pool) or the retrieve analogue (memcpy out of the pool, scatter_chunk) over all
+    chunks of the slot mappings, chunks dealt out to n_threads plain threads by
+    oracle_timing.c.  pool: uint8[n_chunks * chunk_bytes]; buffers: uint8[n_threads *
+    chunk_bytes]; both allocated (and touched) by the caller beforehand."""
+    store_slots, load_slots = _i64(store_slots), _i64(load_slots)
+    n_chunks = store_slots.size // g.CT
+    cb = chunk_bytes(g)
+    assert load_slots.size == store_slots.size and pool.size >= n_chunks * cb and buffers.size >= n_threads * cb
+    dt = _L().orc_time_pass(ctypes.byref(_geom(g)), _layer_table(src_layers), _layer_table(dst_layers),
+                            _ptr(store_slots), _ptr(load_slots), n_chunks, _ptr(pool), _ptr(buffers),
+                            int(n_threads), int(bool(retrieve)))
+    if dt < 0:
+        raise RuntimeError("oracle timing pass failed")
+    return dt
 
 
 def fnv1a64(data: bytes) -> int:

@@ -45,6 +45,7 @@ struct Ring {
 struct Op {
     uint64_t ticket = 0;
     hipEvent_t done = nullptr;       // null: nothing enqueued (yet) for this ticket
+    hipStream_t final_stream = nullptr;  // the library stream `done` was recorded on
     std::vector<int64_t> slots;      // pool slots whose in-flight count this op holds
     // layer-wise operations (paper section 5.2)
     bool layerwise = false;
@@ -116,6 +117,14 @@ struct lmc_ctx {
     std::deque<Timing> timings;
     uint64_t next_ticket = 1;
     std::vector<hipEvent_t> free_sync_events, free_time_events, all_events;
+    // Threads that sleep in hipEventSynchronize with the mutex released.  While there are
+    // any, events that become free are parked in held_events instead of going back to the
+    // free list: an event somebody sleeps on is then never recorded anew under them.
+    int waiters = 0;
+    std::vector<hipEvent_t> held_events;
+    // Test hook (lmc_tune "fail_hip_after"): the n-th checked HIP call from now is not made
+    // and counts as failed.  Forces the error paths without any fault on the device.
+    uint32_t fail_hip_after = 0;
     lmc_stats_t stats{};
     int32_t last_hip_error = 0;
 };
@@ -125,9 +134,13 @@ namespace {
 // A failed HIP call is reported through the library's own status and
 // lmc_last_hip_error(); the runtime's per-thread "last error" is cleared so that it does
 // not surface in the caller's next, unrelated HIP call.
+inline bool injected_failure(lmc_ctx *c) {
+    return c->fail_hip_after > 0 && --c->fail_hip_after == 0;
+}
+
 #define HIPCHK(ctx, expr)                                  \
     do {                                                   \
-        hipError_t e_ = (expr);                            \
+        hipError_t e_ = injected_failure(ctx) ? hipErrorUnknown : (expr); \
         if (e_ != hipSuccess) {                            \
             (ctx)->last_hip_error = int32_t(e_);           \
             (void)hipGetLastError();                       \
@@ -151,6 +164,10 @@ private:
     int prev_ = 0;
     bool restore_ = false;
 };
+
+// The mapped flag block holds 16 words: word 0 is set by the gather / scatter kernels on a
+// slot outside the pages, word kCheckWord by the check kernel of LMC_FLAG_VALIDATE_SLOTS.
+constexpr int kCheckWord = 8;
 
 lmc_status_t get_event(lmc_ctx *c, bool timing, hipEvent_t *out) {
     std::vector<hipEvent_t> &pool = timing ? c->free_time_events : c->free_sync_events;
@@ -236,6 +253,12 @@ double seconds_now(const lmc_ctx *c) {
     return std::chrono::duration<double>(std::chrono::steady_clock::now() - c->born).count();
 }
 
+// An event without timing that nothing enqueued later will wait on is free again; see
+// lmc_ctx::waiters for why it may have to be parked first.
+void recycle(lmc_ctx *c, hipEvent_t e) {
+    (c->waiters > 0 ? c->held_events : c->free_sync_events).push_back(e);
+}
+
 // Finish every operation whose last device step has completed: drop its in-flight
 // counts, collect kernel timings, recycle events.
 void reap(lmc_ctx *c) {
@@ -263,8 +286,8 @@ void reap(lmc_ctx *c) {
             i++;
             continue;
         }
-        if (op.done != nullptr) c->free_sync_events.push_back(op.done);
-        for (hipEvent_t e : op.owned_events) c->free_sync_events.push_back(e);
+        if (op.done != nullptr) recycle(c, op.done);
+        for (hipEvent_t e : op.owned_events) recycle(c, e);
         for (int64_t s : op.slots) {
             lmc::SlotMeta &m = c->index.meta(s);
             m.inflight--;
@@ -311,15 +334,15 @@ lmc_status_t order_after(lmc_ctx *c, hipStream_t waiter, hipStream_t stream) {
 lmc_status_t validate_slots(lmc_ctx *c, const int64_t *slot_mapping, int64_t n_tokens,
                             hipStream_t stream) {
     if (!(c->cfg.flags & LMC_FLAG_VALIDATE_SLOTS) || n_tokens == 0) return LMC_OK;
+    // the check has a flag word of its own (kCheckWord): the shared one may be set at any
+    // moment by a kernel of an earlier call that is still running, and that report
+    // belongs to the next lmc_wait, not to this call
     HIPCHK(c, hipStreamSynchronize(stream));
-    const int32_t before = *c->bad_flag_host;
-    *c->bad_flag_host = 0;
+    c->bad_flag_host[kCheckWord] = 0;
     HIPCHK(c, lmc::launch_check_slots(slot_mapping, uint64_t(n_tokens), c->kg.n_slots,
-                                      c->bad_flag_dev, stream));
+                                      c->bad_flag_dev + kCheckWord, stream));
     HIPCHK(c, hipStreamSynchronize(stream));
-    const bool bad = *c->bad_flag_host != 0;
-    *c->bad_flag_host = before;
-    return bad ? LMC_ERR_BADSLOT : LMC_OK;
+    return c->bad_flag_host[kCheckWord] != 0 ? LMC_ERR_BADSLOT : LMC_OK;
 }
 
 lmc_status_t timed_launch(lmc_ctx *c, bool gather, const lmc::LaunchView &view,
@@ -339,12 +362,21 @@ lmc_status_t timed_launch(lmc_ctx *c, bool gather, const lmc::LaunchView &view,
         staging < c->pool_dev + uint64_t(c->n_pool_slots) * uint64_t(c->chunk_bytes))
         s.paced_groups = c->link_groups;
     const uint64_t moved = uint64_t(n_chunks) * view.by_n_lp.d * c->kg.plane_bytes;
+    const hipError_t e =
+        injected_failure(c) ? hipErrorUnknown
+        : gather ? lmc::launch_gather(c->kg, view, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1)
+                 : lmc::launch_scatter(c->kg, view, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1);
+    if (e != hipSuccess) {
+        if (e0 != nullptr) {
+            c->free_time_events.push_back(e0);
+            c->free_time_events.push_back(e1);
+        }
+        HIPCHK(c, e);
+    }
     if (gather) {
-        HIPCHK(c, lmc::launch_gather(c->kg, view, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1));
         c->stats.gather_launches++;
         c->stats.bytes_gathered += moved;
     } else {
-        HIPCHK(c, lmc::launch_scatter(c->kg, view, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1));
         c->stats.scatter_launches++;
         c->stats.bytes_scattered += moved;
     }
@@ -444,12 +476,20 @@ bool several_runs(const int64_t *pool_slots, int64_t k) {
     return false;
 }
 
+// Registers the operation: from here on reap() gives back what it holds.  On an error
+// nothing has been registered and `op` is still the caller's.
 lmc_status_t finish_op(lmc_ctx *c, Op &&op, hipStream_t last_stream, bool enqueued,
                        uint64_t *ticket_out) {
     if (enqueued) {
         lmc_status_t rc = get_event(c, false, &op.done);
         if (rc != LMC_OK) return rc;
-        HIPCHK(c, hipEventRecord(op.done, last_stream));
+        const hipError_t e = injected_failure(c) ? hipErrorUnknown : hipEventRecord(op.done, last_stream);
+        if (e != hipSuccess) {
+            c->free_sync_events.push_back(op.done);
+            op.done = nullptr;
+            HIPCHK(c, e);
+        }
+        op.final_stream = last_stream;
     }
     if (ticket_out) *ticket_out = op.ticket;
     c->ops.push_back(std::move(op));
@@ -537,6 +577,48 @@ void end_use(lmc_ctx *c, const uint64_t *ids, int64_t n) {
         const int64_t s = c->index.find(ids[i]);
         if (s >= 0) c->index.touch(s);
     }
+}
+
+// Sleeps until every event of `evs` has completed, with the context's mutex released so
+// that other threads go on storing, loading and looking up meanwhile.  The events stay
+// valid: whatever reap() frees while somebody sleeps is parked (lmc_ctx::waiters).
+lmc_status_t sync_unlocked(lmc_ctx *c, std::unique_lock<std::mutex> &lock,
+                           const std::vector<hipEvent_t> &evs) {
+    if (evs.empty()) return LMC_OK;
+    c->waiters++;
+    lock.unlock();
+    hipError_t err = hipSuccess;
+    for (hipEvent_t e : evs) {
+        const hipError_t x = hipEventSynchronize(e);
+        if (x != hipSuccess && err == hipSuccess) err = x;
+    }
+    lock.lock();
+    if (--c->waiters == 0) {
+        c->free_sync_events.insert(c->free_sync_events.end(), c->held_events.begin(), c->held_events.end());
+        c->held_events.clear();
+    }
+    if (err != hipSuccess) {
+        c->last_hip_error = int32_t(err);
+        (void)hipGetLastError();  // the runtime keeps a failure as its "last error": take it back
+        return LMC_ERR_HIP;
+    }
+    return LMC_OK;
+}
+
+// The store that fills the slot of chunk `id`, if it is still under way: its `done`
+// event goes to *ev (null = nothing to wait for).  LMC_ERR_MISS / LMC_ERR_BUSY as lmc_get_host.
+lmc_status_t pending_fill(lmc_ctx *c, uint64_t id, int64_t *slot_out, hipEvent_t *ev) {
+    *ev = nullptr;
+    const int64_t s = c->index.find(id);
+    if (s < 0) return LMC_ERR_MISS;
+    *slot_out = s;
+    const uint64_t store_ticket = c->index.meta(s).ready_ticket;
+    if (store_ticket != 0) {
+        const Op *o = find_op(c, store_ticket);
+        if (o != nullptr && o->pending) return LMC_ERR_BUSY;
+        if (o != nullptr) *ev = o->done;
+    }
+    return LMC_OK;
 }
 
 // A chunk whose store is still on its way to the pool must be loaded after that store:
@@ -649,56 +731,67 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
         return force_sync(c, c->s_scatter);
     };
 
-    if (direct && !op.layerwise) {
-        if ((rc = load_direct(lmc::bulk_view(c->kg), 0)) != LMC_OK) return rc;
-    } else if (!op.layerwise) {
-        const lmc::LaunchView view = lmc::bulk_view(c->kg);
-        if ((rc = ring_reslot(c, ring, ring.buf_bytes, c->s_h2d, c->s_scatter, c->s_h2d2)) != LMC_OK) return rc;
-        // The link is the bottleneck and every scatter but the last hides behind the next
-        // copy, so the last group is a single chunk: only its scatter is exposed.
-        const int64_t edge = std::min<int64_t>(c->edge_chunks, per);
-        const int64_t body = (edge > 0 && n_chunks > edge) ? n_chunks - edge : n_chunks;
-        for (int64_t i0 = 0, k = 0; i0 < n_chunks; i0 += k) {
-            k = i0 < body ? std::min(per, body - i0) : n_chunks - i0;
-            if ((rc = load_group(view, 0, i0, k, c->s_h2d, c->s_h2d2)) != LMC_OK) return rc;
-        }
-    } else {
-        // All chunks' share of a few layers at a time: one rectangle copy per run of pool
-        // slots, one scatter launch, one event that says "these layers are in place".
-        const int32_t L = geom.num_layers, P = geom.num_planes;
-        const uint64_t layer_bytes = uint64_t(P) * c->kg.plane_bytes;
-        op.layer_done.assign(size_t(L), nullptr);
-        for (int32_t l0 = 0; l0 < L; l0 += layers_per_step) {
-            const int32_t kk = std::min(layers_per_step, L - l0);
-            const lmc::LaunchView view = lmc::layer_view(c->kg, uint32_t(P), uint32_t(l0), uint32_t(kk));
-            if (direct) {
-                if ((rc = load_direct(view, uint64_t(l0) * layer_bytes)) != LMC_OK) return rc;
-            } else {
-                const int64_t cap = layer_group_chunks(c, ring, view, n_chunks);
-                if ((rc = ring_reslot(c, ring, (uint64_t(cap) * view.chunk_stride + 255) / 256 * 256, c->s_h2d,
-                                      c->s_scatter, c->s_h2d2)) != LMC_OK)
-                    return rc;
-                // Steps alternate between two copy streams: on one stream the runtime puts
-                // an event marker between consecutive copies, which costs the link about
-                // 20 us per step; with two streams the next step's copy is already running.
-                hipStream_t cs = ((l0 / layers_per_step) & 1) ? c->s_h2d2 : c->s_h2d;
-                for (int64_t i0 = 0; i0 < n_chunks; i0 += cap)
-                    if ((rc = load_group(view, uint64_t(l0) * layer_bytes, i0, std::min(cap, n_chunks - i0), cs, nullptr)) != LMC_OK)
-                        return rc;
+    auto enqueue = [&]() -> lmc_status_t {
+        if (direct && !op.layerwise) {
+            if ((rc = load_direct(lmc::bulk_view(c->kg), 0)) != LMC_OK) return rc;
+        } else if (!op.layerwise) {
+            const lmc::LaunchView view = lmc::bulk_view(c->kg);
+            if ((rc = ring_reslot(c, ring, ring.buf_bytes, c->s_h2d, c->s_scatter, c->s_h2d2)) != LMC_OK) return rc;
+            // The link is the bottleneck and every scatter but the last hides behind the next
+            // copy, so the last group is a single chunk: only its scatter is exposed.
+            const int64_t edge = std::min<int64_t>(c->edge_chunks, per);
+            const int64_t body = (edge > 0 && n_chunks > edge) ? n_chunks - edge : n_chunks;
+            for (int64_t i0 = 0, k = 0; i0 < n_chunks; i0 += k) {
+                k = i0 < body ? std::min(per, body - i0) : n_chunks - i0;
+                if ((rc = load_group(view, 0, i0, k, c->s_h2d, c->s_h2d2)) != LMC_OK) return rc;
             }
-            hipEvent_t e;
-            if ((rc = get_event(c, false, &e)) != LMC_OK) return rc;
-            HIPCHK(c, hipEventRecord(e, c->s_scatter));
-            op.owned_events.push_back(e);
-            for (int32_t l = l0; l < l0 + kk; l++) op.layer_done[size_t(l)] = e;
+        } else {
+            // All chunks' share of a few layers at a time: one rectangle copy per run of pool
+            // slots, one scatter launch, one event that says "these layers are in place".
+            const int32_t L = geom.num_layers, P = geom.num_planes;
+            const uint64_t layer_bytes = uint64_t(P) * c->kg.plane_bytes;
+            op.layer_done.assign(size_t(L), nullptr);
+            for (int32_t l0 = 0; l0 < L; l0 += layers_per_step) {
+                const int32_t kk = std::min(layers_per_step, L - l0);
+                const lmc::LaunchView view = lmc::layer_view(c->kg, uint32_t(P), uint32_t(l0), uint32_t(kk));
+                if (direct) {
+                    if ((rc = load_direct(view, uint64_t(l0) * layer_bytes)) != LMC_OK) return rc;
+                } else {
+                    const int64_t cap = layer_group_chunks(c, ring, view, n_chunks);
+                    if ((rc = ring_reslot(c, ring, (uint64_t(cap) * view.chunk_stride + 255) / 256 * 256, c->s_h2d,
+                                          c->s_scatter, c->s_h2d2)) != LMC_OK)
+                        return rc;
+                    // Steps alternate between two copy streams: on one stream the runtime puts
+                    // an event marker between consecutive copies, which costs the link about
+                    // 20 us per step; with two streams the next step's copy is already running.
+                    hipStream_t cs = ((l0 / layers_per_step) & 1) ? c->s_h2d2 : c->s_h2d;
+                    for (int64_t i0 = 0; i0 < n_chunks; i0 += cap)
+                        if ((rc = load_group(view, uint64_t(l0) * layer_bytes, i0, std::min(cap, n_chunks - i0), cs, nullptr)) != LMC_OK)
+                            return rc;
+                }
+                hipEvent_t e;
+                if ((rc = get_event(c, false, &e)) != LMC_OK) return rc;
+                op.owned_events.push_back(e);
+                HIPCHK(c, hipEventRecord(e, c->s_scatter));
+                for (int32_t l = l0; l < l0 + kk; l++) op.layer_done[size_t(l)] = e;
+            }
         }
+        return LMC_OK;
+    };
+    op.slots = pool_slots;
+    const bool layerwise = op.layerwise;
+    if ((rc = enqueue()) == LMC_OK) rc = finish_op(c, std::move(op), c->s_scatter, true, ticket_out);
+    if (rc != LMC_OK) {
+        // Part of the call may be enqueued and still read the pool slots, which nothing
+        // protects (the in-flight counts belong to a registered operation): it is waited
+        // for.  Pages the call was to fill are then in an unspecified state.
+        for (hipStream_t s : {c->s_h2d, c->s_h2d2, c->s_scatter}) (void)hipStreamSynchronize(s);
+        (void)hipGetLastError();
+        for (hipEvent_t e : op.owned_events) recycle(c, e);
+        return rc;
     }
     for (int64_t s : pool_slots) c->index.meta(s).inflight++;
-    op.slots = pool_slots;
     c->stats.chunks_retrieved += uint64_t(n_chunks);
-    const bool layerwise = op.layerwise;
-    rc = finish_op(c, std::move(op), c->s_scatter, true, ticket_out);
-    if (rc != LMC_OK) return rc;
     // bulk: the caller's stream continues when everything is in place; layer-wise: the
     // caller orders its streams per layer with lmc_wait_layer
     if (!layerwise) HIPCHK(c, hipStreamWaitEvent(user, c->ops.back().done, 0));
@@ -787,7 +880,7 @@ lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out) {
             c->bad_flag_host = nullptr;
             return fail(LMC_ERR_HIP);
         }
-        *c->bad_flag_host = 0;
+        std::memset(c->bad_flag_host, 0, 64);
         if (hipHostGetDevicePointer(reinterpret_cast<void **>(&c->bad_flag_dev), c->bad_flag_host, 0) != hipSuccess)
             return fail(LMC_ERR_HIP);
         for (hipStream_t *s : {&c->s_gather, &c->s_d2h, &c->s_h2d, &c->s_scatter, &c->s_h2d2, &c->s_d2h2})
@@ -889,6 +982,18 @@ static bool admit_new_chunks(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks, 
     return fits;
 }
 
+// A store that failed (a HIP error) after its chunks had been admitted.  What is already
+// enqueued may still write the chunks' slots, so it is waited for; then the chunks leave
+// the index again and their slots are free: no id stays behind that promises bytes which
+// never arrived.  (Chunks that eviction removed to make room are not brought back.)
+static void abort_store(lmc_ctx *c, const std::vector<int64_t> &slots) {
+    for (hipStream_t s : {c->s_gather, c->s_d2h, c->s_d2h2}) (void)hipStreamSynchronize(s);
+    (void)hipGetLastError();
+    for (int64_t s : slots) c->index.erase(c->index.meta(s).id);
+    c->stats.chunks_stored -= std::min<uint64_t>(c->stats.chunks_stored, slots.size());
+    reap(c);
+}
+
 // Gather + D2H of the new chunks' part described by `view` (all layers, or a few),
 // group by group through the store ring.
 static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64_t pool_off,
@@ -979,14 +1084,16 @@ lmc_status_t lmc_store(lmc_ctx_t *c, void *const *kv_layers, const int64_t *slot
     c->stats.chunks_stored += new_chunk.size();
     const bool direct = (c->cfg.flags & LMC_FLAG_DIRECT) != 0 ||
                         int64_t(new_chunk.size()) * c->chunk_bytes <= c->direct_store_below;
-    if (!direct &&
-        (rc = ring_reslot(c, c->store_ring, c->store_ring.buf_bytes, c->s_gather, c->s_d2h)) != LMC_OK)
+    rc = direct ? LMC_OK : ring_reslot(c, c->store_ring, c->store_ring.buf_bytes, c->s_gather, c->s_d2h);
+    if (rc == LMC_OK)
+        rc = store_groups(c, lmc::bulk_view(c->kg), 0, ptrs, slot_mapping, new_chunk, op.slots,
+                          c->cfg.staging_chunks, true, direct);
+    if (rc == LMC_OK)
+        rc = finish_op(c, std::move(op), direct ? c->s_gather : c->s_d2h, !new_chunk.empty(), ticket_out);
+    if (rc != LMC_OK) {
+        abort_store(c, op.slots);   // finish_op registers as its last step: op is still whole
         return rc;
-    rc = store_groups(c, lmc::bulk_view(c->kg), 0, ptrs, slot_mapping, new_chunk, op.slots,
-                      c->cfg.staging_chunks, true, direct);
-    if (rc != LMC_OK) return rc;
-    rc = finish_op(c, std::move(op), direct ? c->s_gather : c->s_d2h, !new_chunk.empty(), ticket_out);
-    if (rc != LMC_OK) return rc;
+    }
     return fits ? LMC_OK : LMC_ERR_NOMEM;
 }
 
@@ -1035,30 +1142,49 @@ lmc_status_t lmc_store_layers(lmc_ctx_t *c, uint64_t ticket, int32_t first_layer
     lmc::LayerPtrs ptrs;
     lmc_status_t rc = build_layer_ptrs(c, kv_layers, &ptrs);
     if (rc != LMC_OK) return rc;
-    // this layer's KV was produced by work already on the caller's stream
-    if ((rc = order_after(c, c->s_gather, static_cast<hipStream_t>(stream_to_wait_on))) != LMC_OK) return rc;
     const lmc::LaunchView view = lmc::layer_view(c->kg, uint32_t(geom.num_planes), uint32_t(first_layer),
                                                  uint32_t(n_layers));
     const uint64_t layer_bytes = uint64_t(geom.num_planes) * c->kg.plane_bytes;
     const int64_t cap = layer_group_chunks(c, c->store_ring, view, int64_t(op->new_chunk.size()));
-    if (!(c->cfg.flags & LMC_FLAG_DIRECT) && (rc = ring_reslot(c, c->store_ring, (uint64_t(cap) * view.chunk_stride + 255) / 256 * 256, c->s_gather,
-                          c->s_d2h)) != LMC_OK)
+    const bool direct = (c->cfg.flags & LMC_FLAG_DIRECT) != 0;
+    hipStream_t last = direct ? c->s_gather : c->s_d2h;
+    // this layer's KV was produced by work already on the caller's stream
+    rc = order_after(c, c->s_gather, static_cast<hipStream_t>(stream_to_wait_on));
+    if (rc == LMC_OK && !direct)
+        rc = ring_reslot(c, c->store_ring, (uint64_t(cap) * view.chunk_stride + 255) / 256 * 256, c->s_gather, c->s_d2h);
+    if (rc == LMC_OK)
+        rc = store_groups(c, view, uint64_t(first_layer) * layer_bytes, ptrs, op->slot_mapping, op->new_chunk,
+                          op->slots, cap, false, direct);
+    hipEvent_t e = nullptr;
+    if (rc == LMC_OK) rc = get_event(c, false, &e);
+    if (rc == LMC_OK) {
+        op->owned_events.push_back(e);
+        rc = [&]() -> lmc_status_t {
+            HIPCHK(c, hipEventRecord(e, last));
+            if (first_layer + n_layers == geom.num_layers) {
+                lmc_status_t r = get_event(c, false, &op->done);
+                if (r != LMC_OK) return r;
+                op->owned_events.push_back(op->done);   // given back with the others if the record fails
+                HIPCHK(c, hipEventRecord(op->done, last));
+                op->owned_events.pop_back();
+                op->final_stream = last;
+            }
+            return LMC_OK;
+        }();
+    }
+    if (rc != LMC_OK) {
+        // the store cannot be completed any more: it is taken back as a whole
+        const uint64_t t = op->ticket;
+        auto it = std::find_if(c->ops.begin(), c->ops.end(), [t](const Op &o) { return o.ticket == t; });
+        const Op gone = std::move(*it);
+        c->ops.erase(it);
+        abort_store(c, gone.slots);
+        for (hipEvent_t x : gone.owned_events) recycle(c, x);
         return rc;
-    rc = store_groups(c, view, uint64_t(first_layer) * layer_bytes, ptrs, op->slot_mapping, op->new_chunk,
-                      op->slots, cap, false, (c->cfg.flags & LMC_FLAG_DIRECT) != 0);
-    if (rc != LMC_OK) return rc;
-    hipEvent_t e;
-    if ((rc = get_event(c, false, &e)) != LMC_OK) return rc;
-    hipStream_t last = (c->cfg.flags & LMC_FLAG_DIRECT) ? c->s_gather : c->s_d2h;
-    HIPCHK(c, hipEventRecord(e, last));
-    op->owned_events.push_back(e);
+    }
     for (int32_t l = first_layer; l < first_layer + n_layers; l++) op->layer_done[size_t(l)] = e;
     op->next_layer = first_layer + n_layers;
-    if (op->next_layer == geom.num_layers) {
-        if ((rc = get_event(c, false, &op->done)) != LMC_OK) return rc;
-        HIPCHK(c, hipEventRecord(op->done, last));
-        op->pending = false;
-    }
+    if (op->next_layer == geom.num_layers) op->pending = false;
     return LMC_OK;
 }
 
@@ -1122,7 +1248,12 @@ lmc_status_t lmc_wait(lmc_ctx_t *c, uint64_t ticket) {
     if (ticket >= c->next_ticket) return LMC_ERR_INVAL;
     if (!c->has_device) return LMC_OK;
     DeviceScope dev(c);
-    hipEvent_t last = nullptr;
+    // Operations end on different streams that are not ordered among each other (a staged
+    // store on the D2H stream, a store without staging on the gather stream, every
+    // retrieve on the scatter stream), so the newest operation alone says nothing about
+    // the older ones: the newest event of every such stream is waited for.
+    std::vector<hipStream_t> streams;
+    std::vector<hipEvent_t> last;
     for (const Op &o : c->ops) {
         if (o.ticket > ticket) continue;
         if (o.pending) {
@@ -1131,18 +1262,17 @@ lmc_status_t lmc_wait(lmc_ctx_t *c, uint64_t ticket) {
             if (everything || o.ticket == ticket) return LMC_ERR_BUSY;
             continue;
         }
-        if (o.done != nullptr) last = o.done;
-    }
-    if (last != nullptr) {
-        lock.unlock();
-        hipError_t e = hipEventSynchronize(last);
-        lock.lock();
-        if (e != hipSuccess) {
-            c->last_hip_error = int32_t(e);
-            (void)hipGetLastError();  // the runtime keeps a failure as its "last error": take it back
-            return LMC_ERR_HIP;
+        if (o.done == nullptr) continue;
+        const size_t i = size_t(std::find(streams.begin(), streams.end(), o.final_stream) - streams.begin());
+        if (i == streams.size()) {
+            streams.push_back(o.final_stream);
+            last.push_back(o.done);
+        } else {
+            last[i] = o.done;   // c->ops is in ticket order, and a stream finishes in order
         }
     }
+    const lmc_status_t rc = sync_unlocked(c, lock, last);
+    if (rc != LMC_OK) return rc;
     reap(c);
     if (*c->bad_flag_host != 0) {
         *c->bad_flag_host = 0;
@@ -1236,38 +1366,43 @@ lmc_status_t lmc_drain_evicted(lmc_ctx_t *c, uint64_t *ids_out, int64_t cap, int
 
 lmc_status_t lmc_get_host(lmc_ctx_t *c, uint64_t id, void *host_dst) {
     if (!c || !host_dst) return LMC_ERR_INVAL;
-    std::lock_guard<std::mutex> lock(c->mu);
+    std::unique_lock<std::mutex> lock(c->mu);
     DeviceScope dev(c);
     if (c->has_device) reap(c);
-    const int64_t s = c->index.find(id);
-    if (s < 0) return LMC_ERR_MISS;
-    const uint64_t store_ticket = c->index.meta(s).ready_ticket;
-    if (store_ticket != 0) {
-        const Op *o = find_op(c, store_ticket);
-        if (o != nullptr && o->pending) return LMC_ERR_BUSY;
-        if (o != nullptr && o->done != nullptr) HIPCHK(c, hipEventSynchronize(o->done));
+    // the bytes must have arrived: wait, without holding up other threads, for the store
+    // that fills the slot; the chunk may be gone when this thread is back
+    for (;;) {
+        int64_t s = -1;
+        hipEvent_t ev = nullptr;
+        lmc_status_t rc = pending_fill(c, id, &s, &ev);
+        if (rc != LMC_OK) return rc;
+        if (ev == nullptr || hipEventQuery(ev) == hipSuccess) {
+            std::memcpy(host_dst, c->pool + s * c->chunk_bytes, size_t(c->chunk_bytes));
+            return LMC_OK;
+        }
+        if ((rc = sync_unlocked(c, lock, {ev})) != LMC_OK) return rc;
+        reap(c);
     }
-    std::memcpy(host_dst, c->pool + s * c->chunk_bytes, size_t(c->chunk_bytes));
-    return LMC_OK;
 }
 
 lmc_status_t lmc_chunk_acquire(lmc_ctx_t *c, uint64_t id, const void **host_ptr_out) {
     if (!c || !host_ptr_out) return LMC_ERR_INVAL;
-    std::lock_guard<std::mutex> lock(c->mu);
+    std::unique_lock<std::mutex> lock(c->mu);
     DeviceScope dev(c);
     if (c->has_device) reap(c);
-    const int64_t s = c->index.find(id);
-    if (s < 0) return LMC_ERR_MISS;
-    // the bytes must have arrived: wait for the store that fills the slot
-    const uint64_t store_ticket = c->index.meta(s).ready_ticket;
-    if (store_ticket != 0) {
-        const Op *o = find_op(c, store_ticket);
-        if (o != nullptr && o->pending) return LMC_ERR_BUSY;
-        if (o != nullptr && o->done != nullptr) HIPCHK(c, hipEventSynchronize(o->done));
+    for (;;) {
+        int64_t s = -1;
+        hipEvent_t ev = nullptr;
+        lmc_status_t rc = pending_fill(c, id, &s, &ev);
+        if (rc != LMC_OK) return rc;
+        if (ev == nullptr || hipEventQuery(ev) == hipSuccess) {
+            c->index.meta(s).refs++;
+            *host_ptr_out = c->pool + s * c->chunk_bytes;
+            return LMC_OK;
+        }
+        if ((rc = sync_unlocked(c, lock, {ev})) != LMC_OK) return rc;
+        reap(c);
     }
-    c->index.meta(s).refs++;
-    *host_ptr_out = c->pool + s * c->chunk_bytes;
-    return LMC_OK;
 }
 
 lmc_status_t lmc_chunk_release(lmc_ctx_t *c, uint64_t id) {
@@ -1351,9 +1486,10 @@ lmc_status_t lmc_reset_stats(lmc_ctx_t *c) {
     return LMC_OK;
 }
 
-lmc_status_t lmc_measure_link(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, double *h2d_out,
-                              double *d2h_out) {
+static lmc_status_t measure_link(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, bool by_kernel,
+                                 double *h2d_out, double *d2h_out) {
     if (!c || !h2d_out || !d2h_out || reps < 1 || nbytes == 0) return LMC_ERR_INVAL;
+    if (by_kernel && (nbytes % 16) != 0) return LMC_ERR_INVAL;
     if (!c->has_device) return LMC_ERR_NODEVICE;
     if (nbytes > uint64_t(c->n_pool_slots) * uint64_t(c->chunk_bytes)) return LMC_ERR_INVAL;
     std::lock_guard<std::mutex> lock(c->mu);
@@ -1376,8 +1512,12 @@ lmc_status_t lmc_measure_link(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, doubl
         hipStream_t s = dir == 0 ? c->s_h2d : c->s_d2h;
         for (int r = 0; r < reps + 1; r++) {  // first pass warms up
             hipError_t a = hipEventRecord(e0, s);
-            hipError_t b = dir == 0 ? hipMemcpyAsync(devbuf, c->pool, nbytes, hipMemcpyHostToDevice, s)
-                                    : hipMemcpyAsync(c->pool, devbuf, nbytes, hipMemcpyDeviceToHost, s);
+            const uint32_t groups = c->link_groups ? c->link_groups : 64u;
+            hipError_t b = by_kernel
+                ? (dir == 0 ? lmc::launch_copy_rect(devbuf, nbytes, c->pool_dev, nbytes, nbytes, 1, groups, s)
+                            : lmc::launch_copy_rect(c->pool_dev, nbytes, devbuf, nbytes, nbytes, 1, groups, s))
+                : (dir == 0 ? hipMemcpyAsync(devbuf, c->pool, nbytes, hipMemcpyHostToDevice, s)
+                            : hipMemcpyAsync(c->pool, devbuf, nbytes, hipMemcpyDeviceToHost, s));
             hipError_t d = hipEventRecord(e1, s);
             hipError_t f = hipEventSynchronize(e1);
             float ms = 0.f;
@@ -1398,6 +1538,16 @@ lmc_status_t lmc_measure_link(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, doubl
     *h2d_out = best[0];
     *d2h_out = best[1];
     return rc;
+}
+
+lmc_status_t lmc_measure_link(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, double *h2d_out,
+                              double *d2h_out) {
+    return measure_link(c, nbytes, reps, false, h2d_out, d2h_out);
+}
+
+lmc_status_t lmc_measure_link_kernel(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, double *h2d_out,
+                                     double *d2h_out) {
+    return measure_link(c, nbytes, reps, true, h2d_out, d2h_out);
 }
 
 lmc_status_t lmc_probe_stream(lmc_ctx_t *c, void *stream, uint32_t *mask_out) {
@@ -1542,6 +1692,9 @@ lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
     } else if (k == "link_groups") {
         if (value > 65536) return LMC_ERR_INVAL;
         c->link_groups = uint32_t(value);
+    } else if (k == "fail_hip_after") {
+        if (value > 0xFFFFFFFFll) return LMC_ERR_INVAL;
+        c->fail_hip_after = uint32_t(value);
     } else if (k == "nt_load" && value <= 1) {
         c->shape.nt_load = value != 0;
     } else if (k == "nt_store" && value <= 1) {

@@ -33,7 +33,7 @@ EXPORTS = [
     "lmc_lookup", "lmc_store", "lmc_retrieve", "lmc_retrieve_batch", "lmc_retrieve_layerwise",
     "lmc_store_begin", "lmc_store_layers", "lmc_wait_layer", "lmc_wait", "lmc_gather",
     "lmc_scatter", "lmc_put_host", "lmc_get_host", "lmc_find_slot", "lmc_pin", "lmc_unpin",
-    "lmc_clear", "lmc_drain_evicted", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_measure_link_duplex",
+    "lmc_clear", "lmc_drain_evicted", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_measure_link_kernel", "lmc_measure_link_duplex",
     "lmc_copy", "lmc_tune", "lmc_probe_stream", "lmc_chunk_acquire", "lmc_chunk_release", "lmc_tier_open", "lmc_tier_close",
     "lmc_tier_write", "lmc_tier_wait", "lmc_tier_lookup", "lmc_tier_read", "lmc_tier_errno",
     "lmc_tier_get_stats",
@@ -147,6 +147,8 @@ def _lib():
             "lmc_get_stats": (st, [vp, ctypes.POINTER(lmc_stats_t)]),
             "lmc_reset_stats": (st, [vp]),
             "lmc_measure_link": (st, [vp, u64, i32, ctypes.POINTER(ctypes.c_double),
+                                      ctypes.POINTER(ctypes.c_double)]),
+            "lmc_measure_link_kernel": (st, [vp, u64, i32, ctypes.POINTER(ctypes.c_double),
                                       ctypes.POINTER(ctypes.c_double)]),
             "lmc_measure_link_duplex": (st, [vp, u64, i32, ctypes.POINTER(ctypes.c_double)]),
             "lmc_copy": (st, [vp, vp, vp, u64, vp]),
@@ -416,6 +418,13 @@ class Context:
         a, b = ctypes.c_double(), ctypes.c_double()
         self._check(_lib().lmc_measure_link(self._h, nbytes, reps, ctypes.byref(a), ctypes.byref(b)),
                     "lmc_measure_link")
+        return a.value, b.value
+
+    def measure_link_kernel(self, nbytes, reps=3):
+        """(h2d GB/s, d2h GB/s) of the library's link-paced copy kernel over the same link."""
+        a, b = ctypes.c_double(), ctypes.c_double()
+        self._check(_lib().lmc_measure_link_kernel(self._h, nbytes, reps, ctypes.byref(a), ctypes.byref(b)),
+                    "lmc_measure_link_kernel")
         return a.value, b.value
 
     def measure_link_duplex(self, nbytes, reps=3):

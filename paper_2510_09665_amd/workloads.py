@@ -122,12 +122,21 @@ def rng_for(name, stream=0):
     return np.random.Generator(np.random.PCG64([SEED_BASE + CONFIGS[name]["id"], stream]))
 
 
-def bf16_uniform(rng, n):
-    """n bf16 values uniform in [-1, 1): drawn in fp32, rounded to nearest even, as uint16."""
-    f = rng.random(n, dtype=np.float32) * np.float32(2.0) - np.float32(1.0)
-    u = f.view(np.uint32)
-    return ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)) \
-        .astype(np.uint16)
+def bf16_uniform(rng, n, block=1 << 20):
+    """n bf16 values uniform in [-1, 1): drawn in fp32, rounded to nearest even, as uint16.
+    Worked through in blocks that stay in cache (the 10 GiB of configuration 3 are drawn
+    on the host); the values do not depend on the block size."""
+    out = np.empty(n, dtype=np.uint16)
+    buf = np.empty(min(block, max(n, 1)), dtype=np.float32)
+    for i in range(0, n, block):
+        f = buf[:min(block, n - i)]
+        rng.random(out=f, dtype=np.float32)
+        f *= np.float32(2.0)
+        f -= np.float32(1.0)
+        u = f.view(np.uint32)
+        u += np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+        out[i:i + f.size] = u >> np.uint32(16)
+    return out
 
 
 _FP8_OK = np.array([b for b in range(256) if b not in (0x7F, 0xFF, 0x80)], dtype=np.uint8)

@@ -22,7 +22,9 @@ class PagedKV:
     blocks, payload that also lives in compact host layers: block blocks[i] of the
     device is block i of the compact geometry `gc`."""
 
-    def __init__(self, geom, blocks, rng=None, device="cuda", fill="payload"):
+    def __init__(self, geom, blocks, rng=None, device="cuda", fill="payload", threads=1):
+        """threads > 1: the layers' payload is drawn in parallel, each layer from its own
+        child generator of rng (for the configurations with GiBs of payload)."""
         self.g = geom
         self.blocks = np.asarray(blocks, dtype=np.int64)
         assert np.unique(self.blocks).size == self.blocks.size
@@ -31,10 +33,15 @@ class PagedKV:
         self.dev = []
         self.host = []
         tb = torch.from_numpy(self.blocks).to(device)
+        drawn = None
+        if fill == "payload" and threads > 1:
+            from concurrent.futures import ThreadPoolExecutor
+            with ThreadPoolExecutor(threads) as ex:
+                drawn = list(ex.map(lambda r: W.payload_bytes(r, geom, self.gc.layer_bytes), rng.spawn(geom.L)))
         for l in range(geom.L):
             d = torch.full((geom.layer_bytes,), sentinel_byte(l), dtype=torch.uint8, device=device)
             if fill == "payload":
-                h = W.payload_bytes(rng, geom, self.gc.layer_bytes)
+                h = drawn[l] if drawn is not None else W.payload_bytes(rng, geom, self.gc.layer_bytes)
                 W.page_view(geom, d)[:, tb] = W.page_view(self.gc, torch.from_numpy(h).to(device))
             else:
                 h = np.full(self.gc.layer_bytes, sentinel_byte(l), dtype=np.uint8)

@@ -190,3 +190,28 @@ def test_size_arithmetic_of_the_paper():
     assert W.geometry("mla_bf16").chunk_bytes == 17989632
     assert W.geometry("mla_fp8").chunk_bytes == 8994816
     assert W.geometry("tiny").chunk_bytes == 512 * 1024
+
+
+def test_timing_driver_only_calls_the_oracle():
+    """oracle/oracle_timing.c (the thread fan-out behind the benchmark's CPU baseline) must
+    leave exactly what the oracle's own gather and scatter leave, whatever the thread count."""
+    import dataclasses
+    g = dataclasses.replace(W.geometry("tiny"), NB=48)
+    rng = np.random.default_rng(5)
+    n = 3
+    src = [rng.integers(0, 256, g.layer_bytes, dtype=np.uint8) for _ in range(g.L)]
+    blocks = rng.permutation(g.NB)
+    s_slots = W.slots_from_blocks(g, blocks, n * g.CT)
+    l_slots = W.slots_from_blocks(g, blocks[::-1].copy(), n * g.CT)
+    want_pool = oracle.gather(g, src, s_slots)
+    want_dst = [np.full(g.layer_bytes, 0x5A, dtype=np.uint8) for _ in range(g.L)]
+    oracle.scatter(g, want_pool, l_slots, want_dst)
+    for threads in (1, 2, 5):
+        pool = np.zeros(n * g.chunk_bytes, dtype=np.uint8)
+        buffers = np.zeros(threads * g.chunk_bytes, dtype=np.uint8)
+        dst = [np.full(g.layer_bytes, 0x5A, dtype=np.uint8) for _ in range(g.L)]
+        assert oracle.time_pass(g, src, dst, s_slots, l_slots, pool, buffers, threads, False) > 0
+        assert np.array_equal(pool.reshape(n, -1), want_pool)
+        assert oracle.time_pass(g, src, dst, s_slots, l_slots, pool, buffers, threads, True) > 0
+        for a, b in zip(dst, want_dst):
+            assert np.array_equal(a, b)
