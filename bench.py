@@ -29,6 +29,9 @@ Also reported in the same JSON line:
   configs      every other benchmark configuration end to end (1 tiny, 2 Llama-3-8B,
                4 batched multi-request retrieve, 5 MLA in bf16 and fp8): store / retrieve
                as a fraction of the link peak and the kernels alone as a fraction of 8 TB/s
+  page_placement  the two kernels against where the engine puts its pages: random 32 KiB
+               pages, the same pages in address order, pages shuffled inside 2 MiB windows,
+               all layers of a block adjacent; and the scatter launch in destination order
   duplex, direct, layerwise, overlap_with_compute, fragmented_pool, small_request
                the other modes of the path on the Llama-3-8B shape (16 chunks, 512 MiB)
   cpu_baseline the CPU oracle doing the same store + retrieve on a stated sample, chunks
@@ -160,20 +163,24 @@ def link_peaks(ctx, pool_bytes):
             "duplex_peak_gbps": duplex}
 
 
-def kernel_only(torch, ctx, W, name, g, kv, n_chunks, dev, stream, slots=None, iters=6, reps=3):
-    """Seconds per launch of the gather, the scatter and a plain copy of the same size over
-    the whole request in one launch (HIP events on `stream`).  Requests below 2 GiB rotate
-    over four block sets and four staging buffers, so that nothing is served from the
-    256 MB Infinity Cache."""
+def kernel_only(torch, ctx, W, name, g, src, dst, n_chunks, dev, stream, gather_slots=None, scatter_slots=None,
+                iters=6, reps=3):
+    """Seconds per launch of the gather (pages of `src` -> staging), the scatter (staging ->
+    other pages, in `dst`: a retrieve fills fresh pages) and a plain copy of the same size,
+    each over the whole request in one launch (HIP events on `stream`).  Requests below
+    2 GiB rotate over four block sets and four staging buffers, so that nothing is served
+    from the 256 MB Infinity Cache."""
     nbytes = n_chunks * g.chunk_bytes
     n_rot = 1 if nbytes >= (2 << 30) else 4
-    if slots is None:
-        slots = [torch.from_numpy(W.sequence(name, g, stream=10 + r)["store_slots"]).to(dev) for r in range(n_rot)]
+    if gather_slots is None:
+        seqs = [W.sequence(name, g, stream=10 + r) for r in range(n_rot)]
+        gather_slots = [torch.from_numpy(q["store_slots"]).to(dev) for q in seqs]
+        scatter_slots = [torch.from_numpy(q["load_slots"]).to(dev) for q in seqs]
     stagings = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(n_rot)]
     spare = torch.empty(nbytes, dtype=torch.uint8, device=dev) if n_rot == 1 else None
     out = []
-    for fn in (lambda r: ctx.gather(kv, slots[r % len(slots)], n_chunks, stagings[r], stream),
-               lambda r: ctx.scatter(stagings[r], slots[r % len(slots)], n_chunks, kv, stream),
+    for fn in (lambda r: ctx.gather(src, gather_slots[r % len(gather_slots)], n_chunks, stagings[r], stream),
+               lambda r: ctx.scatter(stagings[r], scatter_slots[r % len(scatter_slots)], n_chunks, dst, stream),
                lambda r: ctx.copy(stagings[(r + 1) % n_rot] if n_rot > 1 else spare, stagings[r], nbytes // 16 * 16, stream)):
         for r in range(n_rot):
             fn(r)
@@ -211,7 +218,7 @@ def other_configs(torch, lmc, W, dev, stream, timed, peaks):
         g = W.geometry(name)
         seq = W.sequence(name, g)
         n = seq["tokens"].size // g.CT
-        kv, _ = make_pages(torch, W, g, seq["store_blocks"], dev, W.SEED_BASE + W.CONFIGS[name]["id"])
+        kv, fresh = make_pages(torch, W, g, seq["store_blocks"], dev, W.SEED_BASE + W.CONFIGS[name]["id"])
         d_s, d_l = torch.from_numpy(seq["store_slots"]).to(dev), torch.from_numpy(seq["load_slots"]).to(dev)
         ctx = lmc.Context(g, max(n * g.chunk_bytes, 64 << 20), staging_chunks=staging, device=0)
         ids = ctx.hash_chunks(seq["tokens"])
@@ -222,9 +229,9 @@ def other_configs(torch, lmc, W, dev, stream, timed, peaks):
         # best of a dozen: for a few seconds after memory of this size has been allocated or
         # freed in the process, the runtime's device-to-host copies can run at half speed
         ts = timed(st, reps=12)
-        tl = timed(lambda: ctx.wait(ctx.retrieve(ids, d_l, kv, stream)), reps=6)
+        tl = timed(lambda: ctx.wait(ctx.retrieve(ids, d_l, fresh, stream)), reps=6)
         nbytes = n * g.chunk_bytes
-        tg, tsc, tc = kernel_only(torch, ctx, W, name, g, kv, n, dev, stream)
+        tg, tsc, tc = kernel_only(torch, ctx, W, name, g, kv, fresh, n, dev, stream)
         res[name] = {"chunks": n, "payload_bytes": nbytes,
                      "store_gbps": round(nbytes / ts / 1e9, 2), "retrieve_gbps": round(nbytes / tl / 1e9, 2),
                      "store_frac_of_d2h_peak": round(nbytes / ts / 1e9 / d2h, 4),
@@ -235,7 +242,7 @@ def other_configs(torch, lmc, W, dev, stream, timed, peaks):
             res[name]["note"] = ("half a MiB: launch- and latency-bound, no measure of the link or of HBM; by "
                                  "the library's size rule it moves without staging, in one launch each way")
         ctx.destroy()
-        del kv
+        del kv, fresh
     name = "batch_8b"
     g = W.geometry(name)
     reqs = W.request_mix(name, g)
@@ -252,13 +259,122 @@ def other_configs(torch, lmc, W, dev, stream, timed, peaks):
     d_sl = torch.from_numpy(np.concatenate([r["load_slots"] for r in reqs])).to(dev)
     t = timed(lambda: ctx.wait(ctx.retrieve_batch(off, ids_all, d_sl, kv, stream)), reps=3)
     nbytes = n_hit * g.chunk_bytes
-    tg, tsc, tc = kernel_only(torch, ctx, W, name, g, kv, n_hit, dev, stream, slots=[d_sl], iters=3)
+    tg, tsc, tc = kernel_only(torch, ctx, W, name, g, kv, kv, n_hit, dev, stream, gather_slots=[d_sl],
+                              scatter_slots=[d_sl], iters=3)
     res[name] = {"requests": len(reqs), "hit_chunks": n_hit, "payload_bytes": nbytes,
                  "retrieve_batch_gbps": round(nbytes / t / 1e9, 2),
                  "retrieve_frac_of_h2d_peak": round(nbytes / t / 1e9 / h2d, 4),
                  "retrieve_ms": round(t * 1e3, 1),
                  "kernels_alone": kernel_report(nbytes, tg, tsc, tc)}
     ctx.destroy()
+    return res
+
+
+def random_pages_sample(torch, lmc, W, dev, stream):
+    """Gather / scatter / copy read + write GB/s over 1024 random 32 KiB pages of the
+    Llama-3-8B shape (64 chunks, 2 GiB per launch), pages and staging allocated now.  Run
+    once as the very first thing of the process and once late: where in the life of the
+    process the pages were allocated moves the kernels by several per cent."""
+    name = SECONDARY
+    g = W.geometry(name)
+    n_chunks = 64
+    n_tok, nbytes = n_chunks * g.CT, n_chunks * g.chunk_bytes
+    rand = W.rng_for(name, stream=50).permutation(g.NB)[:n_tok // g.BS]
+    d = torch.from_numpy(W.slots_from_blocks(g, rand, n_tok)).to(dev)
+    kv = [torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev) for _ in range(g.L)]
+    staging = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    spare = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    res = {}
+    with lmc.Context(g, 64 << 20, device=0) as ctx:
+        for key, fn in (("gather", lambda: ctx.gather(kv, d, n_chunks, staging, stream)),
+                        ("scatter", lambda: ctx.scatter(staging, d, n_chunks, kv, stream)),
+                        ("copy_kernel", lambda: ctx.copy(spare, staging, nbytes, stream))):
+            fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            best = 1e30
+            for _ in range(3):
+                e0.record(stream)
+                for _ in range(6):
+                    fn()
+                e1.record(stream)
+                e1.synchronize()
+                best = min(best, e0.elapsed_time(e1) / 6 * 1e-3)
+            res[key + "_hbm_gbps"] = round(2 * nbytes / best / 1e9, 1)
+            res[key + "_frac_of_hbm_peak"] = round(2 * nbytes / best / 1e9 / HBM_PEAK_GBPS, 4)
+        ctx.wait()
+    return res
+
+
+def placement_leg(torch, lmc, W, dev, stream):
+    """What the gather / scatter rate depends on: where the engine puts its pages.  The
+    same kernels, the Llama-3-8B shape, 64 chunks (2 GiB, far beyond the Infinity Cache)
+    per launch, read + write GB/s against the 8 TB/s peak:
+      random            1024 of 8192 blocks in seeded random order (what the benchmark's
+                        configurations prescribe)
+      address_order     the same blocks visited in ascending address order
+      contiguous        blocks 0..1023 in order (both sides of the copy linear)
+      window_shuffled   1024 consecutive blocks shuffled inside 2 MiB windows (64 pages)
+      random_dest_order random, and the scatter launch in the order of the destination
+                        (lmc_tune "scatter_order": rows visited in ascending slot order)
+      block_major       random blocks of an engine that keeps all layers of a block
+                        together, [NB][L][P][BS][H][D] in one allocation: 2 MiB per block
+    and the plain copy kernel of the same size as the ceiling."""
+    name = SECONDARY
+    g = W.geometry(name)
+    n_chunks = 64
+    n_tok = n_chunks * g.CT
+    nb = n_tok // g.BS
+    nbytes = n_chunks * g.chunk_bytes
+    rng = W.rng_for(name, stream=50)
+    rand = rng.permutation(g.NB)[:nb]
+    win = np.arange(nb).reshape(-1, (2 << 20) // g.page_bytes)
+    win = np.concatenate([rng.permutation(w_) for w_ in win])
+    patterns = {"random": rand, "address_order": np.sort(rand), "contiguous": np.arange(nb), "window_shuffled": win}
+    kv = [torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev) for _ in range(g.L)]
+    staging = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    spare = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+    def rate(fn, iters=6, reps=3):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        best = 1e30
+        for _ in range(reps):
+            e0.record(stream)
+            for _ in range(iters):
+                fn()
+            e1.record(stream)
+            e1.synchronize()
+            best = min(best, e0.elapsed_time(e1) / iters * 1e-3)
+        return round(2 * nbytes / best / 1e9, 1)
+    res = {"chunks_per_launch": n_chunks, "bytes_per_launch": 2 * nbytes, "page_bytes": g.page_bytes}
+    with lmc.Context(g, 64 << 20, device=0) as ctx:
+        for label, blocks in patterns.items():
+            d = torch.from_numpy(W.slots_from_blocks(g, blocks, n_tok)).to(dev)
+            res[label] = {"gather_hbm_gbps": rate(lambda: ctx.gather(kv, d, n_chunks, staging, stream)),
+                          "scatter_hbm_gbps": rate(lambda: ctx.scatter(staging, d, n_chunks, kv, stream))}
+        d = torch.from_numpy(W.slots_from_blocks(g, rand, n_tok)).to(dev)
+        ctx.tune("scatter_order", 2)
+        res["random_dest_order"] = {}
+        for key, rows in (("groups_of_256_rows", 256), ("plane_by_plane", 0)):
+            ctx.tune("ordered_group_rows", rows)
+            res["random_dest_order"]["scatter_hbm_gbps_" + key] = rate(lambda: ctx.scatter(staging, d, n_chunks, kv, stream))
+        ctx.tune("scatter_order", 0)
+        res["copy_kernel_hbm_gbps"] = rate(lambda: ctx.copy(spare, staging, nbytes, stream))
+        ctx.wait()
+    del kv
+    bm = W.BlockMajorKV(g)
+    big = torch.zeros(bm.total_bytes, dtype=torch.uint8, device=dev)
+    layers = [big.data_ptr() + bm.layer_offset(l) for l in range(g.L)]
+    with lmc.Context(bm, 64 << 20, device=0) as ctx:
+        d = torch.from_numpy(W.slots_from_blocks(g, rand, n_tok)).to(dev)
+        res["block_major"] = {"gather_hbm_gbps": rate(lambda: ctx.gather(layers, d, n_chunks, staging, stream)),
+                              "scatter_hbm_gbps": rate(lambda: ctx.scatter(staging, d, n_chunks, layers, stream)),
+                              "contiguous_bytes_per_block": bm.block_stride}
+        ctx.wait()
+    for v in res.values():
+        if isinstance(v, dict):
+            for k_ in [k_ for k_ in v if k_.endswith("_hbm_gbps")]:
+                v[k_.replace("_hbm_gbps", "_frac_of_hbm_peak")] = round(v[k_] / HBM_PEAK_GBPS, 4)
     return res
 
 
@@ -547,9 +663,9 @@ def main():
                     help="steps measured right after set-up, before anything settles (0 = none)")
     ap.add_argument("--settle-seconds", type=float, default=20.0,
                     help="upper limit for the untimed settling phase before the warm-up (0 = none)")
-    ap.add_argument("--legs", default="pipeline,link,device,configs,duplex,direct,layerwise,overlap,"
+    ap.add_argument("--legs", default="pipeline,link,device,configs,placement,duplex,direct,layerwise,overlap,"
                                       "fragmented,small,cpu",
-                    help="comma list of pipeline (always run), link, device, configs, duplex, direct, "
+                    help="comma list of pipeline (always run), link, device, configs, placement, duplex, direct, "
                          "layerwise, overlap, fragmented, small, cpu: the extra measurements to make; "
                          "profiling runs use a subset")
     ap.add_argument("--tune", action="append", default=[], help="key=value for lmc_tune")
@@ -570,6 +686,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream()
+    first_pages = random_pages_sample(torch, lmc, W, dev, stream) if "placement" in legs else None
     g = W.geometry(WORKLOAD)
     seq = W.sequence(WORKLOAD, g)
     n_chunks = seq["tokens"].size // g.CT
@@ -578,7 +696,6 @@ def main():
     src, dst = make_pages(torch, W, g, seq["store_blocks"], dev, W.SEED_BASE + W.CONFIGS[WORKLOAD]["id"])
     d_store = torch.from_numpy(seq["store_slots"]).to(dev)
     d_load = torch.from_numpy(seq["load_slots"]).to(dev)
-    stream = torch.cuda.current_stream()
 
     pool_bytes = max((n_chunks + 2) * g.chunk_bytes, 2 << 30)
     ctx = lmc.Context(g, pool_bytes, num_staging=args.num_staging,
@@ -725,7 +842,8 @@ def main():
     device = None
     if "device" in legs:
         ctx.tune("timing", 0)     # back-to-back launches, no per-launch events in between
-        tg, tsc, tc = kernel_only(torch, ctx, W, WORKLOAD, g, src, n_chunks, dev, stream, slots=[d_store], iters=3)
+        tg, tsc, tc = kernel_only(torch, ctx, W, WORKLOAD, g, src, dst, n_chunks, dev, stream,
+                                  gather_slots=[d_store], scatter_slots=[d_load], iters=3)
         device = {"chunks_per_launch": n_chunks}
         device.update(kernel_report(payload_one_way, tg, tsc, tc))
         ctx.tune("timing", 1)
@@ -753,6 +871,11 @@ def main():
         out.update(mode_legs(torch, lmc, W, dev, stream, legs, args, timed, peaks))
     if "small" in legs:
         out["small_request"] = small_leg(torch, lmc, W, dev, stream, timed)
+    if "placement" in legs:
+        out["page_placement"] = placement_leg(torch, lmc, W, dev, stream)
+        out["page_placement"]["random_pages_allocated_first_in_the_process"] = first_pages
+        out["page_placement"]["random_pages_allocated_late_in_the_process"] = \
+            random_pages_sample(torch, lmc, W, dev, stream)
     ctx.destroy()
     if "cpu" in legs:
         out["cpu_baseline"] = cpu_baseline()

@@ -501,7 +501,13 @@ lmc_status_t lmc_probe_stream(lmc_ctx_t *ctx, void *stream, uint32_t *mask_out);
  * LMC_FLAG_TIMING), "direct_store_below" / "direct_retrieve_below" (bytes, default 64 MiB
  * each: an lmc_store with at most that many new bytes, or an lmc_retrieve /
  * lmc_retrieve_batch of at most that many bytes, goes the LMC_FLAG_DIRECT way: one launch
- * instead of kernel, event, copy, event; 0 = never), "fail_hip_after" (for tests of the
+ * instead of kernel, event, copy, event; 0 = never), "scatter_order" (default 0; 1 or 2:
+ * scatter launches visit their rows in ascending slot order, built on the device, so that
+ * the writes sweep every plane once; 1 = only launches with at least "ordered_min_pages"
+ * pages that cover at least one block in "ordered_min_density_inv" of a plane, 2 = every
+ * launch; "ordered_group_rows": rows per group, 0 = plane by plane.  Same bytes; on MI355X
+ * it measured slower than the plain order at every density, see the benchmark's
+ * page_placement figures), "fail_hip_after" (for tests of the
  * error paths: the n-th HIP call the library checks from now on is not made and counts as
  * failed, once; 0 = off.  Nothing on the device goes wrong).
  * Unknown key or out-of-range value: LMC_ERR_INVAL. */

@@ -90,6 +90,19 @@ struct lmc_ctx {
     std::vector<CopyTiming> copy_timings;
     std::chrono::steady_clock::time_point born = std::chrono::steady_clock::now();
     int64_t edge_chunks = 1;  // size of the group at the exposed end of a pipeline; 0 = no special group
+    // Scatter launches in the order of the destination (lmc_kernels.hpp): 0 = never, 1 = when
+    // the launch fills enough pages per plane for neighbours to exist (ordered_min_pages pages
+    // and at least one block in ordered_min_density_inv of the plane), 2 = whenever possible.
+    // Off: measured on MI355X it loses to the plain order at every density tried (2048 of
+    // 8192, 6480 of 16384, 4096 of 8192 blocks per plane: 2-6 % slower), because the jumps it
+    // takes off the writes land on the reads of the staging buffer.  Kept as a switch so that
+    // the benchmark can show the comparison.
+    int32_t scatter_order = 0;
+    int64_t ordered_min_pages = 1024, ordered_min_density_inv = 8;
+    lmc::OrderScratch order{};         // device scratch of such launches, grown on demand
+    uint64_t order_cap_tokens = 0;
+    hipEvent_t order_free = nullptr;   // the last such launch has finished with the scratch
+    std::vector<void *> order_retired; // outgrown scratch, freed with the context
     uint64_t use_calls = 0;         // number of the latest call that used chunks (recency of use)
     std::vector<uint64_t> evicted;  // LMC_FLAG_EVICT_LRU: ids evicted and not yet drained
     // Bulk calls that move at most this many bytes skip staging and the copy engine (the
@@ -345,6 +358,59 @@ lmc_status_t validate_slots(lmc_ctx *c, const int64_t *slot_mapping, int64_t n_t
     return c->bad_flag_host[kCheckWord] != 0 ? LMC_ERR_BADSLOT : LMC_OK;
 }
 
+// Does this scatter launch go in the order of the destination?  It pays when the launch
+// finds neighbours among its pages: many pages per plane, and a fair share of the plane.
+bool use_ordered_scatter(const lmc_ctx *c, const lmc::LaunchView &view, uint64_t n_tokens) {
+    if (c->scatter_order == 0 || !lmc::ordered_scatter_fits(c->kg, view, c->shape, n_tokens)) return false;
+    if (c->scatter_order >= 2) return true;
+    const int64_t pages = int64_t(n_tokens) / c->cfg.geom.block_size;
+    return pages >= c->ordered_min_pages && pages * c->ordered_min_density_inv >= int64_t(c->cfg.geom.num_blocks);
+}
+
+// The scratch of an ordered launch: allocated when first needed, grown when a launch has
+// more tokens than any before (the outgrown arrays may still be in use by a launch under
+// way and are kept until the context goes).  `stream` is made to wait for the previous
+// ordered launch, which may have run on another stream: one set serves one launch at a time.
+lmc_status_t prepare_order_scratch(lmc_ctx *c, uint64_t n_tokens, hipStream_t stream) {
+    auto alloc = [&](void **p, uint64_t bytes) -> lmc_status_t {
+        const hipError_t e = injected_failure(c) ? hipErrorOutOfMemory : hipMalloc(p, bytes);
+        if (e != hipSuccess) {
+            *p = nullptr;
+            c->last_hip_error = int32_t(e);
+            (void)hipGetLastError();
+            return e == hipErrorOutOfMemory ? LMC_ERR_NOMEM : LMC_ERR_HIP;
+        }
+        return LMC_OK;
+    };
+    lmc_status_t rc = LMC_OK;
+    if (c->order.token_at == nullptr) {
+        void *a = nullptr, *b = nullptr, *n = nullptr;
+        rc = alloc(&a, lmc::order_table_words(c->kg) * 4);
+        if (rc == LMC_OK) rc = alloc(&b, lmc::order_count_words(c->kg) * 4);
+        if (rc == LMC_OK) rc = alloc(&n, 256);
+        if (rc == LMC_OK) rc = get_event(c, false, &c->order_free);
+        if (rc != LMC_OK) {
+            for (void *p : {a, b, n})
+                if (p) (void)hipFree(p);
+            return rc;
+        }
+        c->order.token_at = static_cast<uint32_t *>(a);
+        c->order.counts = static_cast<uint32_t *>(b);
+        c->order.n_rows = static_cast<uint32_t *>(n);
+    } else if (c->order_cap_tokens > 0) {
+        HIPCHK(c, hipStreamWaitEvent(stream, c->order_free, 0));
+    }
+    if (n_tokens > c->order_cap_tokens) {
+        void *p = nullptr;
+        const uint64_t cap = std::max<uint64_t>(n_tokens, 2 * c->order_cap_tokens);
+        if ((rc = alloc(&p, cap * 8)) != LMC_OK) return rc;
+        if (c->order.pairs != nullptr) c->order_retired.push_back(c->order.pairs);
+        c->order.pairs = static_cast<uint2 *>(p);
+        c->order_cap_tokens = cap;
+    }
+    return LMC_OK;
+}
+
 lmc_status_t timed_launch(lmc_ctx *c, bool gather, const lmc::LaunchView &view,
                           const lmc::LayerPtrs &ptrs, const int64_t *slots, uint32_t n_chunks,
                           uint8_t *staging, hipStream_t stream) {
@@ -362,10 +428,25 @@ lmc_status_t timed_launch(lmc_ctx *c, bool gather, const lmc::LaunchView &view,
         staging < c->pool_dev + uint64_t(c->n_pool_slots) * uint64_t(c->chunk_bytes))
         s.paced_groups = c->link_groups;
     const uint64_t moved = uint64_t(n_chunks) * view.by_n_lp.d * c->kg.plane_bytes;
-    const hipError_t e =
+    const uint64_t n_tokens = uint64_t(n_chunks) * c->kg.chunk_tokens;
+    const bool ordered = !gather && s.paced_groups == 0 && use_ordered_scatter(c, view, n_tokens);
+    if (ordered) {
+        const lmc_status_t rc = prepare_order_scratch(c, n_tokens, stream);
+        if (rc != LMC_OK) {
+            if (e0 != nullptr) {
+                c->free_time_events.push_back(e0);
+                c->free_time_events.push_back(e1);
+            }
+            return rc;
+        }
+    }
+    hipError_t e =
         injected_failure(c) ? hipErrorUnknown
-        : gather ? lmc::launch_gather(c->kg, view, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1)
-                 : lmc::launch_scatter(c->kg, view, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1);
+        : gather  ? lmc::launch_gather(c->kg, view, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1)
+        : ordered ? lmc::launch_scatter_ordered(c->kg, view, s, ptrs, slots, uint32_t(n_tokens), c->order, staging,
+                                                c->bad_flag_dev, stream, e0, e1)
+                  : lmc::launch_scatter(c->kg, view, s, ptrs, slots, n_chunks, staging, c->bad_flag_dev, stream, e0, e1);
+    if (ordered && e == hipSuccess) e = hipEventRecord(c->order_free, stream);
     if (e != hipSuccess) {
         if (e0 != nullptr) {
             c->free_time_events.push_back(e0);
@@ -529,17 +610,19 @@ lmc_status_t ring_reslot(lmc_ctx *c, Ring &r, uint64_t slot_bytes, hipStream_t p
         if (rc == LMC_OK && producer2 != nullptr) rc = order_after(c, producer2, consumer);
         if (rc != LMC_OK) return rc;
     }
-    r.slot_bytes = slot_bytes;
-    r.slots_per_buf = uint32_t(std::max<uint64_t>(1, std::min<uint64_t>(r.buf_bytes / slot_bytes, 32)));
-    const size_t total = r.buf.size() * r.slots_per_buf;
-    while (r.filled.size() < total) {
-        hipEvent_t a, b;
-        lmc_status_t rc = get_event(c, false, &a);
-        if (rc == LMC_OK) rc = get_event(c, false, &b);
+    // the new division takes effect only when its events exist: a failure on the way
+    // leaves the ring as it was
+    const uint32_t per_buf = uint32_t(std::max<uint64_t>(1, std::min<uint64_t>(r.buf_bytes / slot_bytes, 32)));
+    const size_t total = r.buf.size() * per_buf;
+    while (r.filled.size() < total || r.drained.size() < total) {
+        std::vector<hipEvent_t> &v = r.filled.size() < total ? r.filled : r.drained;
+        hipEvent_t e;
+        lmc_status_t rc = get_event(c, false, &e);
         if (rc != LMC_OK) return rc;
-        r.filled.push_back(a);
-        r.drained.push_back(b);
+        v.push_back(e);
     }
+    r.slot_bytes = slot_bytes;
+    r.slots_per_buf = per_buf;
     r.used.assign(total, 0);
     r.pos = 0;
     return LMC_OK;
@@ -804,6 +887,10 @@ void destroy_ctx(lmc_ctx *c) {
         (void)hipDeviceSynchronize();
         free_ring(c->store_ring);
         free_ring(c->load_ring);
+        for (void *p : {static_cast<void *>(c->order.token_at), static_cast<void *>(c->order.counts),
+                        static_cast<void *>(c->order.n_rows), static_cast<void *>(c->order.pairs)})
+            if (p) (void)hipFree(p);
+        for (void *p : c->order_retired) (void)hipFree(p);
         for (hipEvent_t e : c->all_events) (void)hipEventDestroy(e);
         for (hipStream_t s : {c->s_gather, c->s_d2h, c->s_h2d, c->s_scatter, c->s_h2d2, c->s_d2h2})
             if (s) (void)hipStreamDestroy(s);
@@ -844,6 +931,7 @@ lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out) {
     c->shape.nt_store = true;
     c->shape.xcd_run = 32;
     c->shape.paced_groups = 0;
+    c->shape.ordered_group_rows = 256;
     c->has_device = cfg->device != LMC_DEVICE_NONE;
     const size_t pool_bytes = size_t(c->n_pool_slots) * size_t(c->chunk_bytes);
     if (!c->has_device) {
@@ -1692,6 +1780,14 @@ lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
     } else if (k == "link_groups") {
         if (value > 65536) return LMC_ERR_INVAL;
         c->link_groups = uint32_t(value);
+    } else if (k == "scatter_order" && value <= 2) {
+        c->scatter_order = int32_t(value);
+    } else if (k == "ordered_group_rows" && value < (int64_t(1) << 31)) {
+        c->shape.ordered_group_rows = uint32_t(value);
+    } else if (k == "ordered_min_pages") {
+        c->ordered_min_pages = value;
+    } else if (k == "ordered_min_density_inv" && value >= 1) {
+        c->ordered_min_density_inv = value;
     } else if (k == "fail_hip_after") {
         if (value > 0xFFFFFFFFll) return LMC_ERR_INVAL;
         c->fail_hip_after = uint32_t(value);

@@ -180,6 +180,158 @@ __global__ __launch_bounds__(kThreads) void move_rows_paced(const KernelGeom g, 
         move_tile<VEC, GATHER, NT_LD, NT_ST>(a, layers, blk);
 }
 
+// ---- scatter in the order of the destination ---------------------------------------------
+// A launch that fills thousands of pages per plane (a long context, a batch of requests)
+// finds many of its pages close together in memory, but the slot mapping names them in
+// the order of the tokens, which is random in address.  Writes to DRAM are what suffers
+// most from jumping around, so for such launches the rows are visited in ascending slot
+// order, plane by plane: the writes then sweep each plane once, and the jumps move to the
+// reads of the staging buffer.  The order is built on the device, without a sort: every
+// slot number is an index into a table (one word per slot of a plane) that receives the
+// token living there, and compacting the table yields (slot, token) pairs in slot order.
+
+constexpr uint32_t kNoToken = 0xFFFFFFFFu;
+constexpr int kSlotsPerThread = 8;
+constexpr int kSlotsPerGroup = kThreads * kSlotsPerThread;
+
+__global__ __launch_bounds__(kThreads) void order_clear(uint32_t *__restrict__ token_at, uint32_t n_slots) {
+    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i < n_slots) token_at[i] = kNoToken;
+}
+
+// token_at[slot] = token; slots outside the pages raise the flag, negative ones are left out
+__global__ __launch_bounds__(kThreads) void order_mark(const int64_t *__restrict__ slot_mapping,
+                                                       uint32_t n_tokens, uint32_t n_slots,
+                                                       uint32_t *__restrict__ token_at, int32_t *bad_flag) {
+    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n_tokens) return;
+    const int64_t s = slot_mapping[i];
+    if (s >= int64_t(n_slots)) *bad_flag = 1;
+    else if (s >= 0) token_at[s] = i;
+}
+
+// exclusive prefix sum over the workgroup of one value per thread; *total = the sum
+__device__ __forceinline__ uint32_t group_exclusive_scan(uint32_t v, uint32_t *lds, uint32_t *total) {
+    const uint32_t t = threadIdx.x, n = blockDim.x;
+    lds[t] = v;
+    __syncthreads();
+    for (uint32_t d = 1; d < n; d <<= 1) {
+        const uint32_t add = t >= d ? lds[t - d] : 0u;
+        __syncthreads();
+        lds[t] += add;
+        __syncthreads();
+    }
+    const uint32_t incl = lds[t];
+    *total = lds[n - 1];
+    __syncthreads();
+    return incl - v;
+}
+
+__device__ __forceinline__ uint32_t occupied_in_my_slots(const uint32_t *token_at, uint32_t n_slots,
+                                                         uint32_t first) {
+    uint32_t cnt = 0;
+    for (int k = 0; k < kSlotsPerThread; k++)
+        cnt += (first + k < n_slots && token_at[first + k] != kNoToken) ? 1u : 0u;
+    return cnt;
+}
+
+// counts[group] = occupied slots among the group's kSlotsPerGroup slots
+__global__ __launch_bounds__(kThreads) void order_count(const uint32_t *__restrict__ token_at,
+                                                        uint32_t n_slots, uint32_t *__restrict__ counts) {
+    __shared__ uint32_t lds[kThreads];
+    const uint32_t first = blockIdx.x * kSlotsPerGroup + threadIdx.x * kSlotsPerThread;
+    uint32_t total;
+    group_exclusive_scan(occupied_in_my_slots(token_at, n_slots, first), lds, &total);
+    if (threadIdx.x == 0) counts[blockIdx.x] = total;
+}
+
+// one workgroup: counts[] becomes its exclusive prefix sum, *n_rows the grand total
+__global__ __launch_bounds__(1024) void order_offsets(uint32_t *__restrict__ counts, uint32_t n_groups,
+                                                      uint32_t *__restrict__ n_rows) {
+    __shared__ uint32_t lds[1024];
+    const uint32_t per = (n_groups + 1023u) / 1024u;
+    const uint32_t lo = threadIdx.x * per, hi = lo + per < n_groups ? lo + per : n_groups;
+    uint32_t sum = 0;
+    for (uint32_t i = lo; i < hi; i++) sum += counts[i];
+    uint32_t total;
+    uint32_t run = group_exclusive_scan(sum, lds, &total);
+    for (uint32_t i = lo; i < hi; i++) {
+        const uint32_t c = counts[i];
+        counts[i] = run;
+        run += c;
+    }
+    if (threadIdx.x == 0) *n_rows = total;
+}
+
+// pairs[rank of the slot among the occupied ones] = (slot, token)
+__global__ __launch_bounds__(kThreads) void order_emit(const uint32_t *__restrict__ token_at,
+                                                       uint32_t n_slots, const uint32_t *__restrict__ offsets,
+                                                       uint2 *__restrict__ pairs) {
+    __shared__ uint32_t lds[kThreads];
+    const uint32_t first = blockIdx.x * kSlotsPerGroup + threadIdx.x * kSlotsPerThread;
+    uint32_t total;
+    uint32_t at = offsets[blockIdx.x] +
+                  group_exclusive_scan(occupied_in_my_slots(token_at, n_slots, first), lds, &total);
+    for (int k = 0; k < kSlotsPerThread; k++) {
+        if (first + k >= n_slots) break;
+        const uint32_t tok = token_at[first + k];
+        if (tok != kNoToken) pairs[at++] = make_uint2(first + k, tok);
+    }
+}
+
+// The scatter itself.  The pairs are taken in groups of group_rows; workgroups are
+// numbered group by group, inside a group plane by plane, inside a plane along the group's
+// pairs: lane = vector w of the row of pair j.  So what is in flight at any moment is, in
+// each of a few planes, a run of pages that are neighbours in address.  The launch is sized
+// for the tokens of the call; the pairs may be fewer (tokens without a page), the rest of
+// the grid retires.
+template <int VEC, bool NT_LD, bool NT_ST>
+__global__ __launch_bounds__(kThreads) void scatter_rows_ordered(const KernelGeom g, const LaunchView view,
+                                                                 const LayerPtrs layers,
+                                                                 const uint2 *__restrict__ pairs,
+                                                                 const uint32_t *__restrict__ n_rows_at,
+                                                                 const uint8_t *staging, FastDiv by_tiles_per_group,
+                                                                 FastDiv by_chunk_tokens, uint32_t group_rows,
+                                                                 uint32_t n_blocks_permuted, uint32_t xcd_shift) {
+    typedef typename VecOf<VEC>::type V;
+    const TileArgs a = fetch_args(g, view, nullptr, const_cast<uint8_t *>(staging), nullptr);
+    const FastDiv by_tiles = pin(by_tiles_per_group), by_ct = pin(by_chunk_tokens);
+    const uint64_t pairs_at = pin(uint64_t(pairs));
+    const uint32_t n_rows = pin(*n_rows_at), rows = pin(group_rows);
+    uint32_t blk = blockIdx.x;
+    if (blk < n_blocks_permuted) {   // as in move_rows: runs of consecutive tiles per XCD
+        const uint32_t xcd = blk & 7u, local = blk >> 3;
+        const uint32_t grp = local >> xcd_shift;
+        blk = (((grp << 3) + xcd) << xcd_shift) + (local & ((1u << xcd_shift) - 1u));
+    }
+    const uint32_t q = by_tiles.div(blk);
+    const uint32_t tile = blk - q * by_tiles.d;
+    const uint32_t grp = a.by_lp.div(q);
+    const uint32_t lp = q - grp * a.by_lp.d;
+    const uint32_t r = tile * kThreads + threadIdx.x;
+    const uint32_t row = a.by_row.div(r);
+    const uint32_t w = r - row * a.by_row.d;
+    const uint32_t j = grp * rows + row;
+    if (row >= rows || j >= n_rows) return;
+    const typename VecOf<8>::type pr = load_vec<typename VecOf<8>::type, false>(pairs_at + uint64_t(j) * 8u);
+    const uint64_t layer = pin(uint64_t(layers.p[a.lp_base + lp]));
+    const uint32_t su = pr.x, tok = pr.y;
+    const uint32_t c = by_ct.div(tok);
+    const uint32_t t = tok - c * by_ct.d;
+    const uint32_t b = a.by_bs.div(su);
+    const uint32_t o = su - b * a.by_bs.d;
+    uint32_t run = 0, dv = w;
+    if (a.runs_per_row > 1) {
+        run = a.by_run.div(w);
+        dv = w - run * a.by_run.d;
+    }
+    const uint64_t page = layer + uint64_t(int64_t(b) * a.block_stride + int64_t(o) * a.token_stride +
+                                           int64_t(run) * a.run_stride + int64_t(dv) * VEC);
+    const uint64_t st = a.staging_at + uint64_t(c) * a.chunk_stride + uint64_t(lp) * a.plane_bytes +
+                        (uint64_t(t) * a.by_row.d + w) * VEC;
+    store_vec<V, NT_ST>(page, load_vec<V, NT_LD>(st));
+}
+
 __global__ __launch_bounds__(kThreads) void check_slots(const int64_t *__restrict__ slot_mapping,
                                                         uint64_t n, uint32_t n_slots,
                                                         int32_t *bad_flag) {
@@ -334,6 +486,80 @@ hipError_t launch_scatter(const KernelGeom &g, const LaunchView &v, const Launch
                           hipEvent_t start, hipEvent_t stop) {
     return launch_move<false>(g, v, s, layers, slot_mapping, n_chunks,
                               const_cast<uint8_t *>(staging), bad_flag, stream, start, stop);
+}
+
+uint64_t order_table_words(const KernelGeom &g) { return g.n_slots; }
+uint64_t order_count_words(const KernelGeom &g) { return (uint64_t(g.n_slots) + kSlotsPerGroup - 1) / kSlotsPerGroup; }
+
+// rows per group: the launch's choice, rounded so that a group is whole tiles where it can be
+static uint32_t ordered_group_rows(const KernelGeom &g, const LaunchShape &s, uint64_t n_tokens) {
+    uint64_t rows = s.ordered_group_rows == 0 ? n_tokens : std::min<uint64_t>(s.ordered_group_rows, n_tokens);
+    return uint32_t(std::max<uint64_t>(rows, 1));
+}
+
+static uint64_t ordered_blocks(const KernelGeom &g, const LaunchView &v, uint64_t n_tokens, uint64_t rows) {
+    const uint64_t tiles_per_group = (rows * g.by_vec_per_row.d + kThreads - 1) / kThreads;
+    const uint64_t groups = (n_tokens + rows - 1) / rows;
+    return groups * v.by_n_lp.d * tiles_per_group;
+}
+
+bool ordered_scatter_fits(const KernelGeom &g, const LaunchView &v, const LaunchShape &s, uint64_t n_tokens) {
+    if (n_tokens == 0 || n_tokens >= (uint64_t(1) << 31) || g.n_slots > kMaxOrderedSlots) return false;
+    const uint64_t rows = ordered_group_rows(g, s, n_tokens);
+    if (rows * g.by_vec_per_row.d >= (uint64_t(1) << 31)) return false;   // lanes of one group and plane
+    return ordered_blocks(g, v, n_tokens, rows) <= 0x00FFFFFFu;           // as max_chunks_per_launch
+}
+
+template <int VEC>
+static hipError_t launch_scatter_ordered_v(const KernelGeom &g, const LaunchView &v, const LaunchShape &s,
+                                           const LayerPtrs &layers, uint32_t n_tokens, const OrderScratch &o,
+                                           const uint8_t *staging, hipStream_t stream, hipEvent_t start,
+                                           hipEvent_t stop) {
+    const uint32_t rows = ordered_group_rows(g, s, n_tokens);
+    const uint32_t tiles_per_group = uint32_t((uint64_t(rows) * g.by_vec_per_row.d + kThreads - 1) / kThreads);
+    const uint32_t n_blocks = uint32_t(ordered_blocks(g, v, n_tokens, rows));
+    uint32_t shift = 0, permuted = 0;
+    if (s.xcd_run > 0) {
+        while ((2u << shift) <= s.xcd_run) shift++;
+        permuted = n_blocks & ~((8u << shift) - 1u);
+    }
+    const FastDiv by_tiles = make_fastdiv(tiles_per_group), by_ct = make_fastdiv(g.chunk_tokens);
+    dim3 grid(n_blocks), block(kThreads);
+#define LMC_GO(LD, ST)                                                                                 \
+    hipExtLaunchKernelGGL((scatter_rows_ordered<VEC, LD, ST>), grid, block, 0, stream, start, stop, 0, g, \
+                          v, layers, o.pairs, o.n_rows, staging, by_tiles, by_ct, rows, permuted, shift)
+    if (s.nt_load && s.nt_store) LMC_GO(true, true);
+    else if (s.nt_load) LMC_GO(true, false);
+    else if (s.nt_store) LMC_GO(false, true);
+    else LMC_GO(false, false);
+#undef LMC_GO
+    return hipGetLastError();
+}
+
+hipError_t launch_scatter_ordered(const KernelGeom &g, const LaunchView &v, const LaunchShape &s,
+                                  const LayerPtrs &layers, const int64_t *slot_mapping, uint32_t n_tokens,
+                                  const OrderScratch &o, const uint8_t *staging, int32_t *bad_flag,
+                                  hipStream_t stream, hipEvent_t start, hipEvent_t stop) {
+    if (n_tokens == 0) return hipSuccess;
+    const uint32_t n_slots = g.n_slots;
+    const uint32_t n_groups = uint32_t(order_count_words(g));
+    const dim3 block(kThreads);
+    hipLaunchKernelGGL(order_clear, dim3((n_slots + kThreads - 1) / kThreads), block, 0, stream, o.token_at, n_slots);
+    hipLaunchKernelGGL(order_mark, dim3((n_tokens + kThreads - 1) / kThreads), block, 0, stream, slot_mapping,
+                       n_tokens, n_slots, o.token_at, bad_flag);
+    hipLaunchKernelGGL(order_count, dim3(n_groups), block, 0, stream, o.token_at, n_slots, o.counts);
+    hipLaunchKernelGGL(order_offsets, dim3(1), dim3(1024), 0, stream, o.counts, n_groups, o.n_rows);
+    hipLaunchKernelGGL(order_emit, dim3(n_groups), block, 0, stream, o.token_at, n_slots, o.counts, o.pairs);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    switch (g.vec) {
+        case 16: return launch_scatter_ordered_v<16>(g, v, s, layers, n_tokens, o, staging, stream, start, stop);
+        case 8: return launch_scatter_ordered_v<8>(g, v, s, layers, n_tokens, o, staging, stream, start, stop);
+        case 4: return launch_scatter_ordered_v<4>(g, v, s, layers, n_tokens, o, staging, stream, start, stop);
+        case 2: return launch_scatter_ordered_v<2>(g, v, s, layers, n_tokens, o, staging, stream, start, stop);
+        case 1: return launch_scatter_ordered_v<1>(g, v, s, layers, n_tokens, o, staging, stream, start, stop);
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_check_slots(const int64_t *slot_mapping, uint64_t n, uint32_t n_slots,

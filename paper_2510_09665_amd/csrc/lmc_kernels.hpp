@@ -66,6 +66,8 @@ struct LaunchShape {
     uint32_t xcd_run;         // workgroup ids are permuted so that each of the 8 XCDs
                               // takes runs of this many (rounded down to a power of
                               // two) consecutive tiles; 0 = off
+    uint32_t ordered_group_rows;  // scatter in destination order: rows (tokens) per group, see
+                                  // launch_scatter_ordered; 0 = one group, the launch goes plane by plane
     uint32_t paced_groups;    // 0: one tile per workgroup (HBM-bound launches); n > 0: a
                               // fixed grid of n workgroups that take tiles in turn, for
                               // launches whose other side is host memory
@@ -83,6 +85,25 @@ hipError_t launch_scatter(const KernelGeom &g, const LaunchView &v, const Launch
                           const LayerPtrs &layers, const int64_t *slot_mapping, uint32_t n_chunks,
                           const uint8_t *staging, int32_t *bad_flag, hipStream_t stream,
                           hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
+// Scatter in the order of the destination: the rows of the launch are visited in ascending
+// slot order, plane by plane (see lmc_kernels.hip).  The order is built on the device in
+// scratch memory the caller provides: token_at (order_table_words() words), counts
+// (order_count_words() words), pairs (one per token of the launch), n_rows (one word).
+// One scratch set serves one launch at a time.
+constexpr uint32_t kMaxOrderedSlots = 1u << 24;     // 64 MiB of table at most
+struct OrderScratch {
+    uint32_t *token_at, *counts, *n_rows;
+    uint2 *pairs;
+};
+uint64_t order_table_words(const KernelGeom &g);
+uint64_t order_count_words(const KernelGeom &g);
+// whether a launch over n_tokens tokens of view v can go this way (32-bit index limits)
+bool ordered_scatter_fits(const KernelGeom &g, const LaunchView &v, const LaunchShape &s, uint64_t n_tokens);
+// same result as launch_scatter over n_tokens / chunk_tokens chunks
+hipError_t launch_scatter_ordered(const KernelGeom &g, const LaunchView &v, const LaunchShape &s,
+                                  const LayerPtrs &layers, const int64_t *slot_mapping, uint32_t n_tokens,
+                                  const OrderScratch &o, const uint8_t *staging, int32_t *bad_flag,
+                                  hipStream_t stream, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 LaunchView bulk_view(const KernelGeom &g);
 LaunchView layer_view(const KernelGeom &g, uint32_t planes_per_layer, uint32_t first_layer,
                       uint32_t n_layers);

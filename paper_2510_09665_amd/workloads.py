@@ -83,6 +83,46 @@ class KVGeometry:
         return self.NB * self.BS
 
 
+@dataclass(frozen=True)
+class BlockMajorKV:
+    """An engine layout with every layer in ONE allocation and blocks outermost,
+    [NB][L][P][BS][H][D]: all of a block's KV (every layer, K and V) is one contiguous
+    extent of L*P*page bytes.  Expressed with the same four strides: layer l starts
+    layer_offset(l) bytes into the allocation, planes are a page apart and blocks
+    L*P pages.  Carries the attributes a geometry needs (L P H D e BS NB CT and strides)."""
+    shape: KVGeometry
+
+    def __getattr__(self, name):            # L, P, H, D, e, BS, NB, CT, R, chunk_bytes, n_slots, ...
+        return getattr(object.__getattribute__(self, "shape"), name)
+
+    @property
+    def page_bytes(self):
+        return self.shape.BS * self.shape.R
+
+    @property
+    def plane_stride(self):
+        return self.page_bytes
+
+    @property
+    def block_stride(self):
+        return self.shape.L * self.shape.P * self.page_bytes
+
+    @property
+    def token_stride(self):
+        return self.shape.R
+
+    @property
+    def head_stride(self):
+        return self.shape.D * self.shape.e
+
+    @property
+    def total_bytes(self):
+        return self.shape.NB * self.block_stride
+
+    def layer_offset(self, layer):
+        return layer * self.shape.P * self.page_bytes
+
+
 # The five benchmark configurations.  NB where the configuration leaves it open:
 # large enough that the store blocks and the fresh retrieve blocks are disjoint.
 CONFIGS = {

@@ -79,6 +79,77 @@ def test_gather_and_scatter_match_oracle(name, xcd_run):
         assert_layers_equal(dst.device_blocks_to_host(), dst.host, name)
 
 
+@pytest.mark.parametrize("name", list(SHAPES))
+@pytest.mark.parametrize("xcd_run", [None, 4])
+def test_scatter_in_destination_order_matches_oracle(name, xcd_run):
+    """The launch shape for scatters that fill many pages per plane (rows visited in
+    ascending slot order, the order built on the device) must write exactly what the
+    oracle's scatter writes: every shape, tokens without a page, a slot outside the pages
+    (skipped and reported), two calls in a row on the same scratch, the second smaller."""
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    from paper_2510_09665_amd import lmc
+    g = W.KVGeometry(**SHAPES[name])
+    rng = np.random.default_rng(zlib.crc32(name.encode()) + 1)
+    src = PagedKV(g, np.arange(g.NB), rng)
+    with _ctx(g) as c:
+        c.tune("scatter_order", 2)
+        if xcd_run is not None:
+            c.tune("xcd_run", xcd_run)
+        for n_chunks in (3, 1):
+            n_tok = n_chunks * g.CT
+            chunks = oracle.gather(g, src.host, rng.permutation(g.n_slots)[:n_tok].astype(np.int64))
+            tau = rng.permutation(g.n_slots)[:n_tok].astype(np.int64)
+            tau[rng.integers(0, n_tok, 4)] = -3
+            tau[rng.integers(0, n_tok)] = -(2**40)
+            bad = tau.copy()
+            bad[1] = g.n_slots + 5                          # never dereferenced, reported by lmc_wait
+            as_skip = tau.copy()
+            as_skip[1] = -1
+            dst = PagedKV(g, np.arange(g.NB), fill="sentinel")
+            c.scatter(torch.from_numpy(chunks.reshape(-1)).cuda(), slots_to_device(bad), n_chunks, dst.dev,
+                      torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            with pytest.raises(lmc.LMCError) as e:
+                c.wait()
+            assert e.value.status == lmc.LMC_ERR_BADSLOT
+            oracle.scatter(g, chunks, as_skip, dst.host)
+            assert_layers_equal(dst.device_blocks_to_host(), dst.host, "%s, %d chunks" % (name, n_chunks))
+
+
+def test_all_layers_in_one_allocation_with_blocks_outermost():
+    """[NB][L][P][BS][H][D] in a single allocation: the per-layer base pointers lie inside
+    each other's extents and a block's KV over all layers is contiguous.  Same four
+    strides, same kernels; gather and scatter against the oracle on the same bytes."""
+    import torch
+    from gpu_util import slots_to_device
+    g = W.BlockMajorKV(W.KVGeometry(L=5, P=2, H=4, D=64, e=2, BS=16, NB=48, CT=256))
+    rng = np.random.default_rng(77)
+    host = rng.integers(0, 256, g.total_bytes, dtype=np.uint8)
+    layers_host = [host[g.layer_offset(l):] for l in range(g.L)]
+    dev = torch.from_numpy(host).cuda()
+    layers_dev = [dev.data_ptr() + g.layer_offset(l) for l in range(g.L)]
+    n_chunks = 2
+    slots = rng.permutation(g.n_slots)[:n_chunks * g.CT].astype(np.int64)
+    slots[[3, 300]] = -1
+    with _ctx(g) as c:
+        staging = torch.empty(n_chunks * g.chunk_bytes, dtype=torch.uint8, device="cuda")
+        c.gather(layers_dev, slots_to_device(slots), n_chunks, staging, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        want = oracle.gather(g, layers_host, slots)
+        assert np.array_equal(staging.cpu().numpy().reshape(n_chunks, -1), want)
+        tau = rng.permutation(g.n_slots)[:n_chunks * g.CT].astype(np.int64)
+        tau[[0, 511]] = -9
+        dst_host = np.full(g.total_bytes, 0x6B, dtype=np.uint8)
+        dst_dev = torch.from_numpy(dst_host).cuda()
+        c.scatter(staging, slots_to_device(tau), n_chunks, [dst_dev.data_ptr() + g.layer_offset(l) for l in range(g.L)],
+                  torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        c.wait()
+        oracle.scatter(g, want, tau, [dst_host[g.layer_offset(l):] for l in range(g.L)])
+        assert np.array_equal(dst_dev.cpu().numpy(), dst_host)
+
+
 def test_empty_and_single_token_edge_cases():
     import torch
     from gpu_util import PagedKV, slots_to_device

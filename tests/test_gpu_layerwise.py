@@ -24,6 +24,7 @@ CASES = {
     "all_layers_in_one_step": ("tiny", {}, 256, 1, 99, 0),
     "direct_llama_k1": ("llama3_8b", dict(L=8, NB=1024), 10 * 256, 1, 1, "direct"),
     "direct_mla_k3": ("mla_bf16", dict(L=7), 4 * 256, 1, 3, "direct"),
+    "ordered_scatter_k2": ("llama3_8b", dict(L=6, NB=512), 8 * 256, 2, 2, "ordered"),   # layer views, rows in slot order
 }
 
 
@@ -44,6 +45,8 @@ def _setup(case):
     ctx.tune("direct_retrieve_below", 0)    # calls go through staging whatever their size
     if flags == "kcopy":
         ctx.tune("copy_kernel", 3)      # rectangle copies by the library's own copy kernel, both ways
+    if flags == "ordered":
+        ctx.tune("scatter_order", 2)    # every scatter launch in the order of the destination
     return lmc, g, seq, src, dst, ctx, k, n_chunks
 
 

@@ -187,6 +187,19 @@ def test_own_copy_kernel_instead_of_the_runtimes_copies(engines):
                   staging_chunks=2, tune=t)
 
 
+def test_retrieve_with_scatters_in_destination_order():
+    """lmc_tune("scatter_order", 2): every scatter launch of the pipeline visits its rows in
+    ascending slot order (built on the device); consecutive launches share that scratch."""
+    t = (("scatter_order", 2),)
+    g = W.geometry("llama3_8b", L=4, NB=1024)
+    lmc = _lmc()
+    _run_sequence("llama3_8b", g, flags=lmc.LMC_FLAG_POISON_STAGING, n_tokens=24 * 256, num_staging=3,
+                  staging_chunks=5, tune=t)
+    _run_sequence("mla_fp8", W.geometry("mla_fp8", L=7), n_tokens=6 * 256, staging_chunks=2, tune=t)
+    _run_sequence("llama3_8b", W.geometry("llama3_8b", L=6, NB=512, layout="HND"), n_tokens=8 * 256,
+                  staging_chunks=3, tune=t)
+
+
 def test_direct_mode_full_size_config2_and_mla():
     """LMC_FLAG_DIRECT: the kernels read and write the pinned pool themselves."""
     lmc = _lmc()

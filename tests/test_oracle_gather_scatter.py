@@ -215,3 +215,25 @@ def test_timing_driver_only_calls_the_oracle():
         assert oracle.time_pass(g, src, dst, s_slots, l_slots, pool, buffers, threads, True) > 0
         for a, b in zip(dst, want_dst):
             assert np.array_equal(a, b)
+
+
+def test_layers_that_share_one_allocation_blocks_outermost():
+    """[NB][L][P][BS][H][D] in one allocation (W.BlockMajorKV): the oracle, given layer
+    pointers that lie inside one another's extents, must equal plain numpy indexing."""
+    g = W.BlockMajorKV(W.KVGeometry(L=3, P=2, H=2, D=8, e=2, BS=4, NB=10, CT=8))
+    rng = np.random.default_rng(0)
+    host = rng.integers(0, 256, g.total_bytes, dtype=np.uint8)
+    layers = [host[g.layer_offset(l):] for l in range(g.L)]
+    slots = rng.permutation(g.n_slots)[:g.CT].astype(np.int64)
+    v = host.reshape(g.NB, g.L, g.P, g.BS, g.R)
+    want = np.stack([[v[slots // g.BS, l, p, slots % g.BS] for p in range(g.P)] for l in range(g.L)])
+    chunk = oracle.gather_chunk(g, layers, slots)
+    assert np.array_equal(chunk, want.reshape(-1))
+    out = np.zeros_like(host)
+    tau = rng.permutation(g.n_slots)[:g.CT].astype(np.int64)
+    oracle.scatter_chunk(g, chunk, tau, [out[g.layer_offset(l):] for l in range(g.L)])
+    ref = np.zeros_like(host).reshape(g.NB, g.L, g.P, g.BS, g.R)
+    for l in range(g.L):
+        for p in range(g.P):
+            ref[tau // g.BS, l, p, tau % g.BS] = want[l, p]
+    assert np.array_equal(out, ref.reshape(-1))
