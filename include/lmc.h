@@ -67,6 +67,7 @@ enum {
 };
 
 #define LMC_MAX_LAYERS 160        /* kv_layers travels as a kernel argument */
+#define LMC_STATIC_SCRATCH_BYTES (64ull << 20) /* device memory of lmc_store_static, per GPU */
 #define LMC_DEVICE_NONE (-1)      /* index-only context: see lmc_create */
 
 /* lmc_config_t.flags */
@@ -302,6 +303,34 @@ lmc_status_t lmc_gather(lmc_ctx_t *ctx, void *const *kv_layers, const int64_t *s
                         int64_t n_chunks, void *staging_dev, void *stream);
 lmc_status_t lmc_scatter(lmc_ctx_t *ctx, const void *staging_dev, const int64_t *slot_mapping,
                          int64_t n_chunks, void *const *kv_layers, void *stream);
+
+/* For callers that cannot allocate: tight serving loops, harnesses that forbid hipMalloc
+ * after start-up, code that may run while another part of the process captures a HIP
+ * graph.  The data path of lmc_store (gather the pages of each chunk into a contiguous
+ * device buffer, copy the buffer to host memory) with nothing allocated by the call, on
+ * the device or through the runtime: the buffer is a static array of
+ * LMC_STATIC_SCRATCH_BYTES in the library's device image (each GPU the library is used on
+ * holds its own copy until the process ends; its address is looked up when lmc_create
+ * first runs on that GPU), the destination is the caller's, and no event or stream is
+ * created.  There is no index, pool or ticket on this path: chunk i of the slot mapping
+ * (DEVICE int64[n_chunks*chunk_tokens], same rules as lmc_store) arrives at
+ * host_dst + i*lmc_chunk_bytes(), byte for byte what lmc_store would have put into the
+ * pool.  host_dst: HOST memory from hipHostMalloc (the runtime copies to pageable memory
+ * through buffers of its own), n_chunks*chunk_bytes, caller-owned.
+ * Everything is enqueued on `stream` (hipStream_t, NULL = the null stream), kernel and copy
+ * in turn, one piece of at most LMC_STATIC_SCRATCH_BYTES at a time; the stream's order is
+ * what keeps a piece's kernel off the array until the piece before has been copied out.
+ * The work is complete when `stream` has passed it (hipStreamSynchronize or an event of
+ * the caller's).  Any n_chunks is taken; a chunk larger than the array goes a few layers
+ * at a time.  Calls that overlap on one GPU (other streams, other contexts, other
+ * threads) share the array and race: one call at a time per GPU.  Every byte of a piece
+ * is written by its gather, so nothing of an earlier call shows through.
+ * Errors: LMC_ERR_INVAL (NULL argument; one layer of one chunk is larger than
+ * LMC_STATIC_SCRATCH_BYTES; host_dst is not pinned host memory; device ordinal of the
+ * context >= 64), LMC_ERR_NODEVICE, LMC_ERR_BADSLOT as for lmc_gather, LMC_ERR_HIP (pieces
+ * enqueued before the failing call still complete). */
+lmc_status_t lmc_store_static(lmc_ctx_t *ctx, void *const *kv_layers, const int64_t *slot_mapping,
+                              int64_t n_chunks, void *host_dst, void *stream);
 
 /* Chunks that arrive from, or leave to, host memory without touching the GPU (a lower
  * storage tier, section 5.1 "Parallel Store/load Operations").  lmc_put_host stores n

@@ -32,7 +32,7 @@ EXPORTS = [
     "lmc_window_get",
     "lmc_lookup", "lmc_store", "lmc_retrieve", "lmc_retrieve_batch", "lmc_retrieve_layerwise",
     "lmc_store_begin", "lmc_store_layers", "lmc_wait_layer", "lmc_wait", "lmc_gather",
-    "lmc_scatter", "lmc_put_host", "lmc_get_host", "lmc_find_slot", "lmc_pin", "lmc_unpin",
+    "lmc_scatter", "lmc_store_static", "lmc_put_host", "lmc_get_host", "lmc_find_slot", "lmc_pin", "lmc_unpin",
     "lmc_clear", "lmc_drain_evicted", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_measure_link_kernel", "lmc_measure_link_duplex",
     "lmc_copy", "lmc_tune", "lmc_probe_stream", "lmc_chunk_acquire", "lmc_chunk_release", "lmc_tier_open", "lmc_tier_close",
     "lmc_tier_write", "lmc_tier_wait", "lmc_tier_lookup", "lmc_tier_read", "lmc_tier_errno",
@@ -137,6 +137,7 @@ def _lib():
             "lmc_wait": (st, [vp, u64]),
             "lmc_gather": (st, [vp, vp, vp, i64, vp, vp]),
             "lmc_scatter": (st, [vp, vp, vp, i64, vp, vp]),
+            "lmc_store_static": (st, [vp, vp, vp, i64, vp, vp]),
             "lmc_put_host": (st, [vp, vp, i64, vp]),
             "lmc_get_host": (st, [vp, u64, vp]),
             "lmc_find_slot": (st, [vp, u64, ctypes.POINTER(i64)]),
@@ -360,6 +361,11 @@ class Context:
     def scatter(self, staging_dev, slot_mapping, n_chunks, kv_layers, stream=None):
         self._check(_lib().lmc_scatter(self._h, _dev(staging_dev), _dev(slot_mapping), n_chunks,
                                        self._layers(kv_layers), _stream(stream)), "lmc_scatter")
+
+    def store_static(self, kv_layers, slot_mapping, n_chunks, host_dst, stream=None):
+        """host_dst: a pinned uint8 tensor (or address) of n_chunks * chunk_bytes."""
+        self._check(_lib().lmc_store_static(self._h, self._layers(kv_layers), _dev(slot_mapping), n_chunks,
+                                            _dev(host_dst), _stream(stream)), "lmc_store_static")
 
     # -- host-side chunk access -----------------------------------------------------
     def put_host(self, chunk_ids, host_src):
