@@ -26,6 +26,8 @@ Also reported in the same JSON line:
   device       both kernels alone over the whole request in one launch (10 GiB, far
                beyond the 256 MB Infinity Cache), and a plain copy kernel of the same
                size as the achievable ceiling
+  group_size   the headline request with staging buffers of 1 ... 16 chunks: what one copy
+               boundary costs the link
   configs      every other benchmark configuration end to end (1 tiny, 2 Llama-3-8B,
                4 batched multi-request retrieve, 5 MLA in bf16 and fp8): store / retrieve
                as a fraction of the link peak and the kernels alone as a fraction of 8 TB/s
@@ -378,6 +380,90 @@ def placement_leg(torch, lmc, W, dev, stream):
     return res
 
 
+def group_size_leg(torch, lmc, W, g, seq, src, dst, d_store, d_load, stream, timed, peaks, num_staging):
+    """What a copy boundary costs: the headline request stored and retrieved with staging
+    buffers of 1, 2, 4, 8 and 16 chunks (128 ... 8 groups per direction; the copies of a
+    group are one merged transfer).  The time beyond payload / link peak, divided by the
+    number of groups, is the idle time of the link per boundary."""
+    n_chunks = seq["tokens"].size // g.CT
+    nbytes = n_chunks * g.chunk_bytes
+    res = {}
+    for sc in (1, 2, 4, 8, 16):
+        with lmc.Context(g, (n_chunks + 1) * g.chunk_bytes, num_staging=num_staging, staging_chunks=sc,
+                         device=0) as c:
+            ids = c.hash_chunks(seq["tokens"])
+
+            def store_only():
+                c.clear(ids)
+                c.wait(c.store(src, d_store, ids, stream))
+            ts = timed(store_only, reps=4)
+            tl = timed(lambda: c.wait(c.retrieve(ids, d_load, dst, stream)), reps=4)
+        groups = 1 + -(-(n_chunks - 1) // sc)          # one single-chunk group at the exposed end
+        res["staging_chunks_%d" % sc] = {
+            "groups_per_direction": groups,
+            "store_gbps": round(nbytes / ts / 1e9, 2), "retrieve_gbps": round(nbytes / tl / 1e9, 2),
+            "store_frac_of_d2h_peak": round(nbytes / ts / 1e9 / peaks["d2h_peak_gbps"], 4),
+            "retrieve_frac_of_h2d_peak": round(nbytes / tl / 1e9 / peaks["h2d_peak_gbps"], 4),
+            "store_us_beyond_peak_per_group": round((ts - nbytes / (peaks["d2h_peak_gbps"] * 1e9)) / groups * 1e6, 1),
+            "retrieve_us_beyond_peak_per_group": round((tl - nbytes / (peaks["h2d_peak_gbps"] * 1e9)) / groups * 1e6, 1)}
+    return res
+
+
+# shapes beyond the five configurations that --kernels-only can run: a tensor-parallel
+# shard (one KV head of the Llama-3-70B shape per GPU: 256-byte rows, 4 KiB pages) and a
+# token-granular engine (one-token pages, 2 KiB each)
+EXTRA_SHAPES = {
+    "tp8_shard_70b": ("llama3_70b", dict(H=1), 32768),
+    "one_token_pages_8b": ("llama3_8b", dict(BS=1, NB=8192 * 16), 16384),
+}
+
+
+def kernels_only_mode(names, iters, reps):
+    """The gather, the scatter and the plain copy kernel alone over the whole request of each
+    named shape, one launch each time, nothing else in the process: the program that the
+    rocprofv3 counter runs of profiles/ profile.  Prints one JSON line."""
+    import torch
+    from paper_2510_09665_amd import lmc
+    from paper_2510_09665_amd import workloads as W
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream()
+    res = {}
+    for name in names:
+        if name in EXTRA_SHAPES:
+            base, ov, n_tok = EXTRA_SHAPES[name]
+            g = W.geometry(base, **ov)
+            rng = W.rng_for(base, stream=60)
+            perm = rng.permutation(g.NB)
+            nb = n_tok // g.BS
+            gs = [torch.from_numpy(W.slots_from_blocks(g, perm[:nb], n_tok)).to(dev)]
+            ss = [torch.from_numpy(W.slots_from_blocks(g, perm[nb:2 * nb], n_tok)).to(dev)]
+            n = n_tok // g.CT
+            rot = {}
+        elif name == "batch_8b":
+            g = W.geometry(name)
+            reqs = W.request_mix(name, g)
+            sl = np.concatenate([r["load_slots"] for r in reqs])
+            n = sl.size // g.CT
+            gs = ss = [torch.from_numpy(sl).to(dev)]
+            rot = {}
+        else:
+            g = W.geometry(name)
+            n = W.CONFIGS[name]["tokens"] // g.CT
+            gs = ss = None
+            rot = {}
+        src = [torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev) for _ in range(g.L)]
+        dst = [torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev) for _ in range(g.L)]
+        with lmc.Context(g, max(g.chunk_bytes, 64 << 20), device=0) as ctx:
+            tg, ts, tc = kernel_only(torch, ctx, W, name, g, src, dst, n, dev, stream, gather_slots=gs,
+                                     scatter_slots=ss, iters=iters, reps=reps, **rot)
+        res[name] = {"chunks_per_launch": n, "rows_bytes": g.R, "page_bytes": g.BS * g.R}
+        res[name].update(kernel_report(n * g.chunk_bytes, tg, ts, tc))
+        for k_, t_ in (("gather_us", tg), ("scatter_us", ts), ("copy_kernel_us", tc)):
+            res[name][k_] = round(t_ * 1e6, 1)
+        del src, dst
+    print(json.dumps({"kernels_only": res}), flush=True)
+
+
 def mode_legs(torch, lmc, W, dev, stream, legs, args, timed, peaks):
     """The modes beside the bulk pipeline, on the Llama-3-8B shape (16 chunks, 512 MiB)."""
     g = W.geometry(SECONDARY)
@@ -663,12 +749,18 @@ def main():
                     help="steps measured right after set-up, before anything settles (0 = none)")
     ap.add_argument("--settle-seconds", type=float, default=20.0,
                     help="upper limit for the untimed settling phase before the warm-up (0 = none)")
-    ap.add_argument("--legs", default="pipeline,link,device,configs,placement,duplex,direct,layerwise,overlap,"
+    ap.add_argument("--legs", default="pipeline,link,device,groups,configs,placement,duplex,direct,layerwise,overlap,"
                                       "fragmented,small,cpu",
-                    help="comma list of pipeline (always run), link, device, configs, placement, duplex, direct, "
+                    help="comma list of pipeline (always run), link, device, groups, configs, placement, duplex, direct, "
                          "layerwise, overlap, fragmented, small, cpu: the extra measurements to make; "
                          "profiling runs use a subset")
     ap.add_argument("--tune", action="append", default=[], help="key=value for lmc_tune")
+    ap.add_argument("--kernels-only", default="",
+                    help="comma list of shapes (tiny, llama3_8b, llama3_70b, batch_8b, mla_bf16, mla_fp8, "
+                         "tp8_shard_70b, one_token_pages_8b): run only the gather, scatter and copy kernels over "
+                         "each shape's whole request and exit (the program the counter profiles run)")
+    ap.add_argument("--kernels-only-iters", type=int, default=6)
+    ap.add_argument("--kernels-only-reps", type=int, default=3)
     args = ap.parse_args()
     legs = set(args.legs.split(","))
     if args.no_cpu_baseline:
@@ -685,6 +777,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
+    if args.kernels_only:
+        kernels_only_mode(args.kernels_only.split(","), args.kernels_only_iters, args.kernels_only_reps)
+        return
     dev = torch.device("cuda:0")
     stream = torch.cuda.current_stream()
     first_pages = random_pages_sample(torch, lmc, W, dev, stream) if "placement" in legs else None
@@ -865,6 +960,9 @@ def main():
         out["link"] = link
     # the headline's pages and context stay allocated to the end: freeing tens of GiB in
     # the middle of the run is what brings on the slow state described at the settling loop
+    if "groups" in legs:
+        out["group_size"] = group_size_leg(torch, lmc, W, g, seq, src, dst, d_store, d_load, stream, timed, peaks,
+                                           args.num_staging)
     if "configs" in legs:
         out["configs"] = other_configs(torch, lmc, W, dev, stream, timed, peaks)
     if legs & {"duplex", "direct", "layerwise", "overlap", "fragmented"}:
