@@ -492,6 +492,11 @@ lmc_status_t lmc_copy(lmc_ctx_t *ctx, void *dst_dev, const void *src_dev, uint64
  * GB/s, best of reps.  Needs 2*nbytes of pool; pool content is preserved.  Blocks. */
 lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *ctx, uint64_t nbytes, int32_t reps,
                                      double *sum_gbps_out);
+/* The same with the library's link-paced copy kernel in place of the runtime's copy for the
+ * upload (by_kernel bit 0), the download (bit 1) or both; nbytes a multiple of 16.  The
+ * two-way peak of the link is the best of the four combinations. */
+lmc_status_t lmc_measure_link_duplex_kernel(lmc_ctx_t *ctx, uint64_t nbytes, int32_t reps,
+                                            uint32_t by_kernel, double *sum_gbps_out);
 
 /* Would work on `stream` (a hipStream_t of the caller, e.g. the stream its model runs on)
  * have to wait behind the library's copies?  HIP maps streams onto a few hardware queues
@@ -521,10 +526,11 @@ lmc_status_t lmc_probe_stream(lmc_ctx_t *ctx, void *stream, uint32_t *mask_out);
  * pool are made by the library's own link-paced copy kernel instead of hipMemcpyAsync;
  * bit 1: copies from the pool to staging too.  2-3 % slower than the runtime's copies,
  * but independent of which engine the runtime picks and of what else that engine is doing),
- * "d2h_guard" (default 1: the library times the runtime's copies to the host of 32 MiB
+ * "d2h_guard" (default 0; 1: the library times the runtime's copies to the host of 32 MiB
  * and more, and when two of the last four fell below three quarters of the best rate it has seen
  * it makes these copies with its own kernel for 1 s, then tries the runtime again,
- * doubling the pause up to 8 s while the runtime stays slow; 0 = never),
+ * doubling the pause up to 8 s while the runtime stays slow: for processes that allocate
+ * and free memory while they store),
  * "edge_chunks" (size
  * of the group at the exposed end of a pipeline, 0 = none), "timing" (0/1: switches
  * LMC_FLAG_TIMING), "direct_store_below" / "direct_retrieve_below" (bytes, default 64 MiB

@@ -108,8 +108,12 @@ struct lmc_ctx {
     // 55 GB/s does not depend on that.
     uint32_t copy_kernel = 0;
     // ... and the guard that switches device-to-host copies to the kernel by itself while
-    // the runtime's are slow (lmc_guard.hpp)
-    bool d2h_guard_on = true;
+    // the runtime's are slow (lmc_guard.hpp).  Off unless asked for (lmc_tune "d2h_guard").
+    // Measured on a 10 GiB request: in a fresh process's first seconds the guard lifts the
+    // path from 44.5 to 54.5 GB/s; later, after a context with a large pool has been created,
+    // it holds the copies on the copy kernel (55.7 GB/s) for seconds although the runtime's
+    // were back at 56.8 after one store.  Steady state is the same either way.
+    bool d2h_guard_on = false;
     lmc::CopyEngineGuard d2h_guard;
     std::vector<CopyTiming> copy_timings;
     std::chrono::steady_clock::time_point born = std::chrono::steady_clock::now();
@@ -1795,8 +1799,10 @@ lmc_status_t lmc_probe_stream(lmc_ctx_t *c, void *stream, uint32_t *mask_out) {
     return rc;
 }
 
-lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, double *gbps_out) {
-    if (!c || !gbps_out || reps < 1 || nbytes == 0) return LMC_ERR_INVAL;
+static lmc_status_t measure_duplex(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, uint32_t by_kernel,
+                                   double *gbps_out) {
+    if (!c || !gbps_out || reps < 1 || nbytes == 0 || by_kernel > 3) return LMC_ERR_INVAL;
+    if (by_kernel != 0 && (nbytes % 16) != 0) return LMC_ERR_INVAL;
     if (!c->has_device) return LMC_ERR_NODEVICE;
     if (2 * nbytes > uint64_t(c->n_pool_slots) * uint64_t(c->chunk_bytes)) return LMC_ERR_INVAL;
     std::lock_guard<std::mutex> lock(c->mu);
@@ -1827,8 +1833,11 @@ lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *c, uint64_t nbytes, int32_t reps
     for (int r = 0; r < reps + 1 && rc == LMC_OK; r++) {
         ok(hipEventRecord(e0, c->s_h2d));
         ok(hipStreamWaitEvent(c->s_d2h, e0, 0));           // both directions start together
-        ok(hipMemcpyAsync(up, c->pool, nbytes, hipMemcpyHostToDevice, c->s_h2d));
-        ok(hipMemcpyAsync(c->pool + nbytes, down, nbytes, hipMemcpyDeviceToHost, c->s_d2h));
+        const uint32_t groups = c->link_groups ? c->link_groups : 64u;
+        ok((by_kernel & 1u) ? lmc::launch_copy_rect(up, nbytes, c->pool_dev, nbytes, nbytes, 1, groups, c->s_h2d)
+                            : hipMemcpyAsync(up, c->pool, nbytes, hipMemcpyHostToDevice, c->s_h2d));
+        ok((by_kernel & 2u) ? lmc::launch_copy_rect(c->pool_dev + nbytes, nbytes, down, nbytes, nbytes, 1, groups, c->s_d2h)
+                            : hipMemcpyAsync(c->pool + nbytes, down, nbytes, hipMemcpyDeviceToHost, c->s_d2h));
         ok(hipEventRecord(e1, c->s_d2h));
         ok(hipStreamWaitEvent(c->s_h2d, e1, 0));
         ok(hipEventRecord(e2, c->s_h2d));                  // after both
@@ -1843,6 +1852,15 @@ lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *c, uint64_t nbytes, int32_t reps
     (void)hipFree(down);
     *gbps_out = best;
     return rc;
+}
+
+lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, double *gbps_out) {
+    return measure_duplex(c, nbytes, reps, 0, gbps_out);
+}
+
+lmc_status_t lmc_measure_link_duplex_kernel(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, uint32_t by_kernel,
+                                            double *gbps_out) {
+    return measure_duplex(c, nbytes, reps, by_kernel, gbps_out);
 }
 
 lmc_status_t lmc_copy(lmc_ctx_t *c, void *dst, const void *src, uint64_t nbytes, void *stream) {

@@ -33,7 +33,7 @@ EXPORTS = [
     "lmc_lookup", "lmc_store", "lmc_retrieve", "lmc_retrieve_batch", "lmc_retrieve_layerwise",
     "lmc_store_begin", "lmc_store_layers", "lmc_wait_layer", "lmc_wait", "lmc_gather",
     "lmc_scatter", "lmc_store_static", "lmc_put_host", "lmc_get_host", "lmc_find_slot", "lmc_pin", "lmc_unpin",
-    "lmc_clear", "lmc_drain_evicted", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_measure_link_kernel", "lmc_measure_link_duplex",
+    "lmc_clear", "lmc_drain_evicted", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_measure_link_kernel", "lmc_measure_link_duplex", "lmc_measure_link_duplex_kernel",
     "lmc_copy", "lmc_tune", "lmc_probe_stream", "lmc_chunk_acquire", "lmc_chunk_release", "lmc_tier_open", "lmc_tier_close",
     "lmc_tier_write", "lmc_tier_wait", "lmc_tier_lookup", "lmc_tier_read", "lmc_tier_errno",
     "lmc_tier_get_stats",
@@ -152,6 +152,7 @@ def _lib():
             "lmc_measure_link_kernel": (st, [vp, u64, i32, ctypes.POINTER(ctypes.c_double),
                                       ctypes.POINTER(ctypes.c_double)]),
             "lmc_measure_link_duplex": (st, [vp, u64, i32, ctypes.POINTER(ctypes.c_double)]),
+            "lmc_measure_link_duplex_kernel": (st, [vp, u64, i32, ctypes.c_uint32, ctypes.POINTER(ctypes.c_double)]),
             "lmc_copy": (st, [vp, vp, vp, u64, vp]),
             "lmc_tune": (st, [vp, ctypes.c_char_p, i64]),
             "lmc_strerror": (ctypes.c_char_p, [st]),
@@ -438,6 +439,13 @@ class Context:
         a = ctypes.c_double()
         self._check(_lib().lmc_measure_link_duplex(self._h, nbytes, reps, ctypes.byref(a)),
                     "lmc_measure_link_duplex")
+        return a.value
+
+    def measure_link_duplex_kernel(self, nbytes, by_kernel, reps=3):
+        """as measure_link_duplex, the upload (bit 0) and / or download (bit 1) made by the copy kernel"""
+        a = ctypes.c_double()
+        self._check(_lib().lmc_measure_link_duplex_kernel(self._h, nbytes, reps, by_kernel, ctypes.byref(a)),
+                    "lmc_measure_link_duplex_kernel")
         return a.value
 
     def copy(self, dst_dev, src_dev, nbytes, stream=None):

@@ -240,6 +240,34 @@ def test_misaligned_arguments_are_refused():
         assert e.value.status == lmc.LMC_ERR_INVAL
 
 
+def test_link_measurements_agree_with_each_other():
+    """The link's rate measured by the runtime's copy and by the library's copy kernel, one way
+    and both ways at once: sane, close to each other, and the pool's content is preserved."""
+    import torch
+    from paper_2510_09665_amd import lmc
+    g = W.KVGeometry(**SHAPES["tiny_cfg1"])
+    n = 64 << 20
+    with lmc.Context(g, 2 * n) as c:
+        ids = np.arange(1, 9, dtype=np.uint64)
+        payload = np.random.default_rng(3).integers(0, 256, 8 * g.chunk_bytes, dtype=np.uint8)
+        c.put_host(ids, payload)
+        h_rt, d_rt = c.measure_link(n, reps=2)
+        h_k, d_k = c.measure_link_kernel(n, reps=2)
+        for r in (h_rt, d_rt, h_k, d_k):
+            assert 5.0 < r < 200.0
+        assert 0.7 < h_k / h_rt < 1.4 and 0.7 < d_k / d_rt < 1.4
+        two_way = [c.measure_link_duplex(n, reps=2)] + [c.measure_link_duplex_kernel(n, m, reps=2) for m in (1, 2, 3)]
+        for r in two_way:
+            assert max(h_rt, d_rt) * 0.9 < r < 2.05 * max(h_rt, d_rt, h_k, d_k)
+        for k, i in enumerate(ids):
+            assert np.array_equal(c.get_host(i), payload[k * g.chunk_bytes:(k + 1) * g.chunk_bytes])
+        for bad in (lambda: c.measure_link_kernel(n + 8), lambda: c.measure_link_duplex_kernel(n, 4),
+                    lambda: c.measure_link_duplex_kernel(2 * n, 1)):
+            with pytest.raises(lmc.LMCError) as e:
+                bad()
+            assert e.value.status == lmc.LMC_ERR_INVAL
+
+
 def test_copy_kernel():
     import torch
     g = W.KVGeometry(**SHAPES["tiny_cfg1"])

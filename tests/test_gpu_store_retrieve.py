@@ -149,7 +149,9 @@ def test_config2_llama3_8b_full_in_the_benchmarks_launch_configuration():
     # bench.py's defaults: two staging buffers of 16 chunks -> launches of 1 and 15 chunks
     st = _run_sequence("llama3_8b", staging_chunks=16, num_staging=2)
     assert st["gather_launches"] == 2 and st["scatter_launches"] == 2
-    # the 480 MiB copy to the host was timed for the copy-engine guard; nothing was wrong with it
+    assert st["d2h_copy_best_gbps"] == 0.0                       # no copy is watched unless the guard is asked for
+    # with the copy-engine guard on, the 480 MiB copy to the host is timed; nothing is wrong with it
+    st = _run_sequence("llama3_8b", staging_chunks=16, num_staging=2, tune=(("d2h_guard", 1),))
     assert 10.0 < st["d2h_copy_best_gbps"] < 80.0 and st["d2h_guard_switches"] == 0
 
 

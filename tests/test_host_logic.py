@@ -110,7 +110,10 @@ def test_data_path_refuses_to_run_without_a_device():
                      lambda: c.scatter(0x1000, 0x1000, 1, fake),
                      lambda: c.copy(0x1000, 0x2000, 16),
                      lambda: c.measure_link(1024),
-                     lambda: c.measure_link_duplex(1024)):
+                     lambda: c.measure_link_kernel(1024),
+                     lambda: c.measure_link_duplex(1024),
+                     lambda: c.measure_link_duplex_kernel(1024, 3),
+                     lambda: c.store_static(fake, 0x1000, 1, 0x1000)):
             with pytest.raises(lmc.LMCError) as e:
                 call()
             assert e.value.status == lmc.LMC_ERR_NODEVICE
