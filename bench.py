@@ -792,7 +792,12 @@ def main():
         return
     dev = torch.device("cuda:0")
     stream = torch.cuda.current_stream()
-    first_pages = random_pages_sample(torch, lmc, W, dev, stream) if "placement" in legs else None
+    first_pages = None
+    if "placement" in legs:
+        try:
+            first_pages = random_pages_sample(torch, lmc, W, dev, stream)
+        except Exception as e:                               # noqa: BLE001 (a side measurement)
+            first_pages = {"error": "%s: %s" % (type(e).__name__, e)}
     g = W.geometry(WORKLOAD)
     seq = W.sequence(WORKLOAD, g)
     n_chunks = seq["tokens"].size // g.CT
@@ -969,24 +974,38 @@ def main():
     if link:
         out["link"] = link
     # the headline's pages and context stay allocated to the end: freeing tens of GiB in
-    # the middle of the run is what brings on the slow state described at the settling loop
+    # the middle of the run is what brings on the slow state described at the settling loop.
+    # A side leg that fails must not take the headline line with it: its error is reported
+    # in its place.
+    def leg(key, fn):
+        try:
+            val = fn()
+        except Exception as e:                               # noqa: BLE001 (reported, not hidden)
+            key, val = key or "mode_legs", {"error": "%s: %s" % (type(e).__name__, e)}
+        if key is None:
+            out.update(val)
+        else:
+            out[key] = val
+
     if "groups" in legs:
-        out["group_size"] = group_size_leg(torch, lmc, W, g, seq, src, dst, d_store, d_load, stream, timed, peaks,
-                                           args.num_staging)
+        leg("group_size", lambda: group_size_leg(torch, lmc, W, g, seq, src, dst, d_store, d_load, stream, timed,
+                                                 peaks, args.num_staging))
     if "configs" in legs:
-        out["configs"] = other_configs(torch, lmc, W, dev, stream, timed, peaks)
+        leg("configs", lambda: other_configs(torch, lmc, W, dev, stream, timed, peaks))
     if legs & {"duplex", "direct", "layerwise", "overlap", "fragmented"}:
-        out.update(mode_legs(torch, lmc, W, dev, stream, legs, args, timed, peaks))
+        leg(None, lambda: mode_legs(torch, lmc, W, dev, stream, legs, args, timed, peaks))
     if "small" in legs:
-        out["small_request"] = small_leg(torch, lmc, W, dev, stream, timed)
+        leg("small_request", lambda: small_leg(torch, lmc, W, dev, stream, timed))
     if "placement" in legs:
-        out["page_placement"] = placement_leg(torch, lmc, W, dev, stream)
-        out["page_placement"]["random_pages_allocated_first_in_the_process"] = first_pages
-        out["page_placement"]["random_pages_allocated_late_in_the_process"] = \
-            random_pages_sample(torch, lmc, W, dev, stream)
+        def placement():
+            res = placement_leg(torch, lmc, W, dev, stream)
+            res["random_pages_allocated_first_in_the_process"] = first_pages
+            res["random_pages_allocated_late_in_the_process"] = random_pages_sample(torch, lmc, W, dev, stream)
+            return res
+        leg("page_placement", placement)
     ctx.destroy()
     if "cpu" in legs:
-        out["cpu_baseline"] = cpu_baseline()
+        leg("cpu_baseline", cpu_baseline)
     print(json.dumps(out), flush=True)
 
 

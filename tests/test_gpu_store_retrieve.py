@@ -157,10 +157,15 @@ def test_config2_llama3_8b_full_in_the_benchmarks_launch_configuration():
 
 def test_config5_mla_bf16_full():
     _run_sequence("mla_bf16", staging_chunks=2)
+    # bench.py's launch configuration for this shape: the whole request fits one staging buffer
+    st = _run_sequence("mla_bf16", staging_chunks=32)
+    assert st["gather_launches"] == 2 and st["scatter_launches"] == 2
 
 
 def test_config5_mla_fp8_full():
     _run_sequence("mla_fp8", staging_chunks=3)      # 32 chunks in groups of 3: ragged last group
+    st = _run_sequence("mla_fp8", staging_chunks=32)    # as bench.py launches it
+    assert st["gather_launches"] == 2 and st["scatter_launches"] == 2
 
 
 @pytest.mark.parametrize("flags", ["poison", "force_sync", "validate", "direct"])
@@ -361,7 +366,8 @@ def test_stored_chunks_go_to_two_directories_without_a_copy_and_come_back(tmp_pa
 
 def test_config3_llama3_70b_full_size_every_chunk_against_the_oracle():
     """Full size: 40 GiB of pages on the device, 128 chunks = 10 GiB through the pinned
-    pool with the double-buffered pipeline (2 staging buffers of 2 chunks).  The oracle
+    pool with the double-buffered pipeline in the launch configuration bench.py times (2
+    staging buffers of 8 chunks: groups of 1, 15 x 8 and 7 chunks).  The oracle
     sees every source block (a compact host copy, payload drawn on the host) and is
     compared byte for byte with all 128 pool chunks and with every destination page;
     blocks that no slot names must still hold the sentinel."""
@@ -381,7 +387,7 @@ def test_config3_llama3_70b_full_size_every_chunk_against_the_oracle():
     s_slots = src.compact_slots(seq["store_slots"]).reshape(n_chunks, g.CT)
     l_slots = dst.compact_slots(seq["load_slots"]).reshape(n_chunks, g.CT)
     stream = torch.cuda.current_stream()
-    with lmc.Context(g, n_chunks * g.chunk_bytes, staging_chunks=2) as c:
+    with lmc.Context(g, n_chunks * g.chunk_bytes, staging_chunks=8, num_staging=2) as c:
         ids = c.hash_chunks(seq["tokens"])
         assert np.array_equal(ids, oracle.hash_chunks(seq["tokens"], g.CT, 0))
         d_store, d_load = slots_to_device(seq["store_slots"]), slots_to_device(seq["load_slots"])
@@ -407,6 +413,7 @@ def test_config3_llama3_70b_full_size_every_chunk_against_the_oracle():
         st = c.get_stats()
         assert st["chunks_stored"] == st["chunks_retrieved"] == n_chunks
         assert st["bytes_d2h"] == st["bytes_h2d"] == n_chunks * g.chunk_bytes
+        assert st["gather_launches"] == st["scatter_launches"] == 17
 
 
 def test_config4_batched_multi_request_retrieve():
@@ -424,7 +431,8 @@ def test_config4_batched_multi_request_retrieve():
     all_blocks = np.concatenate([r["load_blocks"] for r in reqs])
     dst = PagedKV(g, all_blocks, fill="sentinel")
     base = W.payload_bytes(rng, g, g.chunk_bytes).view(np.uint64)
-    with lmc.Context(g, (n_hit + 3) * g.chunk_bytes, staging_chunks=8) as c:
+    per = 16                                                 # chunks per launch, as bench.py runs this configuration
+    with lmc.Context(g, (n_hit + 3) * g.chunk_bytes, staging_chunks=per) as c:
         ids_per_req = [c.hash_chunks(r["tokens"]) for r in reqs]
         for r, ids in zip(reqs, ids_per_req):
             assert np.array_equal(ids, oracle.hash_chunks(r["tokens"], g.CT, 0))
@@ -450,7 +458,7 @@ def test_config4_batched_multi_request_retrieve():
         c.wait(t)
         torch.cuda.synchronize()
         st = c.get_stats()
-        assert st["chunks_retrieved"] == n_hit and st["scatter_launches"] == -(-(n_hit - 1) // 8) + 1
+        assert st["chunks_retrieved"] == n_hit and st["scatter_launches"] == -(-(n_hit - 1) // per) + 1
         cs = dst.compact_slots(slots)
         j = 0
         for ri, r in enumerate(reqs):
