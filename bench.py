@@ -278,6 +278,23 @@ def other_configs(torch, lmc, W, dev, stream, timed, peaks):
     return res
 
 
+def launch_address_stream(torch, W, g, kv, slots, n_chunks, dev):
+    """The 4 KiB tiles a gather / scatter launch over `slots` touches on the paged side, in
+    the launch's own order (tile, then layer-plane, then chunk), as tile numbers relative to
+    the lowest layer pointer: the input of lmc_copy_tiles.  A tile of the launch is
+    4096 / R token rows, which lie together in the page for the NHD layouts used here."""
+    base = min(t_.data_ptr() for t_ in kv)
+    tiles_per_plane = g.CT * g.R // 4096
+    rows_per_tile = 4096 // g.R
+    w_ = np.arange(n_chunks * g.L * g.P * tiles_per_plane, dtype=np.int64)
+    tile, lp, ch = w_ % tiles_per_plane, (w_ // tiles_per_plane) % (g.L * g.P), w_ // (tiles_per_plane * g.L * g.P)
+    slot0 = np.asarray(slots)[ch * g.CT + tile * rows_per_tile]
+    layer_at = np.array([t_.data_ptr() - base for t_ in kv], dtype=np.int64)
+    addr = layer_at[lp // g.P] + (lp % g.P) * g.plane_stride + slot0 * g.R
+    assert (addr % 4096 == 0).all() and addr.max() // 4096 < 2**32
+    return base, torch.from_numpy((addr // 4096).astype(np.uint32).view(np.int32)).to(dev), int(w_.size)
+
+
 def random_pages_sample(torch, lmc, W, dev, stream):
     """Gather / scatter / copy read + write GB/s over 1024 random 32 KiB pages of the
     Llama-3-8B shape (64 chunks, 2 GiB per launch), pages and staging allocated now.  Run
@@ -293,10 +310,17 @@ def random_pages_sample(torch, lmc, W, dev, stream):
     staging = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     spare = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     res = {}
+    base, pages_order, n_t = launch_address_stream(torch, W, g, kv, W.slots_from_blocks(g, rand, n_tok), n_chunks, dev)
     with lmc.Context(g, 64 << 20, device=0) as ctx:
         for key, fn in (("gather", lambda: ctx.gather(kv, d, n_chunks, staging, stream)),
                         ("scatter", lambda: ctx.scatter(staging, d, n_chunks, kv, stream)),
-                        ("copy_kernel", lambda: ctx.copy(spare, staging, nbytes, stream))):
+                        ("copy_kernel", lambda: ctx.copy(spare, staging, nbytes, stream)),
+                        # plain tile copies with the same address stream: what the pattern alone costs
+                        ("gather_like_plain_copy", lambda: ctx.copy_tiles(staging, None, base, pages_order, n_t, 0, stream)),
+                        ("scatter_like_plain_copy", lambda: ctx.copy_tiles(base, pages_order, staging, None, n_t, 0, stream)),
+                        # ... and its two halves alone (x 2, so that they read on the same scale)
+                        ("twice_read_only_of_the_pages", lambda: ctx.copy_tiles(staging, None, base, pages_order, n_t, 1, stream)),
+                        ("twice_write_only_of_the_pages", lambda: ctx.copy_tiles(base, pages_order, staging, None, n_t, 2, stream))):
             fn()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             best = 1e30
@@ -368,6 +392,18 @@ def placement_leg(torch, lmc, W, dev, stream):
             res["random_dest_order"]["scatter_hbm_gbps_" + key] = rate(lambda: ctx.scatter(staging, d, n_chunks, kv, stream))
         ctx.tune("scatter_order", 0)
         res["copy_kernel_hbm_gbps"] = rate(lambda: ctx.copy(spare, staging, nbytes, stream))
+        # What the access pattern alone costs: a plain copy of 4 KiB tiles (no slot mapping, no
+        # geometry) fed with exactly the address stream of the random-pages launch above, in
+        # the launch's own order (tile, then layer-plane, then chunk).  A tile of the launch
+        # is two token rows = 4 KiB on both sides.
+        base, pages_order, n_t = launch_address_stream(torch, W, g, kv, W.slots_from_blocks(g, rand, n_tok), n_chunks, dev)
+        res["plain_copy_with_the_address_stream_of_random"] = {
+            "scatter_like_hbm_gbps": rate(lambda: ctx.copy_tiles(base, pages_order, staging, None, n_t, 0, stream)),
+            "gather_like_hbm_gbps": rate(lambda: ctx.copy_tiles(staging, None, base, pages_order, n_t, 0, stream)),
+            "read_only_pages_gbps": round(rate(lambda: ctx.copy_tiles(staging, None, base, pages_order, n_t, 1, stream)) / 2, 1),
+            "write_only_pages_gbps": round(rate(lambda: ctx.copy_tiles(base, pages_order, staging, None, n_t, 2, stream)) / 2, 1),
+            "read_only_linear_gbps": round(rate(lambda: ctx.copy_tiles(spare, None, staging, None, n_t, 1, stream)) / 2, 1),
+            "write_only_linear_gbps": round(rate(lambda: ctx.copy_tiles(spare, None, staging, None, n_t, 2, stream)) / 2, 1)}
         ctx.wait()
     del kv
     bm = W.BlockMajorKV(g)

@@ -487,6 +487,18 @@ lmc_status_t lmc_measure_link_kernel(lmc_ctx_t *ctx, uint64_t nbytes, int32_t re
                                      double *h2d_gbps_out, double *d2h_gbps_out);
 lmc_status_t lmc_copy(lmc_ctx_t *ctx, void *dst_dev, const void *src_dev, uint64_t nbytes,
                       void *stream);
+/* The ceiling of an access pattern: a plain copy of 4 KiB tiles in a given order, with no
+ * slot mapping and no geometry.  Workgroup w copies tile src_order[w] of src_dev to tile
+ * dst_order[w] of dst_dev (tile t = bytes [4096 t, 4096 t + 4096) from the pointer; a NULL
+ * order means t = w).  dst_order / src_order: DEVICE uint32[n_tiles]; the caller guarantees
+ * that every tile lies inside memory it owns and that no two workgroups write the same tile.
+ * Fed with the address stream of a gather or scatter launch it measures what that stream
+ * alone costs (section 8.6 compares achieved bandwidths; this is the denominator for the
+ * two kernels on a given page placement).  mode 0 copies, 1 only reads, 2 only writes.
+ * n_tiles < 2^31.  Enqueued on `stream`. */
+lmc_status_t lmc_copy_tiles(lmc_ctx_t *ctx, void *dst_dev, const uint32_t *dst_order,
+                            const void *src_dev, const uint32_t *src_order, uint64_t n_tiles,
+                            uint32_t mode, void *stream);
 /* Both directions at once (section 5.1 "Parallel Store/load Operations": the host link is
  * full duplex): nbytes up and nbytes down at the same time, sum of both directions in
  * GB/s, best of reps.  Needs 2*nbytes of pool; pool content is preserved.  Blocks. */

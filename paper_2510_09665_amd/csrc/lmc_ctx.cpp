@@ -1874,6 +1874,20 @@ lmc_status_t lmc_copy(lmc_ctx_t *c, void *dst, const void *src, uint64_t nbytes,
     return LMC_OK;
 }
 
+lmc_status_t lmc_copy_tiles(lmc_ctx_t *c, void *dst, const uint32_t *dst_order, const void *src,
+                            const uint32_t *src_order, uint64_t n_tiles, uint32_t mode, void *stream) {
+    if (!c || !dst || !src || mode > 2 || n_tiles > 0x7FFFFFFFull ||
+        (reinterpret_cast<uintptr_t>(dst) % 16) != 0 || (reinterpret_cast<uintptr_t>(src) % 16) != 0)
+        return LMC_ERR_INVAL;
+    if (!c->has_device) return LMC_ERR_NODEVICE;
+    DeviceScope dev(c);
+    // mode 1 needs somewhere to pretend to write to: the flag block's last words, seen by the GPU
+    uint8_t *sink = reinterpret_cast<uint8_t *>(c->bad_flag_dev + 12);
+    HIPCHK(c, lmc::launch_copy_tiles(static_cast<uint8_t *>(dst), dst_order, static_cast<const uint8_t *>(src),
+                                     src_order, uint32_t(n_tiles), mode, sink, static_cast<hipStream_t>(stream)));
+    return LMC_OK;
+}
+
 lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
     if (!c || !key || value < 0) return LMC_ERR_INVAL;
     std::lock_guard<std::mutex> lock(c->mu);

@@ -352,6 +352,29 @@ __global__ __launch_bounds__(kThreads) void copy_bytes(u32x4 *__restrict__ dst,
     if (i < n_vec) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+// Plain copy of 4 KiB tiles in a given order, no slot mapping, no geometry: workgroup w
+// copies tile src_order[w] of src to tile dst_order[w] of dst (a null order = w itself).
+// Fed with the address stream of a gather or scatter launch it shows what the access
+// pattern alone costs: the ceiling that launch can reach.  mode 1 only reads, mode 2 only
+// writes (reads and writes react differently to scattered pages).
+__global__ __launch_bounds__(kThreads) void copy_tiles(u32x4 *dst, const uint32_t *__restrict__ dst_order,
+                                                       const u32x4 *src, const uint32_t *__restrict__ src_order,
+                                                       uint32_t n_tiles, uint32_t mode, u32x4 *sink) {
+    const uint32_t w = blockIdx.x;
+    if (w >= n_tiles) return;
+    const uint64_t s = (src_order ? uint64_t(src_order[w]) : uint64_t(w)) * kThreads + threadIdx.x;
+    const uint64_t d = (dst_order ? uint64_t(dst_order[w]) : uint64_t(w)) * kThreads + threadIdx.x;
+    if (mode == 0) {
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + s), dst + d);
+    } else if (mode == 1) {
+        const u32x4 v = __builtin_nontemporal_load(src + s);
+        if (v.x == 0x9E3779B9u && v.y == 0x7F4A7C15u && v.z == 0xF39CC060u && v.w == 0x5CEDC834u) *sink = v;
+    } else {
+        const u32x4 v = {w, w, w, w};
+        __builtin_nontemporal_store(v, dst + d);
+    }
+}
+
 // Copy between device memory and the pinned pool, paced for the host link like
 // move_rows_paced: a fixed, small grid whose workgroups take 4 KiB tiles in turn.  The
 // bytes form `rows` rows of width_vec 16-byte vectors, src_pitch / dst_pitch bytes apart
@@ -581,6 +604,16 @@ hipError_t launch_copy(uint8_t *dst, const uint8_t *src, uint64_t nbytes, hipStr
                            0, stream, reinterpret_cast<u32x4 *>(dst) + v0,
                            reinterpret_cast<const u32x4 *>(src) + v0, n);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_tiles(uint8_t *dst, const uint32_t *dst_order, const uint8_t *src,
+                             const uint32_t *src_order, uint32_t n_tiles, uint32_t mode, uint8_t *sink,
+                             hipStream_t stream) {
+    if (n_tiles == 0) return hipSuccess;
+    if (n_tiles > 0x7FFFFFFFu || mode > 2) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(copy_tiles, dim3(n_tiles), dim3(kThreads), 0, stream, reinterpret_cast<u32x4 *>(dst), dst_order,
+                       reinterpret_cast<const u32x4 *>(src), src_order, n_tiles, mode, reinterpret_cast<u32x4 *>(sink));
     return hipGetLastError();
 }
 

@@ -111,6 +111,11 @@ LaunchView layer_view(const KernelGeom &g, uint32_t planes_per_layer, uint32_t f
 hipError_t launch_check_slots(const int64_t *slot_mapping, uint64_t n, uint32_t n_slots,
                               int32_t *bad_flag, hipStream_t stream);
 hipError_t launch_copy(uint8_t *dst, const uint8_t *src, uint64_t nbytes, hipStream_t stream);
+// n_tiles tiles of 4 KiB: tile src_order[w] of src to tile dst_order[w] of dst (null = w);
+// mode 0 copy, 1 read only, 2 write only; sink: 16 bytes of device memory for mode 1
+hipError_t launch_copy_tiles(uint8_t *dst, const uint32_t *dst_order, const uint8_t *src,
+                             const uint32_t *src_order, uint32_t n_tiles, uint32_t mode, uint8_t *sink,
+                             hipStream_t stream);
 // rows x width bytes, rows src_pitch / dst_pitch apart, by `groups` workgroups that take
 // tiles in turn (the shape that suits a copy whose one side is pinned host memory).
 // Everything must be a multiple of 16 bytes, else hipErrorInvalidValue.

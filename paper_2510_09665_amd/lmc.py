@@ -34,7 +34,7 @@ EXPORTS = [
     "lmc_store_begin", "lmc_store_layers", "lmc_wait_layer", "lmc_wait", "lmc_gather",
     "lmc_scatter", "lmc_store_static", "lmc_put_host", "lmc_get_host", "lmc_find_slot", "lmc_pin", "lmc_unpin",
     "lmc_clear", "lmc_drain_evicted", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_measure_link_kernel", "lmc_measure_link_duplex", "lmc_measure_link_duplex_kernel",
-    "lmc_copy", "lmc_tune", "lmc_probe_stream", "lmc_chunk_acquire", "lmc_chunk_release", "lmc_tier_open", "lmc_tier_close",
+    "lmc_copy", "lmc_copy_tiles", "lmc_tune", "lmc_probe_stream", "lmc_chunk_acquire", "lmc_chunk_release", "lmc_tier_open", "lmc_tier_close",
     "lmc_tier_write", "lmc_tier_wait", "lmc_tier_lookup", "lmc_tier_read", "lmc_tier_errno",
     "lmc_tier_get_stats",
     "lmc_strerror", "lmc_last_hip_error",
@@ -154,6 +154,7 @@ def _lib():
             "lmc_measure_link_duplex": (st, [vp, u64, i32, ctypes.POINTER(ctypes.c_double)]),
             "lmc_measure_link_duplex_kernel": (st, [vp, u64, i32, ctypes.c_uint32, ctypes.POINTER(ctypes.c_double)]),
             "lmc_copy": (st, [vp, vp, vp, u64, vp]),
+            "lmc_copy_tiles": (st, [vp, vp, vp, vp, vp, u64, ctypes.c_uint32, vp]),
             "lmc_tune": (st, [vp, ctypes.c_char_p, i64]),
             "lmc_strerror": (ctypes.c_char_p, [st]),
             "lmc_last_hip_error": (i32, [vp]),
@@ -451,6 +452,11 @@ class Context:
     def copy(self, dst_dev, src_dev, nbytes, stream=None):
         self._check(_lib().lmc_copy(self._h, _dev(dst_dev), _dev(src_dev), nbytes, _stream(stream)),
                     "lmc_copy")
+
+    def copy_tiles(self, dst_dev, dst_order, src_dev, src_order, n_tiles, mode=0, stream=None):
+        """4 KiB tiles in a given order (device uint32 tensors or None); mode 0 copy, 1 read, 2 write"""
+        self._check(_lib().lmc_copy_tiles(self._h, _dev(dst_dev), _dev(dst_order), _dev(src_dev), _dev(src_order),
+                                          n_tiles, mode, _stream(stream)), "lmc_copy_tiles")
 
     def probe_stream(self, stream):
         """Bit mask of the library's copy streams that share a hardware queue with `stream`

@@ -268,6 +268,37 @@ def test_link_measurements_agree_with_each_other():
             assert e.value.status == lmc.LMC_ERR_INVAL
 
 
+def test_copy_tiles_moves_tiles_in_the_given_order():
+    import torch
+    from gpu_util import slots_to_device
+    g = W.KVGeometry(**SHAPES["tiny_cfg1"])
+    rng = np.random.default_rng(9)
+    n_tiles, T = 300, 4096
+    with _ctx(g) as c:
+        src = torch.randint(0, 256, (n_tiles * T,), dtype=torch.uint8, device="cuda")
+        so, do = rng.permutation(n_tiles).astype(np.uint32), rng.permutation(n_tiles).astype(np.uint32)
+        d_so, d_do = torch.from_numpy(so.view(np.int32)).cuda(), torch.from_numpy(do.view(np.int32)).cuda()
+        for use_s, use_d in ((True, True), (True, False), (False, True), (False, False)):
+            dst = torch.zeros(n_tiles * T + T, dtype=torch.uint8, device="cuda")
+            c.copy_tiles(dst, d_do if use_d else None, src, d_so if use_s else None, n_tiles, 0, torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            want = np.zeros((n_tiles + 1, T), dtype=np.uint8)
+            s_np = src.cpu().numpy().reshape(n_tiles, T)
+            want[do if use_d else np.arange(n_tiles)] = s_np[so if use_s else np.arange(n_tiles)]
+            assert np.array_equal(dst.cpu().numpy().reshape(n_tiles + 1, T), want)
+        # read-only and write-only modes touch nothing else / write a known pattern
+        before = src.clone()
+        dst = torch.zeros(n_tiles * T, dtype=torch.uint8, device="cuda")
+        c.copy_tiles(dst, None, src, d_so, n_tiles, 1)
+        c.copy_tiles(dst, d_do, src, None, 17, 2)
+        torch.cuda.synchronize()
+        assert torch.equal(src, before)
+        got = dst.cpu().numpy().view(np.uint32).reshape(n_tiles, T // 4)
+        for w in range(17):
+            assert (got[do[w]] == w).all()
+        assert (np.delete(got, do[:17], axis=0) == 0).all()
+
+
 def test_copy_kernel():
     import torch
     g = W.KVGeometry(**SHAPES["tiny_cfg1"])
