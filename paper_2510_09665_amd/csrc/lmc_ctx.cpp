@@ -53,6 +53,12 @@ hipError_t resolve_static_scratch(int device) {
     return hipSuccess;
 }
 
+uint8_t *static_scratch_of(int device) {
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(static_scratch_mu);
+    return static_scratch_at[device];
+}
+
 // Staging ring of one direction.  The memory is num_staging allocations of buf_bytes;
 // it is handed out in slots of slot_bytes (bulk mode: one slot per allocation;
 // layer-wise mode: many small slots, so that a call seldom has to wait for a slot).
@@ -1458,7 +1464,7 @@ lmc_status_t lmc_store_static(lmc_ctx_t *c, void *const *kv_layers, const int64_
     std::lock_guard<std::mutex> lock(c->mu);
     DeviceScope dev(c);
     if (c->cfg.device >= kMaxDevices) return LMC_ERR_INVAL;
-    uint8_t *const stage = static_scratch_at[c->cfg.device];   // looked up by lmc_create
+    uint8_t *const stage = static_scratch_of(c->cfg.device);   // looked up by lmc_create
     if (stage == nullptr) return LMC_ERR_HIP;
     const lmc_kv_geom_t &geom = c->cfg.geom;
     const uint64_t cb = uint64_t(c->chunk_bytes);
