@@ -85,7 +85,8 @@ def test_scatter_in_destination_order_matches_oracle(name, xcd_run):
     """The launch shape for scatters that fill many pages per plane (rows visited in
     ascending slot order, the order built on the device) must write exactly what the
     oracle's scatter writes: every shape, tokens without a page, a slot outside the pages
-    (skipped and reported), two calls in a row on the same scratch, the second smaller."""
+    (skipped and reported), three calls in a row on the same scratch: a small one, a larger
+    one (the scratch grows), a small one again."""
     import torch
     from gpu_util import PagedKV, assert_layers_equal, slots_to_device
     from paper_2510_09665_amd import lmc
@@ -96,7 +97,7 @@ def test_scatter_in_destination_order_matches_oracle(name, xcd_run):
         c.tune("scatter_order", 2)
         if xcd_run is not None:
             c.tune("xcd_run", xcd_run)
-        for n_chunks in (3, 1):
+        for n_chunks in (1, 3, 1):
             n_tok = n_chunks * g.CT
             chunks = oracle.gather(g, src.host, rng.permutation(g.n_slots)[:n_tok].astype(np.int64))
             tau = rng.permutation(g.n_slots)[:n_tok].astype(np.int64)
