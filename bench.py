@@ -166,9 +166,32 @@ def link_peaks(ctx, pool_bytes):
             r = ctx.measure_link_duplex_kernel(mib << 20, by_kernel, reps=8)
             if r > duplex[0]:
                 duplex = (r, "%s, %d MiB each way" % (how[by_kernel], mib))
+    # each direction as a row of consecutive copies, as the pipelines issue them group by group
+    for gib, pieces in ((4, 2), (4, 8), (4, 16)):
+        if 2 * (gib << 30) > pool_bytes:
+            continue
+        r = ctx.measure_link_duplex_kernel(gib << 30, pieces << 8, reps=2)
+        if r > duplex[0]:
+            duplex = (r, "hipMemcpyAsync both ways, %d GiB each way in %d consecutive copies" % (gib, pieces))
     return {"h2d_peak_gbps": best["h2d"][0], "h2d_peak_from": best["h2d"][1],
             "d2h_peak_gbps": best["d2h"][0], "d2h_peak_from": best["d2h"][1],
             "duplex_peak_gbps": duplex[0], "duplex_peak_from": duplex[1]}
+
+
+def against_duplex_peak(got, peaks):
+    """A summed two-way rate against the link's measured two-way peak.  The link carried
+    what the pipeline moved: a peak below that would be no peak."""
+    peak, peak_from = peaks["duplex_peak_gbps"], peaks["duplex_peak_from"]
+    if got > peak:
+        peak, peak_from = got, "this store + retrieve itself (above every two-way copy measured: %.2f GB/s, %s)" % (
+            peaks["duplex_peak_gbps"], peaks["duplex_peak_from"])
+    one_way = peaks["h2d_peak_gbps"] + peaks["d2h_peak_gbps"]
+    return {"store_plus_retrieve_gbps": round(got, 2),
+            "link_duplex_peak_gbps": round(peak, 2), "link_duplex_peak_from": peak_from,
+            "frac_of_duplex_peak": round(got / peak, 4),
+            # against what two perfect one-way transfers would add up to
+            "sum_of_one_way_peaks_gbps": round(one_way, 2),
+            "frac_of_sum_of_one_way_peaks": round(got / one_way, 4)}
 
 
 def kernel_only(torch, ctx, W, name, g, src, dst, n_chunks, dev, stream, gather_slots=None, scatter_slots=None,
@@ -542,17 +565,7 @@ def mode_legs(torch, lmc, W, dev, stream, legs, args, timed, peaks):
             ctx.wait(t2)
         t_both = timed(both)
         got = 2 * payload_one_way / t_both / 1e9
-        # the link carried what the pipeline moved: a peak below that would be no peak
-        peak, peak_from = peaks["duplex_peak_gbps"], peaks["duplex_peak_from"]
-        if got > peak:
-            peak, peak_from = got, "this store + retrieve itself (above every two-way copy measured: %.2f GB/s, %s)" % (
-                peaks["duplex_peak_gbps"], peaks["duplex_peak_from"])
-        duplex = {"store_plus_retrieve_gbps": round(got, 2),
-                  "link_duplex_peak_gbps": round(peak, 2), "link_duplex_peak_from": peak_from,
-                  "frac_of_duplex_peak": round(got / peak, 4),
-                  # against what two perfect one-way transfers would add up to
-                  "sum_of_one_way_peaks_gbps": round(peaks["h2d_peak_gbps"] + peaks["d2h_peak_gbps"], 2),
-                  "frac_of_sum_of_one_way_peaks": round(got / (peaks["h2d_peak_gbps"] + peaks["d2h_peak_gbps"]), 4)}
+        duplex = against_duplex_peak(got, peaks)
         ctx.clear(ids_a)
         ctx.clear(ids_b)
 
@@ -973,6 +986,22 @@ def main():
             ctx.wait(ctx.store(src, d_store, ids, stream))
         t_store = timed(store_only, reps=4)
         t_load = timed(lambda: ctx.wait(ctx.retrieve(ids, d_load, dst, stream)), reps=4)
+        # both directions at once: the first half of the request is stored while the second
+        # half is retrieved
+        half = n_chunks // 2
+
+        def both():
+            ctx.clear(ids[:half])
+            t1 = ctx.store(src, d_store[:half * g.CT], ids[:half], stream)
+            t2 = ctx.retrieve(ids[half:], d_load[half * g.CT:], dst, stream)
+            ctx.wait(t1)
+            ctx.wait(t2)
+        t_both = timed(both, reps=4)
+        # the same retrieve without the wait it leaves on the caller's stream (the caller
+        # orders by lmc_wait, as this benchmark does anyway)
+        ctx.tune("caller_waits", 0)
+        t_load_nw = timed(lambda: ctx.wait(ctx.retrieve(ids, d_load, dst, stream)), reps=4)
+        ctx.tune("caller_waits", 1)
         ctx.clear(ids)
         link = dict(peaks)
         for k_ in ("h2d_peak_gbps", "d2h_peak_gbps", "duplex_peak_gbps"):
@@ -982,6 +1011,9 @@ def main():
             "retrieve_gbps": round(payload_one_way / t_load / 1e9, 2),
             "store_frac_of_d2h_peak": round(payload_one_way / t_store / 1e9 / peaks["d2h_peak_gbps"], 4),
             "retrieve_frac_of_h2d_peak": round(payload_one_way / t_load / 1e9 / peaks["h2d_peak_gbps"], 4),
+            "retrieve_gbps_without_the_wait_on_the_callers_stream": round(payload_one_way / t_load_nw / 1e9, 2),
+            "half_stored_while_half_is_retrieved": against_duplex_peak(
+                (half + n_chunks - half) * g.chunk_bytes / t_both / 1e9, peaks),
         })
 
     # kernels alone: the whole request (128 chunks, 10 GiB) in one launch

@@ -96,6 +96,15 @@ enum {
                                       the retrieve calls; lookup, pin, unpin are not.  The
                                       paper names no policy (sections 4.2, 7); without the
                                       flag a full pool gives LMC_ERR_NOMEM. */
+#define LMC_FLAG_KEEP_STREAMS 64u   /* leave the library's six streams on the hardware queues
+                                      the runtime gave them.  Without the flag lmc_create (pool
+                                      and staging buffer of 8 MiB or more) spends some tens of
+                                      milliseconds finding out which streams share a queue and
+                                      picks, from a few more than it needs, streams such that
+                                      the two kernel streams and the first copy stream of each
+                                      direction have four different queues: the four streams
+                                      of a store and a retrieve running together then never
+                                      wait for each other. */
 #define LMC_FLAG_TIMING 8u         /* give every gather / scatter launch a start and a stop
                                       HIP event (kernel begin / end on its own stream);
                                       durations appear in lmc_stats_t. */
@@ -505,8 +514,10 @@ lmc_status_t lmc_copy_tiles(lmc_ctx_t *ctx, void *dst_dev, const uint32_t *dst_o
 lmc_status_t lmc_measure_link_duplex(lmc_ctx_t *ctx, uint64_t nbytes, int32_t reps,
                                      double *sum_gbps_out);
 /* The same with the library's link-paced copy kernel in place of the runtime's copy for the
- * upload (by_kernel bit 0), the download (bit 1) or both; nbytes a multiple of 16.  The
- * two-way peak of the link is the best of the four combinations. */
+ * upload (by_kernel bit 0), the download (bit 1) or both.  Bits 8-15 of by_kernel, if not 0:
+ * each direction moves its nbytes as that many consecutive transfers, the way the pipelines
+ * issue them group by group.  nbytes a multiple of 16 times the number of pieces.  The
+ * two-way peak of the link is the best over the combinations. */
 lmc_status_t lmc_measure_link_duplex_kernel(lmc_ctx_t *ctx, uint64_t nbytes, int32_t reps,
                                             uint32_t by_kernel, double *sum_gbps_out);
 
@@ -554,7 +565,14 @@ lmc_status_t lmc_probe_stream(lmc_ctx_t *ctx, void *stream, uint32_t *mask_out);
  * pages that cover at least one block in "ordered_min_density_inv" of a plane, 2 = every
  * launch; "ordered_group_rows": rows per group, 0 = plane by plane.  Same bytes; on MI355X
  * it measured slower than the plain order at every density, see the benchmark's
- * page_placement figures), "fail_hip_after" (for tests of the
+ * page_placement figures), "caller_waits" (default 1: an lmc_retrieve / lmc_retrieve_batch
+ * ends by making the caller's stream wait for it; 0: it does not, and the caller orders its
+ * work after the ticket itself with lmc_wait.  A wait that stands at the head of an
+ * otherwise idle hardware queue for the length of a large retrieve cost that retrieve
+ * 0.5 % on MI355X), "arrange_streams" (1: place the library's streams on hardware queues
+ * again, as lmc_create does without LMC_FLAG_KEEP_STREAMS, e.g. after the process has made
+ * its own streams; LMC_ERR_BUSY unless every ticket has been waited for),
+ * "fail_hip_after" (for tests of the
  * error paths: the n-th HIP call the library checks from now on is not made and counts as
  * failed, once; 0 = off.  Nothing on the device goes wrong).
  * Unknown key or out-of-range value: LMC_ERR_INVAL. */

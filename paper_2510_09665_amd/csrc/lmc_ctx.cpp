@@ -120,6 +120,7 @@ struct lmc_ctx {
     // it holds the copies on the copy kernel (55.7 GB/s) for seconds although the runtime's
     // were back at 56.8 after one store.  Steady state is the same either way.
     bool d2h_guard_on = false;
+    bool caller_waits = true;     // a bulk retrieve ends with the caller's stream waiting for it
     lmc::CopyEngineGuard d2h_guard;
     std::vector<CopyTiming> copy_timings;
     std::chrono::steady_clock::time_point born = std::chrono::steady_clock::now();
@@ -375,6 +376,39 @@ lmc_status_t order_after(lmc_ctx *c, hipStream_t waiter, hipStream_t stream) {
     // record they saw
     c->free_sync_events.push_back(e);
     return LMC_OK;
+}
+
+// Orders `waiter` after the work the caller has put on its own stream so far.  A stream
+// with nothing pending needs no event, and is better off without one: an event recorded on
+// the caller's stream takes its place in that stream's hardware queue, behind whatever a
+// library stream that shares the queue still has to run (with a store under way and the
+// caller's stream in the gather stream's queue, a retrieve issued next would start only
+// when the store's last gather has run).
+lmc_status_t order_after_caller(lmc_ctx *c, hipStream_t waiter, hipStream_t user) {
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(user, &capturing) == hipSuccess && capturing == hipStreamCaptureStatusNone) {
+        if (hipStreamQuery(user) == hipSuccess) return LMC_OK;
+    }
+    (void)hipGetLastError();   // "not ready" is an answer, not a failure
+    return order_after(c, waiter, user);
+}
+
+// Is an operation of the other direction still under way?  The second copy stream of a
+// host-to-device direction sits in the hardware queue of the device-to-host copies (see
+// arrange_streams), and as created any two streams may share one: next to a transfer the
+// other way a second copy stream would not add a copy in flight but hold that transfer's
+// copies up, so it is left out then.
+bool other_direction_busy(lmc_ctx *c, bool for_store) {
+    for (const Op &o : c->ops) {
+        const bool is_store = o.pending || o.final_stream == c->s_d2h || o.final_stream == c->s_gather;
+        if (is_store == for_store) continue;
+        if (o.pending) return true;
+        if (o.done != nullptr && hipEventQuery(o.done) != hipSuccess) {
+            (void)hipGetLastError();
+            return true;
+        }
+    }
+    return false;
 }
 
 // LMC_FLAG_VALIDATE_SLOTS: device-side range check with a host wait.
@@ -783,7 +817,7 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
     const int64_t CT = geom.chunk_tokens;
     // the pages may still be in use, and the slot mapping still be on its way, by work
     // already on the caller's stream
-    if (n_chunks > 0 && (rc = order_after(c, c->s_scatter, user)) != LMC_OK) return rc;
+    if (n_chunks > 0 && (rc = order_after_caller(c, c->s_scatter, user)) != LMC_OK) return rc;
     rc = validate_slots(c, slot_mapping, n_chunks * CT, c->s_scatter);
     if (rc != LMC_OK) return rc;
 
@@ -848,6 +882,7 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
         return force_sync(c, c->s_scatter);
     };
 
+    const bool two_copy_streams = !other_direction_busy(c, false);
     auto enqueue = [&]() -> lmc_status_t {
         if (direct && !op.layerwise) {
             if ((rc = load_direct(lmc::bulk_view(c->kg), 0)) != LMC_OK) return rc;
@@ -860,7 +895,7 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
             const int64_t body = (edge > 0 && n_chunks > edge) ? n_chunks - edge : n_chunks;
             for (int64_t i0 = 0, k = 0; i0 < n_chunks; i0 += k) {
                 k = i0 < body ? std::min(per, body - i0) : n_chunks - i0;
-                if ((rc = load_group(view, 0, i0, k, c->s_h2d, c->s_h2d2)) != LMC_OK) return rc;
+                if ((rc = load_group(view, 0, i0, k, c->s_h2d, two_copy_streams ? c->s_h2d2 : nullptr)) != LMC_OK) return rc;
             }
         } else {
             // All chunks' share of a few layers at a time: one rectangle copy per run of pool
@@ -881,7 +916,7 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
                     // Steps alternate between two copy streams: on one stream the runtime puts
                     // an event marker between consecutive copies, which costs the link about
                     // 20 us per step; with two streams the next step's copy is already running.
-                    hipStream_t cs = ((l0 / layers_per_step) & 1) ? c->s_h2d2 : c->s_h2d;
+                    hipStream_t cs = (two_copy_streams && ((l0 / layers_per_step) & 1)) ? c->s_h2d2 : c->s_h2d;
                     for (int64_t i0 = 0; i0 < n_chunks; i0 += cap)
                         if ((rc = load_group(view, uint64_t(l0) * layer_bytes, i0, std::min(cap, n_chunks - i0), cs, nullptr)) != LMC_OK)
                             return rc;
@@ -911,8 +946,142 @@ lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks,
     c->stats.chunks_retrieved += uint64_t(n_chunks);
     // bulk: the caller's stream continues when everything is in place; layer-wise: the
     // caller orders its streams per layer with lmc_wait_layer
-    if (!layerwise) HIPCHK(c, hipStreamWaitEvent(user, c->ops.back().done, 0));
+    if (!layerwise && c->caller_waits) HIPCHK(c, hipStreamWaitEvent(user, c->ops.back().done, 0));
     return LMC_OK;
+}
+
+// Does work on stream `other` stand still while a copy runs on `busy`?  HIP maps streams
+// onto a few hardware queues and a queue runs its entries in order, so two streams of one
+// queue do not overlap.  A copy of `nbytes` that only reads the pool is enqueued on `busy`
+// (with by_kernel: the link-paced copy kernel, what direct mode runs on the kernel streams)
+// and right behind it, on `other`, a small kernel that depends on nothing; *shares says
+// whether that kernel finished only with the copy.  Two passes, the first warms up.
+lmc_status_t shares_a_queue(lmc_ctx *c, hipStream_t busy, bool by_kernel, hipStream_t other, uint8_t *devbuf,
+                            uint64_t nbytes, hipEvent_t a0, hipEvent_t a1, hipEvent_t k1, bool *shares) {
+    float t_copy = 0.f, t_kernel = 0.f;
+    for (int pass = 0; pass < 2; pass++) {
+        const hipError_t steps[] = {
+            hipEventRecord(a0, busy),
+            by_kernel ? lmc::launch_copy_rect(devbuf, nbytes, c->pool_dev, nbytes, nbytes, 1,
+                                              c->link_groups ? c->link_groups : 64u, busy)
+                      : hipMemcpyAsync(devbuf, c->pool, nbytes, hipMemcpyHostToDevice, busy),
+            hipEventRecord(a1, busy),
+            lmc::launch_fill(devbuf + nbytes, 0, 256, other),
+            hipEventRecord(k1, other),
+            hipEventSynchronize(a1),
+            hipEventSynchronize(k1),
+            hipEventElapsedTime(&t_copy, a0, a1),
+            hipEventElapsedTime(&t_kernel, a0, k1),
+        };
+        for (hipError_t x : steps)
+            if (x != hipSuccess) {
+                c->last_hip_error = int32_t(x);
+                (void)hipGetLastError();
+                return LMC_ERR_HIP;
+            }
+    }
+    *shares = t_kernel > 0.5f * t_copy;
+    return LMC_OK;
+}
+
+// Puts the library's six streams on hardware queues of its choosing.  HIP gives every
+// stream one of a few hardware queues when the stream is created (four by default, the
+// least used one first) and a queue runs its entries in order: a stream stands still not
+// only while a copy of a queue-mate runs but also while a queue-mate *waits* for an event,
+// so a scatter launch waiting for its group's copy holds up a gather behind it.  Left as
+// created, which streams share is a matter of how many streams the process made before;
+// measured on the 10 GiB request with a store and a retrieve running together: 63, 72 or
+// 100 GB/s summed, by arrangement alone.  The plan: the two kernel streams and the first
+// copy stream of each direction on four different queues, so that the four streams of a
+// full-duplex transfer never wait for each other.  The second host-to-device copy stream
+// must not sit behind the first (layer-wise retrieves alternate between them so that one
+// step's copy starts while the other's is being retired: on one queue that gains nothing,
+// 52.7 instead of 56.2 GB/s at four layers a step) nor behind the scatter stream (whose
+// waits would hold it up), so it joins the first device-to-host copy stream; the second
+// device-to-host stream (fragmented stores only, where sharing costs nothing) joins it
+// too.  other_direction_busy() keeps the second streams out of a two-way transfer.  With
+// fewer queues a kernel stream joins the first copy stream of the other direction; with six
+// or more every stream has its own.  Streams are told apart by shares_a_queue(); candidates
+// are created until the plan can be met (at most 16, the unused ones are destroyed); if it
+// cannot be, or anything fails, the streams stay as created.  Streams of the caller are the
+// caller's to place: lmc_probe_stream.  Needs an idle context.
+void arrange_streams(lmc_ctx *c) {
+    // scratch: a staging buffer of the store ring, which nothing is using (no allocation here)
+    if (c->store_ring.buf.empty() || c->store_ring.buf_bytes < 512) return;
+    const uint64_t pool_bytes = uint64_t(c->n_pool_slots) * uint64_t(c->chunk_bytes);
+    const uint64_t nbytes =
+        std::min({uint64_t(32) << 20, pool_bytes, c->store_ring.buf_bytes - 256}) / 256 * 256;
+    if (nbytes < (uint64_t(8) << 20)) return;   // too short a copy to tell waiting from running
+    uint8_t *devbuf = c->store_ring.buf[0];
+    hipEvent_t a0 = nullptr, a1 = nullptr, k1 = nullptr;
+    // roles in the order in which they get a queue of their own while queues last
+    hipStream_t *const role[6] = {&c->s_h2d, &c->s_d2h, &c->s_scatter, &c->s_gather, &c->s_h2d2, &c->s_d2h2};
+    const int partner[6] = {0, 1, 1, 0, 3, 2};   // whose queue to join when none is left
+    std::vector<hipStream_t> cand;
+    for (hipStream_t *r : role) cand.push_back(*r);
+    std::vector<int> queue_of;        // per candidate: number of its hardware queue, as found
+    std::vector<size_t> first_in;     // per queue found: its first candidate
+    int pick[6] = {0, 1, 2, 3, 4, 5};
+    bool ok = get_event(c, true, &a0) == LMC_OK && get_event(c, true, &a1) == LMC_OK && get_event(c, true, &k1) == LMC_OK;
+    bool met = false;
+    while (ok && !met) {
+        // place the candidates not yet placed
+        while (ok && queue_of.size() < cand.size()) {
+            const size_t i = queue_of.size();
+            int q = -1;
+            for (size_t k = 0; ok && q < 0 && k < first_in.size(); k++) {
+                bool shares = false;
+                ok = shares_a_queue(c, cand[first_in[k]], false, cand[i], devbuf, nbytes, a0, a1, k1, &shares) == LMC_OK;
+                if (shares) q = int(k);
+            }
+            if (q < 0) {
+                q = int(first_in.size());
+                first_in.push_back(i);
+            }
+            queue_of.push_back(q);
+        }
+        if (!ok) break;
+        // try the plan with what there is
+        std::vector<char> taken(cand.size(), 0);
+        int role_queue[6], next_queue = 0;
+        met = true;
+        for (int r = 0; r < 6 && met; r++) {
+            const int want = next_queue < int(first_in.size()) ? next_queue++ : role_queue[partner[r]];
+            role_queue[r] = want;
+            met = false;
+            for (size_t i = 0; i < cand.size() && !met; i++)
+                if (!taken[i] && queue_of[i] == want) {
+                    taken[i] = 1;
+                    pick[r] = int(i);
+                    met = true;
+                }
+        }
+        // A queue that other streams of the process use much is handed out last: with fewer
+        // than six queues seen, look at a dozen streams before believing the count.
+        if (met && first_in.size() < 6 && cand.size() < 12) met = false;
+        if (!met) {
+            hipStream_t fresh = nullptr;
+            if (cand.size() >= 16 || hipStreamCreateWithFlags(&fresh, hipStreamNonBlocking) != hipSuccess) break;
+            cand.push_back(fresh);
+        }
+    }
+    (void)hipDeviceSynchronize();
+    std::vector<char> keep(cand.size(), 0);
+    if (ok && met) {
+        hipStream_t chosen[6];
+        for (int r = 0; r < 6; r++) chosen[r] = cand[size_t(pick[r])];
+        for (int r = 0; r < 6; r++) {
+            *role[r] = chosen[r];
+            keep[size_t(pick[r])] = 1;
+        }
+    } else {
+        for (size_t i = 0; i < 6; i++) keep[i] = 1;
+    }
+    for (size_t i = 0; i < cand.size(); i++)
+        if (!keep[i]) (void)hipStreamDestroy(cand[i]);
+    for (hipEvent_t ev : {a0, a1, k1})
+        if (ev) c->free_time_events.push_back(ev);
+    (void)hipGetLastError();
 }
 
 void destroy_ctx(lmc_ctx *c) {
@@ -1014,6 +1183,7 @@ lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out) {
         }
         if ((rc = make_ring(c, c->store_ring)) != LMC_OK) return fail(rc);
         if ((rc = make_ring(c, c->load_ring)) != LMC_OK) return fail(rc);
+        if (!(cfg->flags & LMC_FLAG_KEEP_STREAMS)) arrange_streams(c);
     }
     c->index.reset(c->n_pool_slots);
     c->stats.pool_slots_total = uint64_t(c->n_pool_slots);
@@ -1152,6 +1322,7 @@ static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64
         return LMC_OK;
     }
     const size_t per = size_t(cap_chunks);
+    const bool two_copy_streams = !other_direction_busy(c, true);
     for (size_t j0 = 0; j0 < new_chunk.size();) {
         // one launch covers chunks that are consecutive in the caller's slot mapping.
         // Only the first gather is exposed (later ones hide behind the previous copy),
@@ -1169,7 +1340,7 @@ static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64
         HIPCHK(c, hipEventRecord(ring.filled[b], c->s_gather));
         if ((rc = force_sync(c, c->s_gather)) != LMC_OK) return rc;
         HIPCHK(c, hipStreamWaitEvent(c->s_d2h, ring.filled[b], 0));
-        hipStream_t second = several_runs(&new_slot[j0], int64_t(k)) ? c->s_d2h2 : nullptr;
+        hipStream_t second = (two_copy_streams && several_runs(&new_slot[j0], int64_t(k))) ? c->s_d2h2 : nullptr;
         if (second) HIPCHK(c, hipStreamWaitEvent(second, ring.filled[b], 0));
         bool used_second = false;
         rc = copy_group(c, true, buf, view.chunk_stride, &new_slot[j0], int64_t(k), pool_off,
@@ -1201,7 +1372,7 @@ lmc_status_t lmc_store(lmc_ctx_t *c, void *const *kv_layers, const int64_t *slot
     if (rc != LMC_OK) return rc;
     hipStream_t user = static_cast<hipStream_t>(stream_to_wait_on);
     const int64_t CT = c->cfg.geom.chunk_tokens;
-    if (n_chunks > 0 && (rc = order_after(c, c->s_gather, user)) != LMC_OK) return rc;
+    if (n_chunks > 0 && (rc = order_after_caller(c, c->s_gather, user)) != LMC_OK) return rc;
     if ((rc = validate_slots(c, slot_mapping, n_chunks * CT, c->s_gather)) != LMC_OK) return rc;
 
     Op op;
@@ -1234,7 +1405,7 @@ lmc_status_t lmc_store_begin(lmc_ctx_t *c, const int64_t *slot_mapping, const ui
     lmc_status_t rc;
     hipStream_t user = static_cast<hipStream_t>(stream_to_wait_on);
     const int64_t CT = c->cfg.geom.chunk_tokens;
-    if (n_chunks > 0 && (rc = order_after(c, c->s_gather, user)) != LMC_OK) return rc;
+    if (n_chunks > 0 && (rc = order_after_caller(c, c->s_gather, user)) != LMC_OK) return rc;
     if ((rc = validate_slots(c, slot_mapping, n_chunks * CT, c->s_gather)) != LMC_OK) return rc;
     Op op;
     op.ticket = c->next_ticket++;
@@ -1276,7 +1447,7 @@ lmc_status_t lmc_store_layers(lmc_ctx_t *c, uint64_t ticket, int32_t first_layer
     const bool direct = (c->cfg.flags & LMC_FLAG_DIRECT) != 0;
     hipStream_t last = direct ? c->s_gather : c->s_d2h;
     // this layer's KV was produced by work already on the caller's stream
-    rc = order_after(c, c->s_gather, static_cast<hipStream_t>(stream_to_wait_on));
+    rc = order_after_caller(c, c->s_gather, static_cast<hipStream_t>(stream_to_wait_on));
     if (rc == LMC_OK && !direct)
         rc = ring_reslot(c, c->store_ring, (uint64_t(cap) * view.chunk_stride + 255) / 256 * 256, c->s_gather, c->s_d2h);
     if (rc == LMC_OK)
@@ -1770,32 +1941,10 @@ lmc_status_t lmc_probe_stream(lmc_ctx_t *c, void *stream, uint32_t *mask_out) {
     const hipStream_t copy_streams[6] = {c->s_h2d, c->s_h2d2, c->s_d2h, c->s_d2h2, c->s_gather, c->s_scatter};
     uint32_t mask = 0;
     for (int i = 0; i < 6 && rc == LMC_OK; i++) {
-        float t_copy = 0.f, t_kernel = 0.f;
-        for (int pass = 0; pass < 2 && rc == LMC_OK; pass++) {  // the first pass warms up
-            // a copy that only reads the pool, and right behind it, on the caller's stream,
-            // a kernel that depends on nothing: does it have to wait for the copy?
-            const hipError_t steps[] = {
-                hipEventRecord(a0, copy_streams[i]),
-                // (on the two kernel streams: the link-paced kernel that direct mode runs there)
-                i < 4 ? hipMemcpyAsync(devbuf, c->pool, nbytes, hipMemcpyHostToDevice, copy_streams[i])
-                      : lmc::launch_copy_rect(devbuf, nbytes, c->pool_dev, nbytes, nbytes, 1,
-                                              c->link_groups ? c->link_groups : 64u, copy_streams[i]),
-                hipEventRecord(a1, copy_streams[i]),
-                lmc::launch_fill(devbuf + nbytes, 0, 256, user),
-                hipEventRecord(k1, user),
-                hipEventSynchronize(a1),
-                hipEventSynchronize(k1),
-                hipEventElapsedTime(&t_copy, a0, a1),
-                hipEventElapsedTime(&t_kernel, a0, k1),
-            };
-            for (hipError_t x : steps)
-                if (x != hipSuccess) {
-                    c->last_hip_error = int32_t(x);
-                    (void)hipGetLastError();
-                    rc = LMC_ERR_HIP;
-                }
-        }
-        if (rc == LMC_OK && t_kernel > 0.5f * t_copy) mask |= 1u << i;
+        // on the two kernel streams: the link-paced kernel that direct mode runs there
+        bool shares = false;
+        rc = shares_a_queue(c, copy_streams[i], i >= 4, user, devbuf, nbytes, a0, a1, k1, &shares);
+        if (rc == LMC_OK && shares) mask |= 1u << i;
     }
     for (hipEvent_t ev : {a0, a1, k1})
         if (ev) c->free_time_events.push_back(ev);
@@ -1807,8 +1956,12 @@ lmc_status_t lmc_probe_stream(lmc_ctx_t *c, void *stream, uint32_t *mask_out) {
 
 static lmc_status_t measure_duplex(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, uint32_t by_kernel,
                                    double *gbps_out) {
+    // bits 0-1: which direction the copy kernel makes; bits 8-15: in how many consecutive
+    // pieces each direction moves its bytes (0 = 1), as the pipelines do group by group
+    const uint32_t pieces = std::max<uint32_t>(1u, (by_kernel >> 8) & 0xFFu);
+    by_kernel &= ~0xFF00u;
     if (!c || !gbps_out || reps < 1 || nbytes == 0 || by_kernel > 3) return LMC_ERR_INVAL;
-    if (by_kernel != 0 && (nbytes % 16) != 0) return LMC_ERR_INVAL;
+    if (nbytes % (uint64_t(pieces) * 16) != 0) return LMC_ERR_INVAL;
     if (!c->has_device) return LMC_ERR_NODEVICE;
     if (2 * nbytes > uint64_t(c->n_pool_slots) * uint64_t(c->chunk_bytes)) return LMC_ERR_INVAL;
     std::lock_guard<std::mutex> lock(c->mu);
@@ -1840,10 +1993,13 @@ static lmc_status_t measure_duplex(lmc_ctx_t *c, uint64_t nbytes, int32_t reps, 
         ok(hipEventRecord(e0, c->s_h2d));
         ok(hipStreamWaitEvent(c->s_d2h, e0, 0));           // both directions start together
         const uint32_t groups = c->link_groups ? c->link_groups : 64u;
-        ok((by_kernel & 1u) ? lmc::launch_copy_rect(up, nbytes, c->pool_dev, nbytes, nbytes, 1, groups, c->s_h2d)
-                            : hipMemcpyAsync(up, c->pool, nbytes, hipMemcpyHostToDevice, c->s_h2d));
-        ok((by_kernel & 2u) ? lmc::launch_copy_rect(c->pool_dev + nbytes, nbytes, down, nbytes, nbytes, 1, groups, c->s_d2h)
-                            : hipMemcpyAsync(c->pool + nbytes, down, nbytes, hipMemcpyDeviceToHost, c->s_d2h));
+        const uint64_t piece = nbytes / pieces;
+        for (uint64_t o = 0; o < nbytes; o += piece) {
+            ok((by_kernel & 1u) ? lmc::launch_copy_rect(up + o, piece, c->pool_dev + o, piece, piece, 1, groups, c->s_h2d)
+                                : hipMemcpyAsync(up + o, c->pool + o, piece, hipMemcpyHostToDevice, c->s_h2d));
+            ok((by_kernel & 2u) ? lmc::launch_copy_rect(c->pool_dev + nbytes + o, piece, down + o, piece, piece, 1, groups, c->s_d2h)
+                                : hipMemcpyAsync(c->pool + nbytes + o, down + o, piece, hipMemcpyDeviceToHost, c->s_d2h));
+        }
         ok(hipEventRecord(e1, c->s_d2h));
         ok(hipStreamWaitEvent(c->s_h2d, e1, 0));
         ok(hipEventRecord(e2, c->s_h2d));                  // after both
@@ -1911,6 +2067,8 @@ lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
         c->shape.xcd_run = uint32_t(value);
     } else if (k == "d2h_guard" && value <= 1) {
         c->d2h_guard_on = value != 0;
+    } else if (k == "caller_waits" && value <= 1) {
+        c->caller_waits = value != 0;
     } else if (k == "copy_kernel" && value <= 3) {
         c->copy_kernel = uint32_t(value);
     } else if (k == "link_groups") {
@@ -1924,6 +2082,11 @@ lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
         c->ordered_min_pages = value;
     } else if (k == "ordered_min_density_inv" && value >= 1) {
         c->ordered_min_density_inv = value;
+    } else if (k == "arrange_streams" && value == 1) {
+        if (!c->has_device) return LMC_ERR_NODEVICE;
+        if (!c->ops.empty() || !c->held_events.empty()) return LMC_ERR_BUSY;
+        DeviceScope dev(c);
+        arrange_streams(c);
     } else if (k == "fail_hip_after") {
         if (value > 0xFFFFFFFFll) return LMC_ERR_INVAL;
         c->fail_hip_after = uint32_t(value);

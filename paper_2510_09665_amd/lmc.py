@@ -21,6 +21,7 @@ LMC_DEVICE_NONE = -1
 LMC_FLAG_VALIDATE_SLOTS, LMC_FLAG_FORCE_SYNC, LMC_FLAG_POISON_STAGING, LMC_FLAG_TIMING = 1, 2, 4, 8
 LMC_FLAG_DIRECT = 16
 LMC_FLAG_EVICT_LRU = 32
+LMC_FLAG_KEEP_STREAMS = 64
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblmc.so")
 
