@@ -757,6 +757,25 @@ def mode_legs(torch, lmc, W, dev, stream, legs, args, timed, peaks):
                       "retrieve_gbps": round(payload_one_way / tf_l / 1e9, 2),
                       "store_frac_of_d2h_peak": round(payload_one_way / tf_s / 1e9 / d2h, 4),
                       "retrieve_frac_of_h2d_peak": round(payload_one_way / tf_l / 1e9 / h2d, 4)}
+
+        # layer by layer on the same pool: one 1 MiB piece per chunk and layer; all pieces of
+        # a step go in one launch of the library's copy kernel ("runtime_copies": one
+        # hipMemcpyAsync per piece instead)
+        def f_lw_store():
+            fctx.clear(fids)
+            t = fctx.store_begin(d_store, fids, stream)
+            for l0 in range(g.L):
+                fctx.store_layers(t, l0, 1, src, stream)
+            fctx.wait(t)
+        for key, below in (("layer_by_layer", None), ("layer_by_layer_runtime_copies", 0)):
+            if below is not None:
+                fctx.tune("pieces_by_kernel_below", below)
+            ts_ = timed(f_lw_store)
+            tl_ = timed(lambda: fctx.wait(fctx.retrieve_layerwise(fids, d_load, dst, 1, stream)))
+            fragmented[key] = {"store_gbps": round(payload_one_way / ts_ / 1e9, 2),
+                               "retrieve_gbps": round(payload_one_way / tl_ / 1e9, 2),
+                               "store_frac_of_d2h_peak": round(payload_one_way / ts_ / 1e9 / d2h, 4),
+                               "retrieve_frac_of_h2d_peak": round(payload_one_way / tl_ / 1e9 / h2d, 4)}
         fctx.destroy()
 
 

@@ -565,7 +565,11 @@ lmc_status_t lmc_probe_stream(lmc_ctx_t *ctx, void *stream, uint32_t *mask_out);
  * pages that cover at least one block in "ordered_min_density_inv" of a plane, 2 = every
  * launch; "ordered_group_rows": rows per group, 0 = plane by plane.  Same bytes; on MI355X
  * it measured slower than the plain order at every density, see the benchmark's
- * page_placement figures), "caller_waits" (default 1: an lmc_retrieve / lmc_retrieve_batch
+ * page_placement figures), "pieces_by_kernel_below" (bytes, default 2 MiB: a group whose
+ * chunks lie in several runs of pool slots and whose transfers would average at most that
+ * many bytes, i.e. a layer-wise step on a fragmented pool, is copied between staging and
+ * pool by one launch of the library's copy kernel instead of one small runtime copy per
+ * run; 0 = never), "caller_waits" (default 1: an lmc_retrieve / lmc_retrieve_batch
  * ends by making the caller's stream wait for it; 0: it does not, and the caller orders its
  * work after the ticket itself with lmc_wait.  A wait that stands at the head of an
  * otherwise idle hardware queue for the length of a large retrieve cost that retrieve

@@ -120,6 +120,7 @@ struct lmc_ctx {
     // it holds the copies on the copy kernel (55.7 GB/s) for seconds although the runtime's
     // were back at 56.8 after one store.  Steady state is the same either way.
     bool d2h_guard_on = false;
+    uint64_t pieces_by_kernel_below = uint64_t(2) << 20;   // bytes per transfer; see copy_group
     bool caller_waits = true;     // a bulk retrieve ends with the caller's stream waiting for it
     lmc::CopyEngineGuard d2h_guard;
     std::vector<CopyTiming> copy_timings;
@@ -549,6 +550,29 @@ lmc_status_t copy_group(lmc_ctx *c, bool to_host, uint8_t *staging, uint64_t str
     const uint64_t cb = uint64_t(c->chunk_bytes);
     const hipMemcpyKind kind = to_host ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice;
     if (used_second) *used_second = false;
+    // Many small pieces (a fragmented pool in layer-wise mode: one piece per chunk and step,
+    // 1 MiB for one Llama layer): the runtime pays a fixed price per copy that a piece this
+    // small does not cover (stores of 1 MiB pieces ran at 27-36 GB/s), so all pieces of the
+    // group go in one launch of the library's copy kernel, which is told the slots.
+    if (c->pool_dev != nullptr && k > 1 && width <= c->pieces_by_kernel_below &&
+        ((width | stride | cb | pool_off | reinterpret_cast<uintptr_t>(staging)) % 16) == 0 &&
+        c->n_pool_slots <= int64_t(INT32_MAX)) {
+        int64_t runs = 1;
+        for (int64_t j = 1; j < k; j++) runs += pool_slots[j] != pool_slots[j - 1] + 1;
+        if (uint64_t(k) * width <= uint64_t(runs) * c->pieces_by_kernel_below && runs > 1) {
+            const uint32_t groups = c->link_groups ? c->link_groups : 64u;
+            for (int64_t j = 0; j < k; j += lmc::kMaxPieces) {
+                const int64_t m = std::min<int64_t>(lmc::kMaxPieces, k - j);
+                lmc::PieceSlots table;
+                for (int64_t i = 0; i < m; i++) table.slot[i] = int32_t(pool_slots[j + i]);
+                HIPCHK(c, lmc::launch_copy_pieces(c->pool_dev + pool_off, cb, staging + uint64_t(j) * stride, stride,
+                                                  width, table, uint32_t(m), to_host, groups, first));
+            }
+            if (to_host) c->stats.bytes_d2h += uint64_t(k) * width;
+            else c->stats.bytes_h2d += uint64_t(k) * width;
+            return LMC_OK;
+        }
+    }
     bool watched = false;
     int64_t run = 0;
     for (int64_t j = 0; j < k; run++) {
@@ -2067,6 +2091,8 @@ lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
         c->shape.xcd_run = uint32_t(value);
     } else if (k == "d2h_guard" && value <= 1) {
         c->d2h_guard_on = value != 0;
+    } else if (k == "pieces_by_kernel_below") {
+        c->pieces_by_kernel_below = uint64_t(value);
     } else if (k == "caller_waits" && value <= 1) {
         c->caller_waits = value != 0;
     } else if (k == "copy_kernel" && value <= 3) {

@@ -396,6 +396,29 @@ __global__ __launch_bounds__(kThreads) void copy_rect_paced(uint8_t *__restrict_
     }
 }
 
+// The same for pieces that lie in pool slots of any numbers (a fragmented pool): the row
+// on the pool's side starts at slot[row] * pool_pitch.  One launch for all the pieces of a
+// pipeline step, where the runtime would make one small copy per piece.
+template <bool TO_POOL>
+__global__ __launch_bounds__(kThreads) void copy_pieces_paced(uint8_t *__restrict__ pool, uint64_t pool_pitch,
+                                                              uint8_t *__restrict__ staging, uint64_t stage_pitch,
+                                                              uint64_t width_vec, FastDiv by_tiles_per_row,
+                                                              uint32_t n_tiles, PieceSlots slots) {
+    const uint64_t pool_at = pin(uint64_t(pool)), stage_at = pin(uint64_t(staging));
+    const uint64_t pp = pin(pool_pitch), sp = pin(stage_pitch), wv = pin(width_vec);
+    const FastDiv by_tpr = pin(by_tiles_per_row);
+    const uint32_t step = pin(uint32_t(gridDim.x)), end = pin(n_tiles);
+    for (uint32_t t = blockIdx.x; t < end; t += step) {
+        const uint32_t row = by_tpr.div(t);
+        const uint64_t v = uint64_t(t - row * by_tpr.d) * kThreads + threadIdx.x;
+        if (v >= wv) continue;
+        const uint64_t in_pool = pool_at + uint64_t(uint32_t(slots.slot[row])) * pp + v * 16u;
+        const uint64_t in_stage = stage_at + uint64_t(row) * sp + v * 16u;
+        const u32x4 x = load_vec<u32x4, true>(TO_POOL ? in_stage : in_pool);
+        store_vec<u32x4, true>(TO_POOL ? in_pool : in_stage, x);
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void fill_bytes(uint8_t *dst, uint8_t value, uint64_t n) {
     const uint64_t step = uint64_t(gridDim.x) * kThreads;
     for (uint64_t i = uint64_t(blockIdx.x) * kThreads + threadIdx.x; i < n; i += step)
@@ -635,6 +658,31 @@ hipError_t launch_copy_rect(uint8_t *dst, uint64_t dst_pitch, const uint8_t *src
                            dst + r0 * dst_pitch, dst_pitch, src + r0 * src_pitch, src_pitch, width_vec,
                            make_fastdiv(uint32_t(tiles_per_row)), n_tiles);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_pieces(uint8_t *pool, uint64_t pool_pitch, uint8_t *staging, uint64_t stage_pitch,
+                              uint64_t width, const PieceSlots &slots, uint32_t n_pieces, bool to_pool,
+                              uint32_t groups, hipStream_t stream) {
+    if (width == 0 || n_pieces == 0) return hipSuccess;
+    if ((width % 16) != 0 || (pool_pitch % 16) != 0 || (stage_pitch % 16) != 0 || groups == 0 ||
+        n_pieces > uint32_t(kMaxPieces) || (reinterpret_cast<uintptr_t>(pool) % 16) != 0 ||
+        (reinterpret_cast<uintptr_t>(staging) % 16) != 0)
+        return hipErrorInvalidValue;
+    for (uint32_t i = 0; i < n_pieces; i++)
+        if (slots.slot[i] < 0) return hipErrorInvalidValue;
+    const uint64_t width_vec = width / 16;
+    const uint64_t tiles_per_row = (width_vec + kThreads - 1) / kThreads;
+    // the tile index is 32-bit and stays below 2^24, so t + grid never wraps and FastDiv is exact
+    if (tiles_per_row * n_pieces >= (uint64_t(1) << 24)) return hipErrorInvalidValue;
+    const uint32_t n_tiles = uint32_t(tiles_per_row * n_pieces);
+    const dim3 grid(std::min(n_tiles, groups)), block(kThreads);
+    if (to_pool)
+        hipLaunchKernelGGL(copy_pieces_paced<true>, grid, block, 0, stream, pool, pool_pitch, staging, stage_pitch,
+                           width_vec, make_fastdiv(uint32_t(tiles_per_row)), n_tiles, slots);
+    else
+        hipLaunchKernelGGL(copy_pieces_paced<false>, grid, block, 0, stream, pool, pool_pitch, staging, stage_pitch,
+                           width_vec, make_fastdiv(uint32_t(tiles_per_row)), n_tiles, slots);
     return hipGetLastError();
 }
 

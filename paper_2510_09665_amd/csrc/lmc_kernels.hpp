@@ -121,6 +121,18 @@ hipError_t launch_copy_tiles(uint8_t *dst, const uint32_t *dst_order, const uint
 // Everything must be a multiple of 16 bytes, else hipErrorInvalidValue.
 hipError_t launch_copy_rect(uint8_t *dst, uint64_t dst_pitch, const uint8_t *src, uint64_t src_pitch,
                             uint64_t width, uint64_t rows, uint32_t groups, hipStream_t stream);
+// Pool slots of the pieces of one copy_pieces launch, by value like LayerPtrs.
+constexpr int kMaxPieces = 256;
+struct PieceSlots {
+    int32_t slot[kMaxPieces];
+};
+// n_pieces (<= kMaxPieces) pieces of `width` bytes in one launch of the link-paced copy
+// kernel: piece i lies at staging + i * stage_pitch and at pool + slot[i] * pool_pitch
+// (pool already offset to where a piece starts inside its slot).  to_pool: staging ->
+// pool, else pool -> staging.  Everything a multiple of 16 bytes.
+hipError_t launch_copy_pieces(uint8_t *pool, uint64_t pool_pitch, uint8_t *staging, uint64_t stage_pitch,
+                              uint64_t width, const PieceSlots &slots, uint32_t n_pieces, bool to_pool,
+                              uint32_t groups, hipStream_t stream);
 hipError_t launch_fill(uint8_t *dst, uint8_t value, uint64_t nbytes, hipStream_t stream);
 
 // largest number of chunks one launch may cover (32-bit workgroup index)

@@ -24,6 +24,10 @@ CASES = {
     "all_layers_in_one_step": ("tiny", {}, 256, 1, 99, 0),
     "direct_llama_k1": ("llama3_8b", dict(L=8, NB=1024), 10 * 256, 1, 1, "direct"),
     "direct_mla_k3": ("mla_bf16", dict(L=7), 4 * 256, 1, 3, "direct"),
+    # every other pool slot taken: one small piece per chunk and step, copied by one kernel launch per group
+    "fragmented_pool_k1": ("llama3_8b", dict(L=8, NB=1024), 10 * 256, 4, 1, "frag"),
+    "fragmented_pool_mla_k3": ("mla_fp8", dict(L=9), 6 * 256, 3, 3, "frag"),
+    "fragmented_pool_runtime_copies_k1": ("llama3_8b", dict(L=8, NB=1024), 10 * 256, 4, 1, "frag_runtime"),
     "ordered_scatter_k2": ("llama3_8b", dict(L=6, NB=512), 8 * 256, 2, 2, "ordered"),   # layer views, rows in slot order
 }
 
@@ -40,7 +44,17 @@ def _setup(case):
     f = {"poison": lmc.LMC_FLAG_POISON_STAGING, "direct": lmc.LMC_FLAG_DIRECT,
          "kcopy": lmc.LMC_FLAG_POISON_STAGING}.get(flags, 0)
     n_chunks = n_tok // g.CT
-    ctx = lmc.Context(g, n_chunks * g.chunk_bytes, staging_chunks=staging, flags=f | lmc.LMC_FLAG_TIMING)
+    frag = flags in ("frag", "frag_runtime")
+    ctx = lmc.Context(g, ((2 * n_chunks + 1) if frag else n_chunks) * g.chunk_bytes, staging_chunks=staging,
+                      flags=f | lmc.LMC_FLAG_TIMING)
+    if frag:
+        filler = np.arange(1, 2 * n_chunks + 1, dtype=np.uint64) + np.uint64(1 << 40)
+        zero = np.zeros(g.chunk_bytes, dtype=np.uint8)
+        for x in filler:
+            ctx.put_host([x], zero)
+        ctx.clear(filler[1::2])
+        if flags == "frag_runtime":
+            ctx.tune("pieces_by_kernel_below", 0)
     ctx.tune("direct_store_below", 0)       # the bulk stores and retrieves beside the layer-wise
     ctx.tune("direct_retrieve_below", 0)    # calls go through staging whatever their size
     if flags == "kcopy":
@@ -126,7 +140,8 @@ def _status(fn):
 
 
 @pytest.mark.parametrize("case", ["tiny_k1", "llama8b_k5_ragged", "many_groups_per_layer", "mla_fp8_k3", "hnd_k2",
-                                  "direct_llama_k1", "direct_mla_k3"])
+                                  "direct_llama_k1", "direct_mla_k3", "fragmented_pool_k1", "fragmented_pool_mla_k3",
+                                  "fragmented_pool_runtime_copies_k1"])
 def test_layerwise_store_matches_oracle(case):
     """The 'engine' writes layer l's KV on its stream and submits the layer at once; the
     pool must end up holding exactly the oracle's chunks."""
