@@ -569,7 +569,9 @@ lmc_status_t lmc_probe_stream(lmc_ctx_t *ctx, void *stream, uint32_t *mask_out);
  * chunks lie in several runs of pool slots and whose transfers would average at most that
  * many bytes, i.e. a layer-wise step on a fragmented pool, is copied between staging and
  * pool by one launch of the library's copy kernel instead of one small runtime copy per
- * run; 0 = never), "caller_waits" (default 1: an lmc_retrieve / lmc_retrieve_batch
+ * run; 0 = never), "store_step_streams" (default 2: consecutive lmc_store_layers calls of
+ * a ticket put their copies on the two device-to-host copy streams in turn; 1: on one),
+ * "caller_waits" (default 1: an lmc_retrieve / lmc_retrieve_batch
  * ends by making the caller's stream wait for it; 0: it does not, and the caller orders its
  * work after the ticket itself with lmc_wait.  A wait that stands at the head of an
  * otherwise idle hardware queue for the length of a large retrieve cost that retrieve

@@ -81,6 +81,8 @@ struct Op {
     bool layerwise = false;
     bool pending = false;                 // a store whose layers have not all been submitted
     int32_t next_layer = 0;               // first layer not yet submitted
+    int32_t steps = 0;                    // pending store: lmc_store_layers calls served so far
+    bool both_copy_streams = false;       // pending store: steps went to the two copy streams in turn
     std::vector<int64_t> new_chunk;       // pending store: chunk numbers that are new
     const int64_t *slot_mapping = nullptr;  // pending store: the caller's slot mapping
     std::vector<hipEvent_t> layer_done;   // per layer: event after which the layer is in place
@@ -121,6 +123,7 @@ struct lmc_ctx {
     // were back at 56.8 after one store.  Steady state is the same either way.
     bool d2h_guard_on = false;
     uint64_t pieces_by_kernel_below = uint64_t(2) << 20;   // bytes per transfer; see copy_group
+    int32_t store_step_streams = 2;   // copy streams the steps of a layer-wise store take in turn
     bool caller_waits = true;     // a bulk retrieve ends with the caller's stream waiting for it
     lmc::CopyEngineGuard d2h_guard;
     std::vector<CopyTiming> copy_timings;
@@ -401,7 +404,7 @@ lmc_status_t order_after_caller(lmc_ctx *c, hipStream_t waiter, hipStream_t user
 // copies up, so it is left out then.
 bool other_direction_busy(lmc_ctx *c, bool for_store) {
     for (const Op &o : c->ops) {
-        const bool is_store = o.pending || o.final_stream == c->s_d2h || o.final_stream == c->s_gather;
+        const bool is_store = o.pending || o.final_stream == c->s_d2h || o.final_stream == c->s_d2h2 || o.final_stream == c->s_gather;
         if (is_store == for_store) continue;
         if (o.pending) return true;
         if (o.done != nullptr && hipEventQuery(o.done) != hipSuccess) {
@@ -695,11 +698,12 @@ lmc_status_t make_ring(lmc_ctx *c, Ring &r) {
 // first waits for everything the consumer stream has been given, so no slot of the old
 // division is still being read when the new division is written.
 lmc_status_t ring_reslot(lmc_ctx *c, Ring &r, uint64_t slot_bytes, hipStream_t producer,
-                         hipStream_t consumer, hipStream_t producer2 = nullptr) {
+                         hipStream_t consumer, hipStream_t producer2 = nullptr, hipStream_t consumer2 = nullptr) {
     if (slot_bytes == r.slot_bytes) return LMC_OK;
     if (r.slot_bytes != 0) {
         lmc_status_t rc = order_after(c, producer, consumer);
         if (rc == LMC_OK && producer2 != nullptr) rc = order_after(c, producer2, consumer);
+        if (rc == LMC_OK && consumer2 != nullptr) rc = order_after(c, producer, consumer2);
         if (rc != LMC_OK) return rc;
     }
     // the new division takes effect only when its events exist: a failure on the way
@@ -1321,7 +1325,7 @@ static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64
                                  const lmc::LayerPtrs &ptrs, const int64_t *slot_mapping,
                                  const std::vector<int64_t> &new_chunk,
                                  const std::vector<int64_t> &new_slot, int64_t cap_chunks,
-                                 bool edge_group, bool direct) {
+                                 bool edge_group, bool direct, bool on_second_stream = false) {
     Ring &ring = c->store_ring;
     const int64_t CT = c->cfg.geom.chunk_tokens;
     if (direct) {
@@ -1347,6 +1351,7 @@ static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64
     }
     const size_t per = size_t(cap_chunks);
     const bool two_copy_streams = !other_direction_busy(c, true);
+    hipStream_t copies = on_second_stream ? c->s_d2h2 : c->s_d2h, other = on_second_stream ? c->s_d2h : c->s_d2h2;
     for (size_t j0 = 0; j0 < new_chunk.size();) {
         // one launch covers chunks that are consecutive in the caller's slot mapping.
         // Only the first gather is exposed (later ones hide behind the previous copy),
@@ -1363,20 +1368,20 @@ static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64
         if (rc != LMC_OK) return rc;
         HIPCHK(c, hipEventRecord(ring.filled[b], c->s_gather));
         if ((rc = force_sync(c, c->s_gather)) != LMC_OK) return rc;
-        HIPCHK(c, hipStreamWaitEvent(c->s_d2h, ring.filled[b], 0));
-        hipStream_t second = (two_copy_streams && several_runs(&new_slot[j0], int64_t(k))) ? c->s_d2h2 : nullptr;
+        HIPCHK(c, hipStreamWaitEvent(copies, ring.filled[b], 0));
+        hipStream_t second = (two_copy_streams && several_runs(&new_slot[j0], int64_t(k))) ? other : nullptr;
         if (second) HIPCHK(c, hipStreamWaitEvent(second, ring.filled[b], 0));
         bool used_second = false;
         rc = copy_group(c, true, buf, view.chunk_stride, &new_slot[j0], int64_t(k), pool_off,
-                        view.chunk_stride, c->s_d2h, second, &used_second);
+                        view.chunk_stride, copies, second, &used_second);
         if (rc != LMC_OK) return rc;
-        // the D2H stream stands for the whole group: it ends after the second stream's copies
-        if (used_second && (rc = order_after(c, c->s_d2h, second)) != LMC_OK) return rc;
+        // the group's copy stream stands for the whole group: it ends after the other stream's copies
+        if (used_second && (rc = order_after(c, copies, second)) != LMC_OK) return rc;
         if (c->cfg.flags & LMC_FLAG_POISON_STAGING)
-            HIPCHK(c, lmc::launch_fill(buf, 0xA5, uint64_t(k) * view.chunk_stride, c->s_d2h));
-        HIPCHK(c, hipEventRecord(ring.drained[b], c->s_d2h));
+            HIPCHK(c, lmc::launch_fill(buf, 0xA5, uint64_t(k) * view.chunk_stride, copies));
+        HIPCHK(c, hipEventRecord(ring.drained[b], copies));
         ring.used[b] = 1;
-        if ((rc = force_sync(c, c->s_d2h)) != LMC_OK) return rc;
+        if ((rc = force_sync(c, copies)) != LMC_OK) return rc;
         j0 += k;
     }
     return LMC_OK;
@@ -1406,7 +1411,7 @@ lmc_status_t lmc_store(lmc_ctx_t *c, void *const *kv_layers, const int64_t *slot
     c->stats.chunks_stored += new_chunk.size();
     const bool direct = (c->cfg.flags & LMC_FLAG_DIRECT) != 0 ||
                         int64_t(new_chunk.size()) * c->chunk_bytes <= c->direct_store_below;
-    rc = direct ? LMC_OK : ring_reslot(c, c->store_ring, c->store_ring.buf_bytes, c->s_gather, c->s_d2h);
+    rc = direct ? LMC_OK : ring_reslot(c, c->store_ring, c->store_ring.buf_bytes, c->s_gather, c->s_d2h, nullptr, c->s_d2h2);
     if (rc == LMC_OK)
         rc = store_groups(c, lmc::bulk_view(c->kg), 0, ptrs, slot_mapping, new_chunk, op.slots,
                           c->cfg.staging_chunks, true, direct);
@@ -1469,14 +1474,21 @@ lmc_status_t lmc_store_layers(lmc_ctx_t *c, uint64_t ticket, int32_t first_layer
     const uint64_t layer_bytes = uint64_t(geom.num_planes) * c->kg.plane_bytes;
     const int64_t cap = layer_group_chunks(c, c->store_ring, view, int64_t(op->new_chunk.size()));
     const bool direct = (c->cfg.flags & LMC_FLAG_DIRECT) != 0;
-    hipStream_t last = direct ? c->s_gather : c->s_d2h;
+    // Steps take the two copy streams in turn (as the steps of a layer-wise retrieve do):
+    // between two copies of one stream the runtime leaves the link idle for some 20 us,
+    // 7 % of a step of one Llama-3-8B layer, while on the other stream (another hardware
+    // queue, see arrange_streams) the next step's copy is ready to start.  Not while a
+    // retrieve is under way, whose kernels that stream would hold up.
+    const bool on_second = !direct && (op->steps & 1) != 0 && c->store_step_streams == 2 && !other_direction_busy(c, true);
+    hipStream_t last = direct ? c->s_gather : on_second ? c->s_d2h2 : c->s_d2h;
     // this layer's KV was produced by work already on the caller's stream
     rc = order_after_caller(c, c->s_gather, static_cast<hipStream_t>(stream_to_wait_on));
     if (rc == LMC_OK && !direct)
-        rc = ring_reslot(c, c->store_ring, (uint64_t(cap) * view.chunk_stride + 255) / 256 * 256, c->s_gather, c->s_d2h);
+        rc = ring_reslot(c, c->store_ring, (uint64_t(cap) * view.chunk_stride + 255) / 256 * 256, c->s_gather, c->s_d2h,
+                         nullptr, c->s_d2h2);
     if (rc == LMC_OK)
         rc = store_groups(c, view, uint64_t(first_layer) * layer_bytes, ptrs, op->slot_mapping, op->new_chunk,
-                          op->slots, cap, false, direct);
+                          op->slots, cap, false, direct, on_second);
     hipEvent_t e = nullptr;
     if (rc == LMC_OK) rc = get_event(c, false, &e);
     if (rc == LMC_OK) {
@@ -1484,7 +1496,10 @@ lmc_status_t lmc_store_layers(lmc_ctx_t *c, uint64_t ticket, int32_t first_layer
         rc = [&]() -> lmc_status_t {
             HIPCHK(c, hipEventRecord(e, last));
             if (first_layer + n_layers == geom.num_layers) {
-                lmc_status_t r = get_event(c, false, &op->done);
+                // the ticket is complete when the steps of both streams are
+                lmc_status_t r = (op->both_copy_streams || on_second)
+                                     ? order_after(c, last, on_second ? c->s_d2h : c->s_d2h2) : LMC_OK;
+                if (r == LMC_OK) r = get_event(c, false, &op->done);
                 if (r != LMC_OK) return r;
                 op->owned_events.push_back(op->done);   // given back with the others if the record fails
                 HIPCHK(c, hipEventRecord(op->done, last));
@@ -1506,6 +1521,8 @@ lmc_status_t lmc_store_layers(lmc_ctx_t *c, uint64_t ticket, int32_t first_layer
     }
     for (int32_t l = first_layer; l < first_layer + n_layers; l++) op->layer_done[size_t(l)] = e;
     op->next_layer = first_layer + n_layers;
+    op->steps++;
+    op->both_copy_streams = op->both_copy_streams || on_second;
     if (op->next_layer == geom.num_layers) op->pending = false;
     return LMC_OK;
 }
@@ -2091,6 +2108,8 @@ lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
         c->shape.xcd_run = uint32_t(value);
     } else if (k == "d2h_guard" && value <= 1) {
         c->d2h_guard_on = value != 0;
+    } else if (k == "store_step_streams" && value >= 1 && value <= 2) {
+        c->store_step_streams = int32_t(value);
     } else if (k == "pieces_by_kernel_below") {
         c->pieces_by_kernel_below = uint64_t(value);
     } else if (k == "caller_waits" && value <= 1) {
