@@ -398,10 +398,10 @@ lmc_status_t order_after_caller(lmc_ctx *c, hipStream_t waiter, hipStream_t user
 }
 
 // Is an operation of the other direction still under way?  The second copy stream of a
-// host-to-device direction sits in the hardware queue of the device-to-host copies (see
+// direction sits in the hardware queue of the other direction's kernel stream (see
 // arrange_streams), and as created any two streams may share one: next to a transfer the
 // other way a second copy stream would not add a copy in flight but hold that transfer's
-// copies up, so it is left out then.
+// kernels or copies up, so it is left out then.
 bool other_direction_busy(lmc_ctx *c, bool for_store) {
     for (const Op &o : c->ops) {
         const bool is_store = o.pending || o.final_stream == c->s_d2h || o.final_stream == c->s_d2h2 || o.final_stream == c->s_gather;
@@ -1021,13 +1021,16 @@ lmc_status_t shares_a_queue(lmc_ctx *c, hipStream_t busy, bool by_kernel, hipStr
 // measured on the 10 GiB request with a store and a retrieve running together: 63, 72 or
 // 100 GB/s summed, by arrangement alone.  The plan: the two kernel streams and the first
 // copy stream of each direction on four different queues, so that the four streams of a
-// full-duplex transfer never wait for each other.  The second host-to-device copy stream
-// must not sit behind the first (layer-wise retrieves alternate between them so that one
-// step's copy starts while the other's is being retired: on one queue that gains nothing,
-// 52.7 instead of 56.2 GB/s at four layers a step) nor behind the scatter stream (whose
-// waits would hold it up), so it joins the first device-to-host copy stream; the second
-// device-to-host stream (fragmented stores only, where sharing costs nothing) joins it
-// too.  other_direction_busy() keeps the second streams out of a two-way transfer.  With
+// full-duplex transfer never wait for each other.  A second copy stream must not sit
+// behind the first one of its direction (the steps of a layer-wise transfer alternate
+// between the two so that one step's copy starts while the other's is being retired: in
+// one queue that gains nothing, 52.7 instead of 56.2 GB/s for a retrieve at four layers a
+// step), nor behind the kernel stream of its own direction (whose waits would hold it up),
+// nor with a copy stream of the other direction (the copies of a two-way transfer would
+// take turns).  So each joins the kernel stream of the *other* direction, which a one-way
+// transfer leaves idle: the second host-to-device stream the gather stream's queue, the
+// second device-to-host stream the scatter stream's.  other_direction_busy() keeps the
+// second streams out of a transfer that finds the other direction at work.  With
 // fewer queues a kernel stream joins the first copy stream of the other direction; with six
 // or more every stream has its own.  Streams are told apart by shares_a_queue(); candidates
 // are created until the plan can be met (at most 16, the unused ones are destroyed); if it
