@@ -163,6 +163,7 @@ struct lmc_ctx {
     // steps, scattered pool slots) they alternate between the two streams of their
     // direction, because back-to-back copies on one stream leave the link idle in between
     hipStream_t s_h2d2 = nullptr, s_d2h2 = nullptr;
+    std::vector<hipStream_t> retired_streams;   // see arrange_streams; destroyed with the context, after the events
     Ring store_ring, load_ring;
     int32_t *bad_flag_host = nullptr, *bad_flag_dev = nullptr;
     std::deque<Op> ops;
@@ -1108,8 +1109,14 @@ void arrange_streams(lmc_ctx *c) {
     } else {
         for (size_t i = 0; i < 6; i++) keep[i] = 1;
     }
+    // The streams not chosen live on, unused, until the context goes: events that were
+    // recorded on them are in circulation (the three of the test above, and after a
+    // repeated arrangement every event of the rings), and the runtime looks up the stream an
+    // event was last recorded on when the event is queried or waited for.  With the stream
+    // destroyed, hipEventQuery now and then answered "operation not permitted when stream is
+    // capturing" from whatever lay in the freed stream's place.
     for (size_t i = 0; i < cand.size(); i++)
-        if (!keep[i]) (void)hipStreamDestroy(cand[i]);
+        if (!keep[i]) c->retired_streams.push_back(cand[i]);
     for (hipEvent_t ev : {a0, a1, k1})
         if (ev) c->free_time_events.push_back(ev);
     (void)hipGetLastError();
@@ -1990,10 +1997,17 @@ lmc_status_t lmc_probe_stream(lmc_ctx_t *c, void *stream, uint32_t *mask_out) {
         rc = shares_a_queue(c, copy_streams[i], i >= 4, user, devbuf, nbytes, a0, a1, k1, &shares);
         if (rc == LMC_OK && shares) mask |= 1u << i;
     }
-    for (hipEvent_t ev : {a0, a1, k1})
-        if (ev) c->free_time_events.push_back(ev);
     (void)hipDeviceSynchronize();
+    for (hipEvent_t ev : {a0, a1})
+        if (ev) c->free_time_events.push_back(ev);
+    // k1 was recorded on the caller's stream, which the caller may destroy while the event
+    // is still in circulation here (see arrange_streams): it is not kept
+    if (k1) {
+        c->all_events.erase(std::remove(c->all_events.begin(), c->all_events.end(), k1), c->all_events.end());
+        (void)hipEventDestroy(k1);
+    }
     (void)hipFree(devbuf);
+    (void)hipGetLastError();
     *mask_out = mask;
     return rc;
 }
