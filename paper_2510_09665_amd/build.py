@@ -9,8 +9,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblmc.so")
-SOURCES = ["lmc_kernels.hip", "lmc_ctx.cpp", "lmc_seq.cpp", "lmc_window.cpp", "lmc_tier.cpp"]
-HEADERS = ["lmc_kernels.hpp", "lmc_index.hpp", "lmc_window.hpp", "lmc_guard.hpp", os.path.join("..", "..", "include", "lmc.h")]
+SOURCES = ["lmc_kernels.hip", "lmc_ctx.cpp", "lmc_pipeline.cpp", "lmc_streams.cpp", "lmc_measure.cpp", "lmc_static.cpp",
+           "lmc_seq.cpp", "lmc_window.cpp", "lmc_tier.cpp"]
+HEADERS = ["lmc_ctx.hpp", "lmc_kernels.hpp", "lmc_index.hpp", "lmc_window.hpp", "lmc_guard.hpp", os.path.join("..", "..", "include", "lmc.h")]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",

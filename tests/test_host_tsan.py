@@ -19,8 +19,8 @@ CSRC = os.path.join(ROOT, "paper_2510_09665_amd", "csrc")
 def test_host_side_is_race_free_under_tsan(tmp_path):
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     lib = str(tmp_path / "liblmc_tsan.so")
-    srcs = [os.path.join(CSRC, f) for f in ("lmc_kernels.hip", "lmc_ctx.cpp", "lmc_seq.cpp", "lmc_window.cpp",
-                                                "lmc_tier.cpp")]
+    from paper_2510_09665_amd.build import SOURCES       # every source of the library, as the build lists them
+    srcs = [os.path.join(CSRC, f) for f in SOURCES]
     build = [hipcc, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
              "-Xarch_host", "-fsanitize=thread", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
     res = subprocess.run(build + srcs + ["-o", lib], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
