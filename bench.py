@@ -788,6 +788,65 @@ def mode_legs(torch, lmc, W, dev, stream, legs, args, timed, peaks):
     return out
 
 
+def trace_leg(lmc, ctx, g, src, dst, d_store, d_load, ids, stream, payload_one_way):
+    """Component-wise timeline of one store and one retrieve of the headline request, from
+    the library's own trace (device time stamps of every gather launch, every group's
+    copies and every scatter launch): how long each stage was busy, the gaps between the
+    copies of consecutive groups, and what of the span no copy covered."""
+    names = {lmc.LMC_STAGE_GATHER: "gather", lmc.LMC_STAGE_D2H: "d2h", lmc.LMC_STAGE_H2D: "h2d",
+             lmc.LMC_STAGE_SCATTER: "scatter"}
+
+    def summary(recs, copy_stage, kernel_stage, wall_s):
+        out = {"wall_ms_with_the_trace_on": round(wall_s * 1e3, 3),
+               "gbps_with_the_trace_on": round(payload_one_way / wall_s / 1e9, 2)}
+        copies = sorted((r for r in recs if r["stage"] == copy_stage), key=lambda r: r["begin_us"])
+        kernels = sorted((r for r in recs if r["stage"] == kernel_stage), key=lambda r: r["begin_us"])
+        first = min(r["begin_us"] for r in copies + kernels)
+        last = max(r["end_us"] for r in copies + kernels)
+        out["device_span_ms"] = round((last - first) / 1e3, 3)
+        for name, rs in ((names[copy_stage], copies), (names[kernel_stage], kernels)):
+            busy = sum(r["end_us"] - r["begin_us"] for r in rs)
+            out[name] = {"steps": len(rs), "busy_ms": round(busy / 1e3, 3),
+                         "mean_us": round(busy / max(len(rs), 1), 1),
+                         "gbps_while_busy": round(sum(r["bytes"] for r in rs) / max(busy, 1e-9) / 1e3, 2)}
+        gaps = sorted(b["begin_us"] - a["end_us"] for a, b in zip(copies, copies[1:]))
+        if gaps:
+            out["gap_between_consecutive_groups_copies_us"] = {
+                "min": round(gaps[0], 1), "median": round(gaps[len(gaps) // 2], 1), "max": round(gaps[-1], 1),
+                "sum_ms": round(sum(gaps) / 1e3, 3)}
+        covered = sum(r["end_us"] - r["begin_us"] for r in copies)
+        out["span_not_covered_by_a_copy_ms"] = round((last - first - covered) / 1e3, 3)
+        # kernel time that ran while no copy did: what the pipeline failed to hide
+        exposed = 0.0
+        for k_ in kernels:
+            hidden = sum(max(0.0, min(k_["end_us"], c_["end_us"]) - max(k_["begin_us"], c_["begin_us"])) for c_ in copies)
+            exposed += (k_["end_us"] - k_["begin_us"]) - hidden
+        out["kernel_time_not_behind_a_copy_ms"] = round(exposed / 1e3, 3)
+        return out
+
+    ctx.clear(ids)
+    ctx.tune("trace", 1)
+    res = {}
+    try:
+        t0 = time.perf_counter()
+        ctx.wait(ctx.store(src, d_store, ids, stream))
+        wall = time.perf_counter() - t0
+        recs, dropped = ctx.trace_read()
+        res["store"] = summary(recs, lmc.LMC_STAGE_D2H, lmc.LMC_STAGE_GATHER, wall)
+        t0 = time.perf_counter()
+        ctx.wait(ctx.retrieve(ids, d_load, dst, stream))
+        wall = time.perf_counter() - t0
+        recs, dropped2 = ctx.trace_read()
+        res["retrieve"] = summary(recs, lmc.LMC_STAGE_H2D, lmc.LMC_STAGE_SCATTER, wall)
+        res["records_lost"] = dropped + dropped2
+    finally:
+        ctx.tune("trace", 0)
+        ctx.clear(ids)
+    res["note"] = ("kernels carry their own begin / end time stamps; a group's copies are bracketed by two event "
+                   "markers on the copy stream, which themselves cost the link some microseconds per group")
+    return res
+
+
 def small_leg(torch, lmc, W, dev, stream, timed):
     """One chunk of half a MiB (configuration 1): microseconds from the call to a finished
     lmc_wait, through the staging ring and by the library's size rule (no staging)."""
@@ -827,7 +886,7 @@ def main():
                     help="steps measured right after set-up, before anything settles (0 = none)")
     ap.add_argument("--settle-seconds", type=float, default=20.0,
                     help="upper limit for the untimed settling phase before the warm-up (0 = none)")
-    ap.add_argument("--legs", default="pipeline,link,device,groups,configs,placement,duplex,direct,layerwise,overlap,"
+    ap.add_argument("--legs", default="pipeline,link,device,trace,groups,configs,placement,duplex,direct,layerwise,overlap,"
                                       "fragmented,small,cpu",
                     help="comma list of pipeline (always run), link, device, groups, configs, placement, duplex, direct, "
                          "layerwise, overlap, fragmented, small, cpu: the extra measurements to make; "
@@ -1074,6 +1133,8 @@ def main():
         else:
             out[key] = val
 
+    if "trace" in legs:
+        leg("trace", lambda: trace_leg(lmc, ctx, g, src, dst, d_store, d_load, ids, stream, payload_one_way))
     if "groups" in legs:
         leg("group_size", lambda: group_size_leg(torch, lmc, W, g, seq, src, dst, d_store, d_load, stream, timed,
                                                  peaks, args.num_staging))

@@ -105,6 +105,9 @@ enum {
                                       direction have four different queues: the four streams
                                       of a store and a retrieve running together then never
                                       wait for each other. */
+#define LMC_FLAG_TRACE 128u         /* keep a record of every pipeline step (see lmc_trace_read);
+                                      also switched by lmc_tune("trace", 0 / 1).  Costs two
+                                      event markers per group on the copy streams. */
 #define LMC_FLAG_TIMING 8u         /* give every gather / scatter launch a start and a stop
                                       HIP event (kernel begin / end on its own stream);
                                       durations appear in lmc_stats_t. */
@@ -556,7 +559,8 @@ lmc_status_t lmc_probe_stream(lmc_ctx_t *ctx, void *stream, uint32_t *mask_out);
  * and free memory while they store),
  * "edge_chunks" (size
  * of the group at the exposed end of a pipeline, 0 = none), "timing" (0/1: switches
- * LMC_FLAG_TIMING), "direct_store_below" / "direct_retrieve_below" (bytes, default 64 MiB
+ * LMC_FLAG_TIMING), "trace" (0/1: switches LMC_FLAG_TRACE; 1 also empties the trace and
+ * restarts its clock), "direct_store_below" / "direct_retrieve_below" (bytes, default 64 MiB
  * each: an lmc_store with at most that many new bytes, or an lmc_retrieve /
  * lmc_retrieve_batch of at most that many bytes, goes the LMC_FLAG_DIRECT way: one launch
  * instead of kernel, event, copy, event; 0 = never), "scatter_order" (default 0; 1 or 2:
@@ -583,6 +587,29 @@ lmc_status_t lmc_probe_stream(lmc_ctx_t *ctx, void *stream, uint32_t *mask_out);
  * failed, once; 0 = off.  Nothing on the device goes wrong).
  * Unknown key or out-of-range value: LMC_ERR_INVAL. */
 lmc_status_t lmc_tune(lmc_ctx_t *ctx, const char *key, int64_t value);
+
+/* Component-wise timeline of the pipelines (the paper breaks its delays down by component,
+ * sections 8.1 and 8.6; here per step on the device).  Under LMC_FLAG_TRACE every gather
+ * launch, every group's device-to-host copies, every group's host-to-device copies and
+ * every scatter launch leaves one record when it has completed: kernels with their own
+ * begin / end time stamps, copies between two event markers on their copy stream (copies
+ * that a fragmented group puts on the second copy stream are inside the same bracket).
+ * Times are device time in microseconds since the trace was switched on.  The library keeps
+ * the newest 65536 records. */
+enum { LMC_STAGE_GATHER = 0, LMC_STAGE_D2H = 1, LMC_STAGE_H2D = 2, LMC_STAGE_SCATTER = 3 };
+typedef struct {
+    uint64_t ticket;          /* the store / retrieve the step belongs to; 0: lmc_gather / lmc_scatter */
+    int32_t stage;            /* LMC_STAGE_* */
+    int32_t chunks;           /* chunks of the group */
+    uint64_t bytes;           /* payload bytes of the step */
+    double begin_us, end_us;
+} lmc_trace_rec_t;
+/* Takes up to cap finished records out of the trace, oldest first, into out (HOST);
+ * *n_out (HOST) receives their number, *dropped_out (HOST, may be NULL) how many records
+ * were lost to the limit since the last call.  Steps still running stay for a later call.
+ * LMC_ERR_NODEVICE. */
+lmc_status_t lmc_trace_read(lmc_ctx_t *ctx, lmc_trace_rec_t *out, int64_t cap, int64_t *n_out,
+                            uint64_t *dropped_out);
 
 const char *lmc_strerror(lmc_status_t status);
 int32_t lmc_last_hip_error(const lmc_ctx_t *ctx); /* hipError_t of the last LMC_ERR_HIP */

@@ -134,14 +134,25 @@ void reap(lmc_ctx *c) {
         Timing &t = c->timings[i];
         if (hipEventQuery(t.stop) == hipSuccess) {
             float ms = 0.f;
-            if (hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) {
-                if (t.is_gather) {
+            const bool kernel = t.stage == LMC_STAGE_GATHER || t.stage == LMC_STAGE_SCATTER;
+            if (kernel && hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) {
+                if (t.stage == LMC_STAGE_GATHER) {
                     c->stats.gather_ms += ms;
                     c->stats.timed_gather_launches++;
                 } else {
                     c->stats.scatter_ms += ms;
                     c->stats.timed_scatter_launches++;
                 }
+            }
+            float b = 0.f, e = 0.f;
+            if ((c->cfg.flags & LMC_FLAG_TRACE) && c->trace_epoch != nullptr &&
+                hipEventElapsedTime(&b, c->trace_epoch, t.start) == hipSuccess &&
+                hipEventElapsedTime(&e, c->trace_epoch, t.stop) == hipSuccess) {
+                if (c->trace.size() >= kTraceCap) {
+                    c->trace.pop_front();
+                    c->trace_dropped++;
+                }
+                c->trace.push_back(lmc_trace_rec_t{t.ticket, t.stage, t.chunks, t.bytes, double(b) * 1e3, double(e) * 1e3});
             }
             c->free_time_events.push_back(t.start);
             c->free_time_events.push_back(t.stop);
@@ -150,6 +161,39 @@ void reap(lmc_ctx *c) {
             i++;
         }
     }
+    (void)hipGetLastError();
+}
+
+// LMC_FLAG_TRACE: a timing event in front of the copies of a group ...
+lmc_status_t trace_begin(lmc_ctx *c, hipStream_t stream, hipEvent_t *start) {
+    *start = nullptr;
+    if (!(c->cfg.flags & LMC_FLAG_TRACE)) return LMC_OK;
+    lmc_status_t rc = get_event(c, true, start);
+    if (rc != LMC_OK) return rc;
+    const hipError_t e = injected_failure(c) ? hipErrorUnknown : hipEventRecord(*start, stream);
+    if (e != hipSuccess) {
+        c->free_time_events.push_back(*start);
+        *start = nullptr;
+        HIPCHK(c, e);
+    }
+    return LMC_OK;
+}
+
+// ... and one behind them; the pair is read when both have completed (reap).
+lmc_status_t trace_end(lmc_ctx *c, hipStream_t stream, hipEvent_t start, int32_t stage, int64_t chunks, uint64_t bytes) {
+    if (start == nullptr) return LMC_OK;
+    hipEvent_t stop = nullptr;
+    lmc_status_t rc = get_event(c, true, &stop);
+    hipError_t e = hipSuccess;
+    if (rc == LMC_OK) e = injected_failure(c) ? hipErrorUnknown : hipEventRecord(stop, stream);
+    if (rc != LMC_OK || e != hipSuccess) {
+        c->free_time_events.push_back(start);
+        if (stop) c->free_time_events.push_back(stop);
+        if (rc != LMC_OK) return rc;
+        HIPCHK(c, e);
+    }
+    c->timings.push_back(Timing{start, stop, stage, c->cur_ticket, int32_t(chunks), bytes});
+    return LMC_OK;
 }
 
 // Orders `waiter` after everything enqueued so far on `stream`.
@@ -302,6 +346,20 @@ static lmc_status_t pending_fill(lmc_ctx *c, uint64_t id, int64_t *slot_out, hip
     return LMC_OK;
 }
 
+// Switches the trace on: device time counts from here.
+static lmc_status_t start_trace(lmc_ctx *c) {
+    if (c->trace_epoch == nullptr) {
+        lmc_status_t rc = get_event(c, true, &c->trace_epoch);
+        if (rc != LMC_OK) return rc;
+    }
+    HIPCHK(c, hipEventRecord(c->trace_epoch, c->s_gather));
+    HIPCHK(c, hipEventSynchronize(c->trace_epoch));
+    c->trace.clear();
+    c->trace_dropped = 0;
+    c->cfg.flags |= LMC_FLAG_TRACE;
+    return LMC_OK;
+}
+
 static void destroy_ctx(lmc_ctx *c) {
     if (c->has_device) {
         DeviceScope dev(c);
@@ -425,6 +483,7 @@ lmc_status_t lmc_create(const lmc_config_t *cfg, lmc_ctx_t **ctx_out) {
         if ((rc = make_ring(c, c->store_ring)) != LMC_OK) return fail(rc);
         if ((rc = make_ring(c, c->load_ring)) != LMC_OK) return fail(rc);
         if (!(cfg->flags & LMC_FLAG_KEEP_STREAMS)) arrange_streams(c);
+        if ((cfg->flags & LMC_FLAG_TRACE) && (rc = start_trace(c)) != LMC_OK) return fail(rc);
     }
     c->index.reset(c->n_pool_slots);
     c->stats.pool_slots_total = uint64_t(c->n_pool_slots);
@@ -684,12 +743,40 @@ lmc_status_t lmc_reset_stats(lmc_ctx_t *c) {
     return LMC_OK;
 }
 
+lmc_status_t lmc_trace_read(lmc_ctx_t *c, lmc_trace_rec_t *out, int64_t cap, int64_t *n_out, uint64_t *dropped_out) {
+    if (!c || !n_out || cap < 0 || (cap > 0 && !out)) return LMC_ERR_INVAL;
+    if (!c->has_device) return LMC_ERR_NODEVICE;
+    std::lock_guard<std::mutex> lock(c->mu);
+    DeviceScope dev(c);
+    reap(c);
+    int64_t n = 0;
+    while (n < cap && !c->trace.empty()) {
+        out[n++] = c->trace.front();
+        c->trace.pop_front();
+    }
+    *n_out = n;
+    if (dropped_out) {
+        *dropped_out = c->trace_dropped;
+        c->trace_dropped = 0;
+    }
+    return LMC_OK;
+}
+
 lmc_status_t lmc_tune(lmc_ctx_t *c, const char *key, int64_t value) {
     if (!c || !key || value < 0) return LMC_ERR_INVAL;
     std::lock_guard<std::mutex> lock(c->mu);
     const std::string k(key);
     if (k == "timing" && value <= 1) {
         c->cfg.flags = value ? (c->cfg.flags | LMC_FLAG_TIMING) : (c->cfg.flags & ~LMC_FLAG_TIMING);
+    } else if (k == "trace" && value <= 1) {
+        if (!c->has_device) return LMC_ERR_NODEVICE;
+        if (value == 0) {
+            c->cfg.flags &= ~LMC_FLAG_TRACE;
+        } else {
+            DeviceScope dev(c);
+            lmc_status_t rc = start_trace(c);
+            if (rc != LMC_OK) return rc;
+        }
     } else if (k == "edge_chunks") {
         c->edge_chunks = value;
     } else if (k == "direct_store_below") {

@@ -53,9 +53,14 @@ struct Op {
     std::vector<hipEvent_t> owned_events; // the distinct events behind layer_done
 };
 
+// One timed step of a pipeline: a kernel launch (LMC_FLAG_TIMING, LMC_FLAG_TRACE) or the
+// copies of one group (LMC_FLAG_TRACE), between two timing events.
 struct Timing {
     hipEvent_t start, stop;
-    bool is_gather;
+    int32_t stage;        // LMC_STAGE_*
+    uint64_t ticket;      // the operation the step belongs to, 0 = none
+    int32_t chunks;
+    uint64_t bytes;
 };
 
 struct CopyTiming {   // a large device-to-host copy by the runtime, watched by the guard
@@ -137,6 +142,11 @@ struct lmc_ctx {
     int32_t *bad_flag_host = nullptr, *bad_flag_dev = nullptr;
     std::deque<Op> ops;
     std::deque<Timing> timings;
+    // LMC_FLAG_TRACE: finished steps, oldest first, at most kTraceCap; device time counts from trace_epoch
+    std::deque<lmc_trace_rec_t> trace;
+    uint64_t trace_dropped = 0;
+    hipEvent_t trace_epoch = nullptr;
+    uint64_t cur_ticket = 0;   // the operation whose steps are being enqueued (for the trace)
     uint64_t next_ticket = 1;
     std::vector<hipEvent_t> free_sync_events, free_time_events, all_events;
     // Threads that sleep in hipEventSynchronize with the mutex released.  While there are
@@ -190,6 +200,7 @@ private:
 // The mapped flag block holds 16 words: word 0 is set by the gather / scatter kernels on a
 // slot outside the pages, word kCheckWord by the check kernel of LMC_FLAG_VALIDATE_SLOTS.
 constexpr int kCheckWord = 8;
+constexpr size_t kTraceCap = size_t(1) << 16;
 
 // lmc_ctx.cpp
 lmc_status_t get_event(lmc_ctx *c, bool timing, hipEvent_t *out);
@@ -204,6 +215,8 @@ bool other_direction_busy(lmc_ctx *c, bool for_store);
 lmc_status_t validate_slots(lmc_ctx *c, const int64_t *slot_mapping, int64_t n_tokens,
                             hipStream_t stream);
 lmc_status_t force_sync(lmc_ctx *c, hipStream_t s);
+lmc_status_t trace_begin(lmc_ctx *c, hipStream_t stream, hipEvent_t *start);
+lmc_status_t trace_end(lmc_ctx *c, hipStream_t stream, hipEvent_t start, int32_t stage, int64_t chunks, uint64_t bytes);
 void begin_use(lmc_ctx *c, const uint64_t *ids, int64_t n);
 void end_use(lmc_ctx *c, const uint64_t *ids, int64_t n);
 int64_t take_slot(lmc_ctx *c, uint64_t id);

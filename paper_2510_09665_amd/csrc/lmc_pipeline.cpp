@@ -73,7 +73,7 @@ lmc_status_t timed_launch(lmc_ctx *c, bool gather, const lmc::LaunchView &view,
     // LMC_FLAG_TIMING: the launch itself carries a start and a stop event, which receive
     // the kernel's own begin / end time stamps; the stream gets no extra marker.
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (c->cfg.flags & LMC_FLAG_TIMING) {
+    if (c->cfg.flags & (LMC_FLAG_TIMING | LMC_FLAG_TRACE)) {
         lmc_status_t rc = get_event(c, true, &e0);
         if (rc == LMC_OK) rc = get_event(c, true, &e1);
         if (rc != LMC_OK) return rc;
@@ -117,7 +117,8 @@ lmc_status_t timed_launch(lmc_ctx *c, bool gather, const lmc::LaunchView &view,
         c->stats.scatter_launches++;
         c->stats.bytes_scattered += moved;
     }
-    if (e0 != nullptr) c->timings.push_back(Timing{e0, e1, gather});
+    if (e0 != nullptr)
+        c->timings.push_back(Timing{e0, e1, gather ? LMC_STAGE_GATHER : LMC_STAGE_SCATTER, c->cur_ticket, int32_t(n_chunks), moved});
     return LMC_OK;
 }
 
@@ -352,6 +353,7 @@ static lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunk
     end_use(c, ids, n_chunks);
     Op op;
     op.ticket = c->next_ticket++;
+    c->cur_ticket = op.ticket;
     op.layerwise = layers_per_step > 0;
     if (n_chunks == 0) return finish_op(c, std::move(op), nullptr, false, ticket_out);
 
@@ -388,11 +390,19 @@ static lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunk
             if (second) HIPCHK(c, hipStreamWaitEvent(second, ring.drained[b], 0));
         }
         bool used_second = false;
-        lmc_status_t r = copy_group(c, false, buf, view.chunk_stride, &pool_slots[size_t(i0)], k,
-                                    pool_off, view.chunk_stride, copy_stream, second, &used_second);
+        hipEvent_t traced = nullptr;
+        lmc_status_t r = trace_begin(c, copy_stream, &traced);
         if (r != LMC_OK) return r;
+        r = copy_group(c, false, buf, view.chunk_stride, &pool_slots[size_t(i0)], k,
+                       pool_off, view.chunk_stride, copy_stream, second, &used_second);
         // the buffer is full when the copies of both streams are in
-        if (used_second && (r = order_after(c, copy_stream, second)) != LMC_OK) return r;
+        if (r == LMC_OK && used_second) r = order_after(c, copy_stream, second);
+        if (r != LMC_OK) {
+            if (traced) c->free_time_events.push_back(traced);
+            return r;
+        }
+        if ((r = trace_end(c, copy_stream, traced, LMC_STAGE_H2D, k, uint64_t(k) * view.by_n_lp.d * c->kg.plane_bytes)) != LMC_OK)
+            return r;
         HIPCHK(c, hipEventRecord(ring.filled[b], copy_stream));
         if ((r = force_sync(c, copy_stream)) != LMC_OK) return r;
         HIPCHK(c, hipStreamWaitEvent(c->s_scatter, ring.filled[b], 0));
@@ -564,11 +574,18 @@ static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64
         hipStream_t second = (two_copy_streams && several_runs(&new_slot[j0], int64_t(k))) ? other : nullptr;
         if (second) HIPCHK(c, hipStreamWaitEvent(second, ring.filled[b], 0));
         bool used_second = false;
+        hipEvent_t traced = nullptr;
+        if ((rc = trace_begin(c, copies, &traced)) != LMC_OK) return rc;
         rc = copy_group(c, true, buf, view.chunk_stride, &new_slot[j0], int64_t(k), pool_off,
                         view.chunk_stride, copies, second, &used_second);
-        if (rc != LMC_OK) return rc;
         // the group's copy stream stands for the whole group: it ends after the other stream's copies
-        if (used_second && (rc = order_after(c, copies, second)) != LMC_OK) return rc;
+        if (rc == LMC_OK && used_second) rc = order_after(c, copies, second);
+        if (rc != LMC_OK) {
+            if (traced) c->free_time_events.push_back(traced);
+            return rc;
+        }
+        if ((rc = trace_end(c, copies, traced, LMC_STAGE_D2H, int64_t(k), uint64_t(k) * view.by_n_lp.d * c->kg.plane_bytes)) != LMC_OK)
+            return rc;
         if (c->cfg.flags & LMC_FLAG_POISON_STAGING)
             HIPCHK(c, lmc::launch_fill(buf, 0xA5, uint64_t(k) * view.chunk_stride, copies));
         HIPCHK(c, hipEventRecord(ring.drained[b], copies));
@@ -587,6 +604,7 @@ static lmc_status_t device_only(lmc_ctx_t *c, bool gather, void *const *kv_layer
     if (!c->has_device) return LMC_ERR_NODEVICE;
     if (reinterpret_cast<uintptr_t>(staging) % c->kg.vec) return LMC_ERR_INVAL;
     std::lock_guard<std::mutex> lock(c->mu);
+    c->cur_ticket = 0;
     DeviceScope dev(c);
     reap(c);
     lmc::LayerPtrs ptrs;
@@ -631,6 +649,7 @@ lmc_status_t lmc_store(lmc_ctx_t *c, void *const *kv_layers, const int64_t *slot
 
     Op op;
     op.ticket = c->next_ticket++;
+    c->cur_ticket = op.ticket;
     std::vector<int64_t> new_chunk;
     const bool fits = admit_new_chunks(c, ids, n_chunks, &op, &new_chunk);
     c->stats.chunks_stored += new_chunk.size();
@@ -691,6 +710,7 @@ lmc_status_t lmc_store_layers(lmc_ctx_t *c, uint64_t ticket, int32_t first_layer
     }
     if (!op->pending || first_layer != op->next_layer || first_layer + n_layers > geom.num_layers)
         return LMC_ERR_INVAL;
+    c->cur_ticket = op->ticket;
     lmc::LayerPtrs ptrs;
     lmc_status_t rc = build_layer_ptrs(c, kv_layers, &ptrs);
     if (rc != LMC_OK) return rc;

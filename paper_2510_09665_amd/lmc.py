@@ -22,6 +22,8 @@ LMC_FLAG_VALIDATE_SLOTS, LMC_FLAG_FORCE_SYNC, LMC_FLAG_POISON_STAGING, LMC_FLAG_
 LMC_FLAG_DIRECT = 16
 LMC_FLAG_EVICT_LRU = 32
 LMC_FLAG_KEEP_STREAMS = 64
+LMC_FLAG_TRACE = 128
+LMC_STAGE_GATHER, LMC_STAGE_D2H, LMC_STAGE_H2D, LMC_STAGE_SCATTER = 0, 1, 2, 3
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblmc.so")
 
@@ -35,7 +37,7 @@ EXPORTS = [
     "lmc_store_begin", "lmc_store_layers", "lmc_wait_layer", "lmc_wait", "lmc_gather",
     "lmc_scatter", "lmc_store_static", "lmc_put_host", "lmc_get_host", "lmc_find_slot", "lmc_pin", "lmc_unpin",
     "lmc_clear", "lmc_drain_evicted", "lmc_get_stats", "lmc_reset_stats", "lmc_measure_link", "lmc_measure_link_kernel", "lmc_measure_link_duplex", "lmc_measure_link_duplex_kernel",
-    "lmc_copy", "lmc_copy_tiles", "lmc_tune", "lmc_probe_stream", "lmc_chunk_acquire", "lmc_chunk_release", "lmc_tier_open", "lmc_tier_close",
+    "lmc_copy", "lmc_copy_tiles", "lmc_tune", "lmc_trace_read", "lmc_probe_stream", "lmc_chunk_acquire", "lmc_chunk_release", "lmc_tier_open", "lmc_tier_close",
     "lmc_tier_write", "lmc_tier_wait", "lmc_tier_lookup", "lmc_tier_read", "lmc_tier_errno",
     "lmc_tier_get_stats",
     "lmc_strerror", "lmc_last_hip_error",
@@ -55,6 +57,11 @@ class lmc_config_t(ctypes.Structure):
                 ("num_staging", ctypes.c_int32), ("staging_chunks", ctypes.c_int32),
                 ("device", ctypes.c_int32), ("flags", ctypes.c_uint32),
                 ("hash_seed", ctypes.c_uint64)]
+
+
+class lmc_trace_rec_t(ctypes.Structure):
+    _fields_ = [("ticket", ctypes.c_uint64), ("stage", ctypes.c_int32), ("chunks", ctypes.c_int32),
+                ("bytes", ctypes.c_uint64), ("begin_us", ctypes.c_double), ("end_us", ctypes.c_double)]
 
 
 class lmc_stats_t(ctypes.Structure):
@@ -157,6 +164,7 @@ def _lib():
             "lmc_copy": (st, [vp, vp, vp, u64, vp]),
             "lmc_copy_tiles": (st, [vp, vp, vp, vp, vp, u64, ctypes.c_uint32, vp]),
             "lmc_tune": (st, [vp, ctypes.c_char_p, i64]),
+            "lmc_trace_read": (st, [vp, ctypes.POINTER(lmc_trace_rec_t), i64, ctypes.POINTER(i64), ctypes.POINTER(u64)]),
             "lmc_strerror": (ctypes.c_char_p, [st]),
             "lmc_last_hip_error": (i32, [vp]),
         }
@@ -468,6 +476,16 @@ class Context:
 
     def tune(self, key, value):
         self._check(_lib().lmc_tune(self._h, key.encode(), int(value)), "lmc_tune")
+
+    def trace_read(self, cap=65536):
+        """Finished records of the trace (LMC_FLAG_TRACE), oldest first: a list of dicts with
+        ticket, stage (LMC_STAGE_*), chunks, bytes, begin_us, end_us; and how many were lost."""
+        buf = (lmc_trace_rec_t * cap)()
+        n, dropped = ctypes.c_int64(0), ctypes.c_uint64(0)
+        self._check(_lib().lmc_trace_read(self._h, buf, cap, ctypes.byref(n), ctypes.byref(dropped)), "lmc_trace_read")
+        recs = [dict(ticket=r.ticket, stage=r.stage, chunks=r.chunks, bytes=r.bytes, begin_us=r.begin_us,
+                     end_us=r.end_us) for r in buf[:n.value]]
+        return recs, dropped.value
 
 
 class Sequence:

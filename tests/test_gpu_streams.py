@@ -202,3 +202,62 @@ def test_retrieve_that_does_not_make_the_callers_stream_wait():
         for sl, tl in zip(src.compact_slots(ss).reshape(n, g.CT), dst.compact_slots(ts).reshape(n, g.CT)):
             oracle.scatter_chunk(dst.gc, oracle.gather_chunk(src.gc, src.host, sl), tl, dst.host)
         assert_layers_equal(dst.device_blocks_to_host(), dst.host)
+
+
+@pytest.mark.parametrize("at_create", [True, False])
+def test_trace_has_one_record_per_step_in_dependency_order(at_create):
+    """LMC_FLAG_TRACE: one record per gather launch, per group's copies each way and per
+    scatter launch; a group's copy begins after its gather has ended, its scatter after its
+    copy; the bytes add up to the payload; the data is what it is without the trace."""
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    lmc = _lmc()
+    g = _geom()
+    n, per = 9, 2
+    rng = np.random.default_rng(81)
+    bpc = g.CT // g.BS
+    blocks = rng.permutation(g.NB)
+    src = PagedKV(g, blocks[:n * bpc], rng)
+    dst = PagedKV(g, blocks[n * bpc:2 * n * bpc], fill="sentinel")
+    ss = W.slots_from_blocks(g, src.blocks, n * g.CT)
+    ts = W.slots_from_blocks(g, dst.blocks, n * g.CT)
+    ids = np.arange(1, n + 1, dtype=np.uint64)
+    stream = torch.cuda.current_stream()
+    with lmc.Context(g, n * g.chunk_bytes, staging_chunks=per, flags=lmc.LMC_FLAG_TRACE if at_create else 0) as c:
+        for key in ("direct_store_below", "direct_retrieve_below"):
+            c.tune(key, 0)
+        if not at_create:
+            assert c.trace_read()[0] == []
+            c.tune("trace", 1)
+        d_ss, d_ts = slots_to_device(ss), slots_to_device(ts)
+        t1 = c.store(src.dev, d_ss, ids, stream)
+        c.wait(t1)
+        t2 = c.retrieve(ids, d_ts, dst.dev, stream)
+        c.wait(t2)
+        recs, dropped = c.trace_read()
+        assert dropped == 0
+        by_stage = {s: [r for r in recs if r["stage"] == s] for s in range(4)}
+        # edge groups of one chunk at the exposed ends: 1 + 4 x 2 chunks for the store, 4 x 2 + 1 for the retrieve
+        assert [r["chunks"] for r in by_stage[lmc.LMC_STAGE_GATHER]] == [1, 2, 2, 2, 2]
+        assert [r["chunks"] for r in by_stage[lmc.LMC_STAGE_D2H]] == [1, 2, 2, 2, 2]
+        assert [r["chunks"] for r in by_stage[lmc.LMC_STAGE_H2D]] == [2, 2, 2, 2, 1]
+        assert [r["chunks"] for r in by_stage[lmc.LMC_STAGE_SCATTER]] == [2, 2, 2, 2, 1]
+        for s in range(4):
+            assert sum(r["bytes"] for r in by_stage[s]) == n * g.chunk_bytes
+            assert all(r["ticket"] == (t1 if s < 2 else t2) for r in by_stage[s])
+            assert all(0 <= r["begin_us"] < r["end_us"] for r in by_stage[s])
+        for k_, d in zip(by_stage[lmc.LMC_STAGE_GATHER], by_stage[lmc.LMC_STAGE_D2H]):
+            assert d["begin_us"] >= k_["end_us"] - 1.0        # the copy waits for its gather (1 us of clock slack)
+        for h, k_ in zip(by_stage[lmc.LMC_STAGE_H2D], by_stage[lmc.LMC_STAGE_SCATTER]):
+            assert k_["begin_us"] >= h["end_us"] - 1.0        # the scatter waits for its copy
+        assert by_stage[lmc.LMC_STAGE_H2D][0]["begin_us"] >= by_stage[lmc.LMC_STAGE_D2H][-1]["end_us"] - 1.0
+        # nothing left, and off means off
+        assert c.trace_read()[0] == []
+        c.tune("trace", 0)
+        c.wait(c.retrieve(ids, d_ts, dst.dev, stream))
+        assert c.trace_read()[0] == []
+        for i, sl in zip(ids.tolist(), src.compact_slots(ss).reshape(n, g.CT)):
+            assert np.array_equal(c.get_host(i), oracle.gather_chunk(src.gc, src.host, sl))
+        for sl, tl in zip(src.compact_slots(ss).reshape(n, g.CT), dst.compact_slots(ts).reshape(n, g.CT)):
+            oracle.scatter_chunk(dst.gc, oracle.gather_chunk(src.gc, src.host, sl), tl, dst.host)
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host)

@@ -113,7 +113,10 @@ def test_data_path_refuses_to_run_without_a_device():
                      lambda: c.measure_link_kernel(1024),
                      lambda: c.measure_link_duplex(1024),
                      lambda: c.measure_link_duplex_kernel(1024, 3),
-                     lambda: c.store_static(fake, 0x1000, 1, 0x1000)):
+                     lambda: c.store_static(fake, 0x1000, 1, 0x1000),
+                     lambda: c.trace_read(4),
+                     lambda: c.tune("trace", 1),
+                     lambda: c.tune("arrange_streams", 1)):
             with pytest.raises(lmc.LMCError) as e:
                 call()
             assert e.value.status == lmc.LMC_ERR_NODEVICE
