@@ -69,6 +69,8 @@ void arrange_streams(lmc_ctx *c) {
         std::min({uint64_t(32) << 20, pool_bytes, c->store_ring.buf_bytes - 256}) / 256 * 256;
     if (nbytes < (uint64_t(8) << 20)) return;   // too short a copy to tell waiting from running
     uint8_t *devbuf = c->store_ring.buf[0];
+    // the test tells waiting from running by the clock: nothing else should be running
+    (void)hipDeviceSynchronize();
     hipEvent_t a0 = nullptr, a1 = nullptr, k1 = nullptr;
     // roles in the order in which they get a queue of their own while queues last
     hipStream_t *const role[6] = {&c->s_h2d, &c->s_d2h, &c->s_scatter, &c->s_gather, &c->s_h2d2, &c->s_d2h2};
