@@ -231,7 +231,8 @@ lmc_status_t lmc_store(lmc_ctx_t *ctx, void *const *kv_layers, const int64_t *sl
  * touched.  stream_to_signal: a hipStream_t (NULL names the null stream).  The scatter
  * is ordered after everything enqueued on it so far (earlier users of the pages, the
  * producer of the slot mapping), and the stream is made to wait for the last scatter,
- * so work enqueued on it afterwards sees the pages.  Enqueue only.
+ * so work enqueued on it afterwards sees the pages (unless lmc_tune "caller_waits" is 0:
+ * then the caller orders its work after lmc_wait itself).  Enqueue only.
  * LMC_ERR_HIP in the middle of the call: what had been enqueued is waited for, no count
  * stays on the chunks, no ticket is issued; the pages named by slot_mapping are then
  * partly written. */
