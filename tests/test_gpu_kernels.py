@@ -79,6 +79,42 @@ def test_gather_and_scatter_match_oracle(name, xcd_run):
         assert_layers_equal(dst.device_blocks_to_host(), dst.host, name)
 
 
+def test_planes_larger_than_4_gib():
+    """Offsets inside a layer beyond 32 bits: planes of 5 GiB (163840 pages of 32 KiB), the
+    chunks' pages taken from both ends of the planes and from either side of the 4 GiB and
+    8 GiB marks of the layer.  The oracle sees a compact copy of those pages; every other
+    page must keep its sentinel."""
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    g = W.KVGeometry(L=1, P=2, H=8, D=128, e=2, BS=16, NB=163840, CT=256)
+    assert g.plane_stride > (1 << 32) and g.layer_bytes > (1 << 33)
+    rng = np.random.default_rng(4096)
+    n_chunks = 3
+    marks = [0, 1, 2, 131070, 131071, 131072, 131073, 98302, 98303, 98304, 98305,
+             g.NB - 1, g.NB - 2, g.NB - 3]
+    rest = rng.permutation(g.NB)
+    rest = rest[~np.isin(rest, marks)][:2 * n_chunks * (g.CT // g.BS) - len(marks)]
+    blocks = rng.permutation(np.concatenate([np.array(marks), rest]))
+    half = blocks.size // 2
+    src = PagedKV(g, blocks[:half], rng)
+    dst = PagedKV(g, blocks[half:], fill="sentinel")
+    slots = W.slots_from_blocks(g, src.blocks, n_chunks * g.CT)
+    tau = W.slots_from_blocks(g, dst.blocks, n_chunks * g.CT)
+    with _ctx(g) as c:
+        staging = torch.full((n_chunks * g.chunk_bytes,), 0xCD, dtype=torch.uint8, device="cuda")
+        c.gather(src.dev, slots_to_device(slots), n_chunks, staging, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        c.wait()
+        want = oracle.gather(src.gc, src.host, src.compact_slots(slots))
+        assert np.array_equal(staging.cpu().numpy().reshape(n_chunks, -1), want)
+        c.scatter(staging, slots_to_device(tau), n_chunks, dst.dev, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        c.wait()
+        oracle.scatter(dst.gc, want, dst.compact_slots(tau), dst.host)
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host, "planes of 5 GiB")
+        assert dst.untracked_blocks_untouched() and src.untracked_blocks_untouched()
+
+
 @pytest.mark.parametrize("name", list(SHAPES))
 @pytest.mark.parametrize("xcd_run", [None, 4])
 def test_scatter_in_destination_order_matches_oracle(name, xcd_run):
