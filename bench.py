@@ -209,6 +209,7 @@ def kernel_only(torch, ctx, W, name, g, src, dst, n_chunks, dev, stream, gather_
         scatter_slots = [torch.from_numpy(q["load_slots"]).to(dev) for q in seqs]
     stagings = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(n_rot)]
     spare = torch.empty(nbytes, dtype=torch.uint8, device=dev) if n_rot == 1 else None
+    torch.cuda.synchronize()      # pages and slot mappings were made on PyTorch's own stream
     out = []
     for fn in (lambda r: ctx.gather(src, gather_slots[r % len(gather_slots)], n_chunks, stagings[r], stream),
                lambda r: ctx.scatter(stagings[r], scatter_slots[r % len(scatter_slots)], n_chunks, dst, stream),
@@ -491,7 +492,7 @@ def kernels_only_mode(names, iters, reps):
     from paper_2510_09665_amd import lmc
     from paper_2510_09665_amd import workloads as W
     dev = torch.device("cuda:0")
-    stream = torch.cuda.current_stream()
+    stream = torch.cuda.Stream()     # the engine's stream, which the library orders itself after (not the null stream)
     res = {}
     for name in names:
         if name in EXTRA_SHAPES:
@@ -918,7 +919,7 @@ def main():
         kernels_only_mode(args.kernels_only.split(","), args.kernels_only_iters, args.kernels_only_reps)
         return
     dev = torch.device("cuda:0")
-    stream = torch.cuda.current_stream()
+    stream = torch.cuda.Stream()     # the engine's stream, which the library orders itself after (not the null stream)
     first_pages = None
     if "placement" in legs:
         try:

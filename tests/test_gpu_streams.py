@@ -67,7 +67,7 @@ def test_store_and_retrieve_issued_together_from_one_stream(order, fragmented):
     src_a, src_b, dst_b, sa, sb, tb = _two_requests(g, np.random.default_rng(77), n)
     ids_a = np.arange(1, n + 1, dtype=np.uint64)
     ids_b = np.arange(101, n + 101, dtype=np.uint64)
-    stream = torch.cuda.current_stream()
+    stream = torch.cuda.Stream()        # not the null stream: when it is idle, no event is recorded on it
     with lmc.Context(g, (4 * n + 1) * g.chunk_bytes, staging_chunks=2, flags=lmc.LMC_FLAG_POISON_STAGING) as c:
         for key in ("direct_store_below", "direct_retrieve_below"):
             c.tune(key, 0)
@@ -78,6 +78,7 @@ def test_store_and_retrieve_issued_together_from_one_stream(order, fragmented):
                 c.put_host([f], zero)
             c.clear(filler[1::2])
         d_sa, d_sb, d_tb = slots_to_device(sa), slots_to_device(sb), slots_to_device(tb)
+        torch.cuda.synchronize()            # pages and mappings were made on PyTorch's stream
         c.wait(c.store(src_b.dev, d_sb, ids_b, stream))
         if fragmented:
             assert [c.find_slot(i) for i in ids_b[:3]] == [1, 3, 5]
