@@ -214,13 +214,13 @@ lmc_status_t order_after(lmc_ctx *c, hipStream_t waiter, hipStream_t stream) {
 // the caller's stream takes its place in that stream's hardware queue, behind whatever a
 // library stream that shares the queue still has to run (with a store under way and the
 // caller's stream in the gather stream's queue, a retrieve issued next would start only
-// when the store's last gather has run).  The null stream always gets its event: work
-// recorded there also waits for what the process's other blocking streams hold, which a
-// query of the null stream alone does not see.
+// when the store's last gather has run).  This holds for the null stream too: work recorded
+// there also waits for what the process's other blocking streams hold, and the runtime's
+// query of the null stream answers "not ready" while any of them is busy (checked by
+// tests/test_gpu_streams.py, with the producer of the KV on a blocking stream).
 lmc_status_t order_after_caller(lmc_ctx *c, hipStream_t waiter, hipStream_t user) {
     hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
-    if (user != nullptr && hipStreamIsCapturing(user, &capturing) == hipSuccess &&
-        capturing == hipStreamCaptureStatusNone) {
+    if (hipStreamIsCapturing(user, &capturing) == hipSuccess && capturing == hipStreamCaptureStatusNone) {
         if (hipStreamQuery(user) == hipSuccess) return LMC_OK;
     }
     (void)hipGetLastError();   // "not ready" is an answer, not a failure

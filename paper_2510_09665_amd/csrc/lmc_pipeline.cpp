@@ -527,7 +527,7 @@ static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64
                                  const lmc::LayerPtrs &ptrs, const int64_t *slot_mapping,
                                  const std::vector<int64_t> &new_chunk,
                                  const std::vector<int64_t> &new_slot, int64_t cap_chunks,
-                                 bool edge_group, bool direct, bool on_second_stream = false) {
+                                 bool edge_group, bool direct, bool layer_step = false, bool on_second_stream = false) {
     Ring &ring = c->store_ring;
     const int64_t CT = c->cfg.geom.chunk_tokens;
     if (direct) {
@@ -571,7 +571,9 @@ static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64
         HIPCHK(c, hipEventRecord(ring.filled[b], c->s_gather));
         if ((rc = force_sync(c, c->s_gather)) != LMC_OK) return rc;
         HIPCHK(c, hipStreamWaitEvent(copies, ring.filled[b], 0));
-        hipStream_t second = (two_copy_streams && several_runs(&new_slot[j0], int64_t(k))) ? other : nullptr;
+        // a layer-wise step has the two streams step by step, not run by run (as the steps of a retrieve)
+        hipStream_t second = (two_copy_streams && !(layer_step && c->store_step_streams == 2) && several_runs(&new_slot[j0], int64_t(k)))
+                                 ? other : nullptr;
         if (second) HIPCHK(c, hipStreamWaitEvent(second, ring.filled[b], 0));
         bool used_second = false;
         hipEvent_t traced = nullptr;
@@ -733,7 +735,7 @@ lmc_status_t lmc_store_layers(lmc_ctx_t *c, uint64_t ticket, int32_t first_layer
                          nullptr, c->s_d2h2);
     if (rc == LMC_OK)
         rc = store_groups(c, view, uint64_t(first_layer) * layer_bytes, ptrs, op->slot_mapping, op->new_chunk,
-                          op->slots, cap, false, direct, on_second);
+                          op->slots, cap, false, direct, true, on_second);
     hipEvent_t e = nullptr;
     if (rc == LMC_OK) rc = get_event(c, false, &e);
     if (rc == LMC_OK) {

@@ -262,3 +262,68 @@ def test_trace_has_one_record_per_step_in_dependency_order(at_create):
         for sl, tl in zip(src.compact_slots(ss).reshape(n, g.CT), dst.compact_slots(ts).reshape(n, g.CT)):
             oracle.scatter_chunk(dst.gc, oracle.gather_chunk(src.gc, src.host, sl), tl, dst.host)
         assert_layers_equal(dst.device_blocks_to_host(), dst.host)
+
+
+def _hip():
+    import ctypes
+    with open("/proc/self/maps") as maps:
+        for line in maps:
+            if "libamdhip64" in line:
+                hip = ctypes.CDLL(line.split()[-1])
+                vp = ctypes.c_void_p
+                hip.hipStreamCreateWithFlags.argtypes = [ctypes.POINTER(vp), ctypes.c_uint]
+                hip.hipStreamQuery.argtypes = [vp]
+                hip.hipStreamSynchronize.argtypes = [vp]
+                hip.hipStreamDestroy.argtypes = [vp]
+                return hip
+    pytest.skip("HIP runtime not found in this process")
+
+
+def test_null_stream_as_the_callers_stream_covers_blocking_streams():
+    """A caller that names the null stream relies on its legacy meaning: work recorded there
+    waits for what every blocking stream of the process holds.  The KV is produced late on a
+    blocking stream; lmc_store(..., NULL) must still store the produced bytes.  (The
+    library records no event on an idle stream; that is safe here only because the
+    runtime's query of the null stream says "not ready" while a blocking stream is busy,
+    which is checked first.)"""
+    import ctypes
+    import torch
+    from gpu_util import PagedKV, slots_to_device
+    lmc = _lmc()
+    hip = _hip()
+    g = _geom()
+    n = 4
+    rng = np.random.default_rng(82)
+    bpc = g.CT // g.BS
+    blocks = rng.permutation(g.NB)
+    src = PagedKV(g, blocks[:n * bpc], rng)
+    ss = W.slots_from_blocks(g, src.blocks, n * g.CT)
+    ids = np.arange(1, n + 1, dtype=np.uint64)
+    raw = ctypes.c_void_p()
+    assert hip.hipStreamCreateWithFlags(ctypes.byref(raw), 0) == 0          # 0: a blocking stream
+    producer = torch.cuda.ExternalStream(raw.value)
+    a = torch.randn(4096, 4096, device="cuda", dtype=torch.bfloat16)
+    late = [d.clone() for d in src.dev]
+    for d in src.dev:
+        d.zero_()
+    try:
+        with lmc.Context(g, n * g.chunk_bytes, staging_chunks=2) as c:
+            d_ss = slots_to_device(ss)
+            torch.cuda.synchronize()
+            with torch.cuda.stream(producer):
+                for _ in range(40):
+                    a = (a @ a).clamp_(-1, 1)
+                for d, p in zip(src.dev, late):
+                    d.copy_(p, non_blocking=True)
+            assert hip.hipStreamQuery(raw) != 0, "the producer finished too early for this test to say anything"
+            assert hip.hipStreamQuery(None) != 0, "the null stream's query does not see the blocking stream"
+            hip.hipGetLastError()
+            t = c.store(src.dev, d_ss, ids, None)                           # NULL: the null stream
+            c.wait(t)
+            for i, sl in zip(ids.tolist(), src.compact_slots(ss).reshape(n, g.CT)):
+                assert np.array_equal(c.get_host(i), oracle.gather_chunk(src.gc, src.host, sl)), "store ran ahead"
+            torch.cuda.synchronize()
+    finally:
+        torch.cuda.synchronize()
+        del producer
+        hip.hipStreamDestroy(raw)
