@@ -814,7 +814,10 @@ def trace_leg(lmc, ctx, g, src, dst, d_store, d_load, ids, stream, payload_one_w
         if gaps:
             out["gap_between_consecutive_groups_copies_us"] = {
                 "min": round(gaps[0], 1), "median": round(gaps[len(gaps) // 2], 1), "max": round(gaps[-1], 1),
-                "sum_ms": round(sum(gaps) / 1e3, 3)}
+                "sum_ms": round(sum(gaps) / 1e3, 3),
+                "histogram": {"%s-%s us" % (lo, hi): sum(1 for x in gaps if lo <= x < hi)
+                              for lo, hi in ((0, 10), (10, 12), (12, 14), (14, 16), (16, 18), (18, 20), (20, 30),
+                                             (30, 100), (100, 10 ** 9)) if any(lo <= x < hi for x in gaps)}}
         covered = sum(r["end_us"] - r["begin_us"] for r in copies)
         out["span_not_covered_by_a_copy_ms"] = round((last - first - covered) / 1e3, 3)
         # kernel time that ran while no copy did: what the pipeline failed to hide
