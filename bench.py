@@ -464,6 +464,20 @@ def group_size_leg(torch, lmc, W, g, seq, src, dst, d_store, d_load, stream, tim
                 c.wait(c.store(src, d_store, ids, stream))
             ts = timed(store_only, reps=4)
             tl = timed(lambda: c.wait(c.retrieve(ids, d_load, dst, stream)), reps=4)
+            # the link's idle time between the copies of consecutive groups, from the trace
+            gaps = {}
+            c.tune("trace", 1)
+            c.clear(ids)
+            c.wait(c.store(src, d_store, ids, stream))
+            c.wait(c.retrieve(ids, d_load, dst, stream))
+            recs, _ = c.trace_read()
+            c.tune("trace", 0)
+            for key, stage in (("store", lmc.LMC_STAGE_D2H), ("retrieve", lmc.LMC_STAGE_H2D)):
+                cp = sorted((r for r in recs if r["stage"] == stage), key=lambda r: r["begin_us"])
+                gp = sorted(b["begin_us"] - a["end_us"] for a, b in zip(cp, cp[1:]))
+                if gp:
+                    gaps[key] = {"median": round(gp[len(gp) // 2], 1), "p90": round(gp[(len(gp) * 9) // 10], 1),
+                                 "max": round(gp[-1], 1), "sum_ms": round(sum(gp) / 1e3, 3)}
         groups = 1 + -(-(n_chunks - 1) // sc)          # one single-chunk group at the exposed end
         res["staging_chunks_%d" % sc] = {
             "groups_per_direction": groups,
@@ -471,7 +485,8 @@ def group_size_leg(torch, lmc, W, g, seq, src, dst, d_store, d_load, stream, tim
             "store_frac_of_d2h_peak": round(nbytes / ts / 1e9 / peaks["d2h_peak_gbps"], 4),
             "retrieve_frac_of_h2d_peak": round(nbytes / tl / 1e9 / peaks["h2d_peak_gbps"], 4),
             "store_us_beyond_peak_per_group": round((ts - nbytes / (peaks["d2h_peak_gbps"] * 1e9)) / groups * 1e6, 1),
-            "retrieve_us_beyond_peak_per_group": round((tl - nbytes / (peaks["h2d_peak_gbps"] * 1e9)) / groups * 1e6, 1)}
+            "retrieve_us_beyond_peak_per_group": round((tl - nbytes / (peaks["h2d_peak_gbps"] * 1e9)) / groups * 1e6, 1),
+            "gap_between_consecutive_groups_copies_us": gaps}
     return res
 
 
