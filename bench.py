@@ -1094,6 +1094,16 @@ def main():
             ctx.wait(t1)
             ctx.wait(t2)
         t_both = timed(both, reps=4)
+
+        # the whole request stored and retrieved with no host wait in between: the retrieve
+        # follows the store group by group on the device, both directions of the link at work
+        def chained():
+            ctx.clear(ids)
+            t1 = ctx.store(src, d_store, ids, stream)
+            t2 = ctx.retrieve(ids, d_load, dst, stream)
+            ctx.wait(t1)
+            ctx.wait(t2)
+        t_chained = timed(chained, reps=4)
         # the same retrieve without the wait it leaves on the caller's stream (the caller
         # orders by lmc_wait, as this benchmark does anyway)
         ctx.tune("caller_waits", 0)
@@ -1109,6 +1119,9 @@ def main():
             "store_frac_of_d2h_peak": round(payload_one_way / t_store / 1e9 / peaks["d2h_peak_gbps"], 4),
             "retrieve_frac_of_h2d_peak": round(payload_one_way / t_load / 1e9 / peaks["h2d_peak_gbps"], 4),
             "retrieve_gbps_without_the_wait_on_the_callers_stream": round(payload_one_way / t_load_nw / 1e9, 2),
+            "retrieve_enqueued_right_behind_the_store_of_the_same_chunks": dict(
+                against_duplex_peak(2 * payload_one_way / t_chained / 1e9, peaks),
+                ms=round(t_chained * 1e3, 2), ms_store_wait_retrieve_wait=round((t_store + t_load) * 1e3, 2)),
             "half_stored_while_half_is_retrieved": against_duplex_peak(
                 (half + n_chunks - half) * g.chunk_bytes / t_both / 1e9, peaks),
         })

@@ -212,7 +212,10 @@ lmc_status_t lmc_lookup(lmc_ctx_t *ctx, const uint64_t *chunk_ids, int64_t n,
  * the slot mapping).
  * The call only enqueues; *ticket_out (HOST, may be NULL) names the work for lmc_wait.
  * A stored chunk is visible to lmc_lookup at once; a retrieve of it is ordered after
- * the store on the device.
+ * the store on the device, group by group: the copy of a chunk to the device waits for the
+ * copies of the store's group that holds the chunk, not for the whole store, so a retrieve
+ * enqueued right behind the store of the same chunks runs beside it (both directions of
+ * the link at work).
  * Errors: LMC_ERR_NOMEM when the pool fills: chunks before the failing one are stored
  * and their work is still covered by the ticket.  LMC_ERR_BADSLOT under
  * LMC_FLAG_VALIDATE_SLOTS (nothing stored).  LMC_ERR_NODEVICE.  LMC_ERR_HIP: the call

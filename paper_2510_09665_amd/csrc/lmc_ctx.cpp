@@ -126,7 +126,10 @@ void reap(lmc_ctx *c) {
         for (int64_t s : op.slots) {
             lmc::SlotMeta &m = c->index.meta(s);
             m.inflight--;
-            if (m.ready_ticket == op.ticket) m.ready_ticket = 0;
+            if (m.ready_ticket == op.ticket) {
+                m.ready_ticket = 0;
+                m.ready_event = nullptr;
+            }
         }
         c->ops.erase(c->ops.begin() + long(i));
     }

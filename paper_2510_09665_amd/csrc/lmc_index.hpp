@@ -93,6 +93,8 @@ struct SlotMeta {
     int32_t inflight = 0;      // enqueued transfers that read or write this slot
     int32_t refs = 0;          // readers that use the slot's bytes in place (lmc_chunk_acquire)
     uint64_t ready_ticket = 0; // the store whose D2H fills this slot (0 = already filled)
+    void *ready_event = nullptr;  // while ready_ticket != 0: the event (a hipEvent_t of that store) after
+                                  // which this slot's bytes are in the pool; null = the store's last event
     uint64_t use_call = 0;     // number of the last store / retrieve call that used the chunk
     int64_t older = -1, newer = -1;  // neighbours in the order of last use
     bool used = false;

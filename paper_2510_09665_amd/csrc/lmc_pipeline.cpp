@@ -297,24 +297,25 @@ static int64_t layer_group_chunks(const lmc_ctx *c, const Ring &r, const lmc::La
 }
 
 // A chunk whose store is still on its way to the pool must be loaded after that store:
-// the loading stream waits for every such store (stores end on different streams, the
+// the loading stream waits for the event behind the copies of the store's group that holds
+// the chunk (a staged bulk store records one per group, so that a retrieve issued right
+// behind a store of the same chunks follows it group by group, both directions of the
+// link at work), or else for the store's last event (stores end on different streams, the
 // D2H stream or, without staging, the gather stream, so the newest alone says nothing
 // about the others).  A layer-wise store that has not been submitted completely cannot
 // be waited for on the device: LMC_ERR_BUSY.
-static lmc_status_t after_stores(lmc_ctx *c, const std::vector<int64_t> &pool_slots, hipStream_t waiter) {
-    std::vector<uint64_t> tickets;
-    for (int64_t s : pool_slots) {
-        const uint64_t t = c->index.meta(s).ready_ticket;
-        if (t == 0 || (!tickets.empty() && tickets.back() == t)) continue;
-        const Op *o = find_op(c, t);
+static lmc_status_t after_stores(lmc_ctx *c, const int64_t *pool_slots, int64_t n, hipStream_t waiter) {
+    std::vector<hipEvent_t> events;
+    for (int64_t i = 0; i < n; i++) {
+        const lmc::SlotMeta &m = c->index.meta(pool_slots[i]);
+        if (m.ready_ticket == 0) continue;
+        const Op *o = find_op(c, m.ready_ticket);
         if (o == nullptr) continue;  // finished
         if (o->pending) return LMC_ERR_BUSY;
-        if (std::find(tickets.begin(), tickets.end(), t) == tickets.end()) tickets.push_back(t);
+        hipEvent_t e = m.ready_event != nullptr ? static_cast<hipEvent_t>(m.ready_event) : o->done;
+        if (e != nullptr && std::find(events.begin(), events.end(), e) == events.end()) events.push_back(e);
     }
-    for (uint64_t t : tickets) {
-        const Op *o = find_op(c, t);
-        if (o != nullptr && o->done != nullptr) HIPCHK(c, hipStreamWaitEvent(waiter, o->done, 0));
-    }
+    for (hipEvent_t e : events) HIPCHK(c, hipStreamWaitEvent(waiter, e, 0));
     return LMC_OK;
 }
 
@@ -347,8 +348,14 @@ static lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunk
 
     const bool direct = (c->cfg.flags & LMC_FLAG_DIRECT) != 0 ||
                         (layers_per_step == 0 && n_chunks * c->chunk_bytes <= c->direct_retrieve_below);
-    if ((rc = after_stores(c, pool_slots, direct ? c->s_scatter : c->s_h2d)) != LMC_OK) return rc;
-    if (!direct && (rc = after_stores(c, pool_slots, c->s_h2d2)) != LMC_OK) return rc;
+    // without staging the scatter stream waits for every store at once; with staging each
+    // group's copies wait for the stores of their own chunks (load_group)
+    if ((rc = after_stores(c, pool_slots.data(), direct ? n_chunks : 0, c->s_scatter)) != LMC_OK) return rc;
+    for (int64_t s : pool_slots) {
+        const uint64_t t = c->index.meta(s).ready_ticket;
+        const Op *o = t != 0 ? find_op(c, t) : nullptr;
+        if (o != nullptr && o->pending) return LMC_ERR_BUSY;    // before anything is enqueued
+    }
     begin_use(c, ids, n_chunks);   // a retrieve that is served is a use of its chunks
     end_use(c, ids, n_chunks);
     Op op;
@@ -385,6 +392,9 @@ static lmc_status_t do_retrieve(lmc_ctx *c, const uint64_t *ids, int64_t n_chunk
         uint8_t *buf;
         const size_t b = ring_next(ring, &buf);
         if (!several_runs(&pool_slots[size_t(i0)], k)) second = nullptr;
+        lmc_status_t ra = after_stores(c, &pool_slots[size_t(i0)], k, copy_stream);
+        if (ra == LMC_OK && second) ra = after_stores(c, &pool_slots[size_t(i0)], k, second);
+        if (ra != LMC_OK) return ra;
         if (ring.used[b]) {
             HIPCHK(c, hipStreamWaitEvent(copy_stream, ring.drained[b], 0));
             if (second) HIPCHK(c, hipStreamWaitEvent(second, ring.drained[b], 0));
@@ -502,6 +512,7 @@ static bool admit_new_chunks(lmc_ctx *c, const uint64_t *ids, int64_t n_chunks, 
         lmc::SlotMeta &m = c->index.meta(s);
         m.inflight = 1;
         m.ready_ticket = op->ticket;
+        m.ready_event = nullptr;
         new_chunk->push_back(i);
         op->slots.push_back(s);
     }
@@ -527,7 +538,8 @@ static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64
                                  const lmc::LayerPtrs &ptrs, const int64_t *slot_mapping,
                                  const std::vector<int64_t> &new_chunk,
                                  const std::vector<int64_t> &new_slot, int64_t cap_chunks,
-                                 bool edge_group, bool direct, bool layer_step = false, bool on_second_stream = false) {
+                                 bool edge_group, bool direct, bool layer_step = false, bool on_second_stream = false,
+                                 std::vector<hipEvent_t> *group_events = nullptr) {
     Ring &ring = c->store_ring;
     const int64_t CT = c->cfg.geom.chunk_tokens;
     if (direct) {
@@ -592,6 +604,15 @@ static lmc_status_t store_groups(lmc_ctx *c, const lmc::LaunchView &view, uint64
             HIPCHK(c, lmc::launch_fill(buf, 0xA5, uint64_t(k) * view.chunk_stride, copies));
         HIPCHK(c, hipEventRecord(ring.drained[b], copies));
         ring.used[b] = 1;
+        if (group_events != nullptr) {
+            // "these chunks are in the pool": an event of the group's own (drained[b] is recorded
+            // again whenever the buffer comes round), kept by the store until it is reaped
+            hipEvent_t in_pool;
+            if ((rc = get_event(c, false, &in_pool)) != LMC_OK) return rc;
+            group_events->push_back(in_pool);
+            HIPCHK(c, hipEventRecord(in_pool, copies));
+            for (size_t j = j0; j < j0 + k; j++) c->index.meta(new_slot[j]).ready_event = in_pool;
+        }
         if ((rc = force_sync(c, copies)) != LMC_OK) return rc;
         j0 += k;
     }
@@ -660,11 +681,12 @@ lmc_status_t lmc_store(lmc_ctx_t *c, void *const *kv_layers, const int64_t *slot
     rc = direct ? LMC_OK : ring_reslot(c, c->store_ring, c->store_ring.buf_bytes, c->s_gather, c->s_d2h, nullptr, c->s_d2h2);
     if (rc == LMC_OK)
         rc = store_groups(c, lmc::bulk_view(c->kg), 0, ptrs, slot_mapping, new_chunk, op.slots,
-                          c->cfg.staging_chunks, true, direct);
+                          c->cfg.staging_chunks, true, direct, false, false, &op.owned_events);
     if (rc == LMC_OK)
         rc = finish_op(c, std::move(op), direct ? c->s_gather : c->s_d2h, !new_chunk.empty(), ticket_out);
     if (rc != LMC_OK) {
         abort_store(c, op.slots);   // finish_op registers as its last step: op is still whole
+        for (hipEvent_t e : op.owned_events) recycle(c, e);
         return rc;
     }
     return fits ? LMC_OK : LMC_ERR_NOMEM;

@@ -327,3 +327,54 @@ def test_null_stream_as_the_callers_stream_covers_blocking_streams():
         torch.cuda.synchronize()
         del producer
         hip.hipStreamDestroy(raw)
+
+
+def test_retrieve_behind_a_store_of_the_same_chunks_follows_it_group_by_group():
+    """No host wait between the store of a request and its retrieve: each group's copy to the
+    device waits for the store groups that hold its chunks and for nothing more, so the
+    two directions overlap (seen in the trace) and the bytes are exact."""
+    import torch
+    from gpu_util import PagedKV, assert_layers_equal, slots_to_device
+    lmc = _lmc()
+    g = _geom()
+    n, per = 17, 2
+    rng = np.random.default_rng(83)
+    bpc = g.CT // g.BS
+    blocks = rng.permutation(g.NB)
+    src = PagedKV(g, blocks[:n * bpc], rng)
+    dst = PagedKV(g, blocks[n * bpc:2 * n * bpc], fill="sentinel")
+    ss = W.slots_from_blocks(g, src.blocks, n * g.CT)
+    ts = W.slots_from_blocks(g, dst.blocks, n * g.CT)
+    ids = np.arange(1, n + 1, dtype=np.uint64)
+    stream = torch.cuda.Stream()
+    with lmc.Context(g, n * g.chunk_bytes, staging_chunks=per, flags=lmc.LMC_FLAG_TRACE | lmc.LMC_FLAG_POISON_STAGING) as c:
+        for key in ("direct_store_below", "direct_retrieve_below"):
+            c.tune(key, 0)
+        d_ss, d_ts = slots_to_device(ss), slots_to_device(ts)
+        torch.cuda.synchronize()
+        t1 = c.store(src.dev, d_ss, ids, stream)
+        t2 = c.retrieve(ids, d_ts, dst.dev, stream)
+        c.wait(t1)
+        c.wait(t2)
+        recs, _ = c.trace_read()
+        d2h = [r for r in recs if r["stage"] == lmc.LMC_STAGE_D2H]
+        h2d = [r for r in recs if r["stage"] == lmc.LMC_STAGE_H2D]
+        assert [r["chunks"] for r in d2h] == [1] + [2] * 8 and [r["chunks"] for r in h2d] == [2] * 8 + [1]
+        # chunk ranges of the groups, in order
+        def ranges(rs):
+            out, a = [], 0
+            for r in rs:
+                out.append((a, a + r["chunks"], r))
+                a += r["chunks"]
+            return out
+        for a, b, r in ranges(h2d):
+            need = max(s["end_us"] for sa, sb, s in ranges(d2h) if sa < b and a < sb)
+            assert r["begin_us"] >= need - 1.0, "a group was loaded before its chunks were in the pool"
+        # and it did not wait for the whole store: the first load begins before the last store copy ends
+        assert h2d[0]["begin_us"] < d2h[-1]["begin_us"]
+        for i, sl in zip(ids.tolist(), src.compact_slots(ss).reshape(n, g.CT)):
+            assert np.array_equal(c.get_host(i), oracle.gather_chunk(src.gc, src.host, sl))
+        for sl, tl in zip(src.compact_slots(ss).reshape(n, g.CT), dst.compact_slots(ts).reshape(n, g.CT)):
+            oracle.scatter_chunk(dst.gc, oracle.gather_chunk(src.gc, src.host, sl), tl, dst.host)
+        assert_layers_equal(dst.device_blocks_to_host(), dst.host)
+        assert dst.untracked_blocks_untouched()
