@@ -336,18 +336,19 @@ static lmc_status_t sync_unlocked(lmc_ctx *c, std::unique_lock<std::mutex> &lock
     return LMC_OK;
 }
 
-// The store that fills the slot of chunk `id`, if it is still under way: its `done`
-// event goes to *ev (null = nothing to wait for).  LMC_ERR_MISS / LMC_ERR_BUSY as lmc_get_host.
+// The store that fills the slot of chunk `id`, if it is still under way: the event behind
+// the copies of the chunk's group, or else the store's last event, goes to *ev (null =
+// nothing to wait for).  LMC_ERR_MISS / LMC_ERR_BUSY as lmc_get_host.
 static lmc_status_t pending_fill(lmc_ctx *c, uint64_t id, int64_t *slot_out, hipEvent_t *ev) {
     *ev = nullptr;
     const int64_t s = c->index.find(id);
     if (s < 0) return LMC_ERR_MISS;
     *slot_out = s;
-    const uint64_t store_ticket = c->index.meta(s).ready_ticket;
-    if (store_ticket != 0) {
-        const Op *o = find_op(c, store_ticket);
+    const lmc::SlotMeta &m = c->index.meta(s);
+    if (m.ready_ticket != 0) {
+        const Op *o = find_op(c, m.ready_ticket);
         if (o != nullptr && o->pending) return LMC_ERR_BUSY;
-        if (o != nullptr) *ev = o->done;
+        if (o != nullptr) *ev = m.ready_event != nullptr ? static_cast<hipEvent_t>(m.ready_event) : o->done;
     }
     return LMC_OK;
 }
