@@ -378,3 +378,27 @@ def test_retrieve_behind_a_store_of_the_same_chunks_follows_it_group_by_group():
             oracle.scatter_chunk(dst.gc, oracle.gather_chunk(src.gc, src.host, sl), tl, dst.host)
         assert_layers_equal(dst.device_blocks_to_host(), dst.host)
         assert dst.untracked_blocks_untouched()
+
+
+def test_host_reads_of_a_store_under_way_are_exact_chunk_by_chunk():
+    """lmc_get_host behind an unfinished store waits for the group of copies that brings in
+    the chunk it asks for; every chunk read that way, in order, with no lmc_wait, is exact."""
+    import torch
+    from gpu_util import PagedKV, slots_to_device
+    lmc = _lmc()
+    g = _geom()
+    n = 17
+    rng = np.random.default_rng(84)
+    bpc = g.CT // g.BS
+    src = PagedKV(g, rng.permutation(g.NB)[:n * bpc], rng)
+    ss = W.slots_from_blocks(g, src.blocks, n * g.CT)
+    ids = np.arange(1, n + 1, dtype=np.uint64)
+    stream = torch.cuda.Stream()
+    with lmc.Context(g, n * g.chunk_bytes, staging_chunks=2, flags=lmc.LMC_FLAG_POISON_STAGING) as c:
+        c.tune("direct_store_below", 0)
+        d_ss = slots_to_device(ss)
+        torch.cuda.synchronize()
+        t = c.store(src.dev, d_ss, ids, stream)
+        for i, sl in zip(ids.tolist(), src.compact_slots(ss).reshape(n, g.CT)):
+            assert np.array_equal(c.get_host(i), oracle.gather_chunk(src.gc, src.host, sl)), "chunk %d" % i
+        c.wait(t)
