@@ -866,6 +866,43 @@ def trace_leg(lmc, ctx, g, src, dst, d_store, d_load, ids, stream, payload_one_w
     return res
 
 
+def host_leg(torch, ctx, seq, src, dst, d_store, d_load, ids, stream, n_chunks):
+    """The host side of the path (token processor, index, pool bookkeeping; rows a1-a3 and
+    a10 of the hot-path table) and what the two enqueue calls cost the calling thread,
+    on the headline request: microseconds, best of several."""
+    def best(fn, reps=20):
+        b = 1e30
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            fn()
+            b = min(b, time.perf_counter() - t0)
+        return round(b * 1e6, 1)
+    res = {"tokens": int(seq["tokens"].size), "chunks": n_chunks}
+    res["hash_chunks_us"] = best(lambda: ctx.hash_chunks(seq["tokens"]))
+    ctx.clear(ids)
+    res["lookup_all_missing_us"] = best(lambda: ctx.lookup(ids))
+    enq_s, enq_l = [], []
+    for _ in range(4):
+        ctx.clear(ids)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        t = ctx.store(src, d_store, ids, stream)
+        enq_s.append(time.perf_counter() - t0)
+        ctx.wait(t)
+        t0 = time.perf_counter()
+        t = ctx.retrieve(ids, d_load, dst, stream)
+        enq_l.append(time.perf_counter() - t0)
+        ctx.wait(t)
+    res["store_call_returns_after_us"] = round(min(enq_s) * 1e6, 1)
+    res["retrieve_call_returns_after_us"] = round(min(enq_l) * 1e6, 1)
+    res["lookup_all_present_us"] = best(lambda: ctx.lookup(ids))
+    res["pin_then_unpin_us"] = best(lambda: (ctx.pin(ids), ctx.unpin(ids)))
+    t0 = time.perf_counter()
+    ctx.clear(ids)
+    res["clear_us"] = round((time.perf_counter() - t0) * 1e6, 1)
+    return res
+
+
 def small_leg(torch, lmc, W, dev, stream, timed):
     """One chunk of half a MiB (configuration 1): microseconds from the call to a finished
     lmc_wait, through the staging ring and by the library's size rule (no staging)."""
@@ -905,7 +942,7 @@ def main():
                     help="steps measured right after set-up, before anything settles (0 = none)")
     ap.add_argument("--settle-seconds", type=float, default=20.0,
                     help="upper limit for the untimed settling phase before the warm-up (0 = none)")
-    ap.add_argument("--legs", default="pipeline,link,device,trace,groups,configs,placement,duplex,direct,layerwise,overlap,"
+    ap.add_argument("--legs", default="pipeline,link,device,host,trace,groups,configs,placement,duplex,direct,layerwise,overlap,"
                                       "fragmented,small,cpu",
                     help="comma list of pipeline (always run), link, device, groups, configs, placement, duplex, direct, "
                          "layerwise, overlap, fragmented, small, cpu: the extra measurements to make; "
@@ -1165,6 +1202,8 @@ def main():
         else:
             out[key] = val
 
+    if "host" in legs:
+        leg("host_side", lambda: host_leg(torch, ctx, seq, src, dst, d_store, d_load, ids, stream, n_chunks))
     if "trace" in legs:
         leg("trace", lambda: trace_leg(lmc, ctx, g, src, dst, d_store, d_load, ids, stream, payload_one_way))
     if "groups" in legs:
