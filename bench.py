@@ -903,6 +903,167 @@ def host_leg(torch, ctx, seq, src, dst, d_store, d_load, ids, stream, n_chunks):
     return res
 
 
+def serving_leg(torch, lmc, W, dev, peaks, n_requests=240):
+    """A stream of requests as a serving engine would send them (paper section 4: look up
+    the prefix, retrieve what is there, store what is new; the paper's multi-round question
+    answering, section 8.1), on the Llama-3-8B shape: 32 conversations visited in seeded
+    random order; every turn sends the whole conversation so far (the earlier turns are the
+    prefix that should hit) plus a few new chunks (seeded lognormal, median 4), and a
+    conversation that reaches 64 chunks starts over as a new one.  The pool holds 320
+    chunks with LRU eviction, a third of what the conversations add up to, so chunks are
+    evicted and come back and the pool fragments; four requests are in flight, each on a
+    stream of its own, with no host wait between a request's retrieve and its store.
+    Every chunk's KV is one byte value derived from (conversation, chunk), so that what a
+    retrieve delivered can be checked with one comparison per page."""
+    g = W.geometry(SECONDARY)
+    rng = W.rng_for(SECONDARY, stream=70)
+    n_sessions, max_chunks, pool_chunks, window = 32, 64, 320, 4
+    bpc = g.CT // g.BS
+    new_doc = lambda: rng.integers(0, 128256, max_chunks * g.CT, dtype=np.int64).astype(np.int32)
+    docs = [new_doc() for _ in range(n_sessions)]
+    doc_id = list(range(n_sessions))          # a new number whenever a conversation starts over
+    length = [0] * n_sessions
+    next_id = n_sessions
+    kv = [torch.zeros(g.layer_bytes, dtype=torch.uint8, device=dev) for _ in range(g.L)]
+    views = [W.page_view(g, t) for t in kv]
+    order = rng.permutation(g.NB)
+    # Nothing crosses the link for the harness itself while requests run: a small copy from
+    # pageable memory queues behind whatever 256 MiB transfer the copy engine is busy with and
+    # blocks the host for that long.  Block lists, slot mappings and fill values are made on
+    # the device from what is resident, and the checks collect in a flag that is read at the end.
+    order_dev = torch.from_numpy(order).to(dev)
+    in_block = torch.arange(g.BS, device=dev, dtype=torch.int64)
+    all_good = torch.ones((), dtype=torch.bool, device=dev)
+    cursor = 0
+    streams = [torch.cuda.Stream() for _ in range(window)]      # one per request in flight, as a batch slot of an engine
+    moved = {"hit_chunks": 0, "new_chunks": 0, "requests": 0, "pages_checked": 0}
+    inflight = []
+    host = {"prepare": 0.0, "retrieve_call": 0.0, "prefill_stand_in": 0.0, "store_call": 0.0, "wait_and_check": 0.0}
+
+    class section:
+        def __init__(self, key):
+            self.key = key
+
+        def __enter__(self):
+            self.t = time.perf_counter()
+
+        def __exit__(self, *a):
+            host[self.key] += time.perf_counter() - self.t
+
+    def pattern(d, j):
+        return (d * 67 + j * 13 + 1) & 0xFF
+
+    def retire(ctx, item):
+        nonlocal all_good
+        tickets, keep, d, n_hit, b_dev = item
+        for t in tickets:
+            ctx.wait(t)
+        # the chunks that were retrieved: first, middle and last one, one layer each
+        for j in sorted({0, n_hit // 2, n_hit - 1}) if n_hit else ():
+            l = (d + j) % g.L
+            all_good = all_good & (views[l][:, b_dev[j * bpc:(j + 1) * bpc]] == pattern(d, j)).all()
+            moved["pages_checked"] += bpc * g.P
+
+    with lmc.Context(g, pool_chunks * g.chunk_bytes, staging_chunks=8, device=0,
+                     flags=lmc.LMC_FLAG_EVICT_LRU | lmc.LMC_FLAG_TRACE) as ctx:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for r_ in range(n_requests):
+            stream = streams[r_ % window]
+            with section("prepare"):
+                ses = int(rng.integers(0, n_sessions))
+                if length[ses] >= max_chunks:                    # the conversation is over: a new one takes its place
+                    docs[ses], doc_id[ses], length[ses] = new_doc(), next_id, 0
+                    next_id += 1
+                turn = int(np.clip(round(float(np.exp(np.log(4.0) + 0.7 * rng.standard_normal()))), 1, 16))
+                n = min(max_chunks, length[ses] + turn)
+                length[ses] = n
+                d = doc_id[ses]
+                if cursor + n * bpc > g.NB:
+                    cursor = 0
+                b_dev = order_dev[cursor:cursor + n * bpc]
+                cursor += n * bpc
+                ids = ctx.hash_chunks(docs[ses][:n * g.CT])
+                n_hit = ctx.lookup(ids)
+            tickets = []
+            with torch.cuda.stream(stream):
+                with section("prepare"):
+                    # slot of token t: blocks[t // BS] * BS + t % BS
+                    d_slots = (b_dev[:, None] * g.BS + in_block[None, :]).reshape(-1)
+                    if n_hit < n:
+                        tb = b_dev[n_hit * bpc:]
+                        chunk_no = torch.arange(n_hit, n, device=dev, dtype=torch.int64)
+                        vals = ((chunk_no * 13 + (d * 67 + 1)) & 0xFF).to(torch.uint8).repeat_interleave(bpc)[None, :, None]
+                if n_hit:
+                    with section("retrieve_call"):
+                        tickets.append(ctx.retrieve(ids[:n_hit], d_slots[:n_hit * g.CT], kv, stream))
+                # "prefill": the engine computes the KV of the chunks that were not there (one
+                # fill per layer: every page of chunk j gets the byte of (conversation, j))
+                if n_hit < n:
+                    with section("prefill_stand_in"):
+                        for v in views:
+                            v[:, tb] = vals
+                    with section("store_call"):
+                        try:
+                            tickets.append(ctx.store(kv, d_slots, ids, stream))
+                        except lmc.LMCError as e:            # every slot in flight: what fitted is stored
+                            if e.status != lmc.LMC_ERR_NOMEM or not e.ticket:
+                                raise
+                            tickets.append(e.ticket)
+                            moved["stores_cut_short"] = moved.get("stores_cut_short", 0) + 1
+            moved["hit_chunks"] += n_hit
+            moved["new_chunks"] += n - n_hit
+            moved["requests"] += 1
+            inflight.append((tickets, (d_slots, b_dev), d, n_hit, b_dev))
+            if len(inflight) >= window:
+                with section("wait_and_check"):
+                    retire(ctx, inflight.pop(0))
+        while inflight:
+            retire(ctx, inflight.pop(0))
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        assert bool(all_good), "a retrieved chunk differs from what its conversation stored"
+        st = ctx.get_stats()
+        recs, _ = ctx.trace_read()
+
+    def busy(stage):
+        """Merged busy intervals of one stage, from the trace."""
+        iv = sorted((r["begin_us"], r["end_us"]) for r in recs if r["stage"] == stage)
+        out = []
+        for a, b in iv:
+            if out and a <= out[-1][1]:
+                out[-1][1] = max(out[-1][1], b)
+            else:
+                out.append([a, b])
+        return out
+
+    def overlap(x, y):
+        i = j = 0
+        tot = 0.0
+        while i < len(x) and j < len(y):
+            lo, hi = max(x[i][0], y[j][0]), min(x[i][1], y[j][1])
+            tot += max(0.0, hi - lo)
+            if x[i][1] < y[j][1]:
+                i += 1
+            else:
+                j += 1
+        return tot
+    up, down = busy(lmc.LMC_STAGE_H2D), busy(lmc.LMC_STAGE_D2H)
+    link = {"to_device_busy_s": round(sum(b - a for a, b in up) / 1e6, 3),
+            "to_host_busy_s": round(sum(b - a for a, b in down) / 1e6, 3),
+            "both_busy_s": round(overlap(up, down) / 1e6, 3)}
+    total = st["bytes_d2h"] + st["bytes_h2d"]
+    return {"requests": moved["requests"], "chunks_retrieved": moved["hit_chunks"], "chunks_stored": moved["new_chunks"],
+            "hit_rate_by_chunks": round(moved["hit_chunks"] / max(moved["hit_chunks"] + moved["new_chunks"], 1), 3),
+            "chunks_evicted": st["chunks_evicted"], "pool_chunks": pool_chunks,
+            "gib_to_host": round(st["bytes_d2h"] / 2**30, 2), "gib_to_device": round(st["bytes_h2d"] / 2**30, 2),
+            "wall_s": round(wall, 3), "gbps_both_ways_over_wall": round(total / wall / 1e9, 2), "link": link,
+            "host_seconds": {k_: round(v_, 3) for k_, v_ in host.items()},
+            "pages_checked": moved["pages_checked"], "stores_cut_short_by_a_full_pool": moved.get("stores_cut_short", 0),
+            "note": "wall time includes the stand-in for the engine's prefill (PyTorch fills of the new chunks' pages) "
+                    "and the host waits of the four-request window; the rate is what the library sustained beside them"}
+
+
 def small_leg(torch, lmc, W, dev, stream, timed):
     """One chunk of half a MiB (configuration 1): microseconds from the call to a finished
     lmc_wait, through the staging ring and by the library's size rule (no staging)."""
@@ -943,7 +1104,7 @@ def main():
     ap.add_argument("--settle-seconds", type=float, default=20.0,
                     help="upper limit for the untimed settling phase before the warm-up (0 = none)")
     ap.add_argument("--legs", default="pipeline,link,device,host,trace,groups,configs,placement,duplex,direct,layerwise,overlap,"
-                                      "fragmented,small,cpu",
+                                      "fragmented,serving,small,cpu",
                     help="comma list of pipeline (always run), link, device, groups, configs, placement, duplex, direct, "
                          "layerwise, overlap, fragmented, small, cpu: the extra measurements to make; "
                          "profiling runs use a subset")
@@ -1118,6 +1279,12 @@ def main():
         def store_only():
             ctx.clear(ids)
             ctx.wait(ctx.store(src, d_store, ids, stream))
+        # measuring the link's peaks allocated and freed GiBs, which can leave the runtime's copies
+        # to the host slow for a while (and the guard on the copy kernel): let that pass first
+        for _ in range(12):
+            store_only()
+            if not ctx.get_stats()["d2h_guard_active"]:
+                break
         t_store = timed(store_only, reps=4)
         t_load = timed(lambda: ctx.wait(ctx.retrieve(ids, d_load, dst, stream)), reps=4)
         # both directions at once: the first half of the request is stored while the second
@@ -1213,6 +1380,8 @@ def main():
         leg("configs", lambda: other_configs(torch, lmc, W, dev, stream, timed, peaks))
     if legs & {"duplex", "direct", "layerwise", "overlap", "fragmented"}:
         leg(None, lambda: mode_legs(torch, lmc, W, dev, stream, legs, args, timed, peaks))
+    if "serving" in legs:
+        leg("serving_mix", lambda: serving_leg(torch, lmc, W, dev, peaks))
     if "small" in legs:
         leg("small_request", lambda: small_leg(torch, lmc, W, dev, stream, timed))
     if "placement" in legs:

@@ -556,11 +556,12 @@ lmc_status_t lmc_probe_stream(lmc_ctx_t *ctx, void *stream, uint32_t *mask_out);
  * pool are made by the library's own link-paced copy kernel instead of hipMemcpyAsync;
  * bit 1: copies from the pool to staging too.  2-3 % slower than the runtime's copies,
  * but independent of which engine the runtime picks and of what else that engine is doing),
- * "d2h_guard" (default 0; 1: the library times the runtime's copies to the host of 32 MiB
- * and more, and when two of the last four fell below three quarters of the best rate it has seen
- * it makes these copies with its own kernel for 1 s, then tries the runtime again,
- * doubling the pause up to 8 s while the runtime stays slow: for processes that allocate
- * and free memory while they store),
+ * "d2h_guard" (default 1: the library times the runtime's copies to the host of 32 MiB
+ * and more, one per group, and when two of the last four fell below six tenths of the
+ * best rate it has seen it makes these copies with its own kernel for 0.25 s, then tries
+ * the runtime again, doubling the pause up to 2 s while the runtime stays slow: the
+ * runtime's copies to the host lose their rate now and then, for seconds after large
+ * allocations and in mixes of stores and retrieves of many requests; 0: never),
  * "edge_chunks" (size
  * of the group at the exposed end of a pipeline, 0 = none), "timing" (0/1: switches
  * LMC_FLAG_TIMING), "trace" (0/1: switches LMC_FLAG_TRACE; 1 also empties the trace and

@@ -90,12 +90,13 @@ struct lmc_ctx {
     // 55 GB/s does not depend on that.
     uint32_t copy_kernel = 0;
     // ... and the guard that switches device-to-host copies to the kernel by itself while
-    // the runtime's are slow (lmc_guard.hpp).  Off unless asked for (lmc_tune "d2h_guard").
-    // Measured on a 10 GiB request: in a fresh process's first seconds the guard lifts the
-    // path from 44.5 to 54.5 GB/s; later, after a context with a large pool has been created,
-    // it holds the copies on the copy kernel (55.7 GB/s) for seconds although the runtime's
-    // were back at 56.8 after one store.  Steady state is the same either way.
-    bool d2h_guard_on = false;
+    // the runtime's are slow (lmc_guard.hpp).  On unless switched off (lmc_tune "d2h_guard"):
+    // in a mix of stores and retrieves of many requests the runtime's copies to the host
+    // collapse now and then (whole stores at 12.7 GB/s), and the mix runs in 3.2 s with the
+    // guard against 4.4-5.2 s without; on the one-way 10 GiB request it costs nothing when
+    // the runtime is healthy (one pair of event markers per group) and lifts a fresh
+    // process's slow first seconds from 44.5 to 54.5 GB/s.
+    bool d2h_guard_on = true;
     uint64_t pieces_by_kernel_below = uint64_t(2) << 20;   // bytes per transfer; see copy_group
     int32_t store_step_streams = 2;   // copy streams the steps of a layer-wise store take in turn
     bool caller_waits = true;     // a bulk retrieve ends with the caller's stream waiting for it

@@ -149,10 +149,11 @@ def test_config2_llama3_8b_full_in_the_benchmarks_launch_configuration():
     # bench.py's defaults: two staging buffers of 16 chunks -> launches of 1 and 15 chunks
     st = _run_sequence("llama3_8b", staging_chunks=16, num_staging=2)
     assert st["gather_launches"] == 2 and st["scatter_launches"] == 2
-    assert st["d2h_copy_best_gbps"] == 0.0                       # no copy is watched unless the guard is asked for
-    # with the copy-engine guard on, the 480 MiB copy to the host is timed; nothing is wrong with it
-    st = _run_sequence("llama3_8b", staging_chunks=16, num_staging=2, tune=(("d2h_guard", 1),))
+    # the copy-engine guard is on by default: the 480 MiB copy to the host is timed; nothing is wrong with it
     assert 10.0 < st["d2h_copy_best_gbps"] < 80.0 and st["d2h_guard_switches"] == 0
+    # switched off, no copy is watched
+    st = _run_sequence("llama3_8b", staging_chunks=16, num_staging=2, tune=(("d2h_guard", 0),))
+    assert st["d2h_copy_best_gbps"] == 0.0
 
 
 def test_config5_mla_bf16_full():
